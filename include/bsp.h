@@ -1,0 +1,170 @@
+/*
+ * bsp — block-sparse convolution / fully-connected inference for AMD MI355X
+ * (gfx950).  C ABI of libbsp.so.
+ *
+ * Notation follows the paper (Section I): a layer computes Y = W * X + b with
+ * Y of size M x N x O, X of size L x J x I, W of size O x H x K x I and b of
+ * size O.  W-bar[o][i] = W[o][*][*][i] is the O x I matrix whose entries hide
+ * the H x K kernel window; the mask Gamma has one entry per b_o x b_i block of
+ * W-bar (Eq. (1)) and a zero entry means the whole b_o x H x K x b_i
+ * sub-tensor is zero.  A leading batch dimension B is added to X and Y.
+ *
+ * Layouts (row-major, last index fastest):
+ *   X        [B][L][J][I]          input channel innermost
+ *   Y        [B][M][N][O]          M = (L + 2*pad_h - H)/stride_h + 1 (floor), N alike
+ *   W        [O][H][K][I]          the layout the paper's compiler uses (Section V)
+ *   Gamma    [ceil(O/b_o)][ceil(I/b_i)]  one byte per block, 1 = kept, 0 = zeroed
+ *   bias     [O] float
+ *
+ * Block-compressed weights (compressed block row, Section III):
+ *   row_ptr  [ceil(O/b_o)+1] int32   exclusive prefix sums of kept blocks per block row
+ *   col_idx  [nnzb] int32            kept block columns of each row, ascending
+ *   payload  [nnzb][b_o][H][K][b_i]  the kept blocks, fp32 or bf16; where a block
+ *                                    overhangs O or I the missing entries are +0
+ * For given (W, Gamma) these three arrays are unique, so they are compared
+ * bit for bit.
+ *
+ * Every function returns an int: BSP_OK or a negative bsp_status.  Nothing
+ * aborts, throws or prints.  The library allocates no device memory and keeps
+ * no global state; every buffer belongs to the caller.
+ */
+#ifndef BSP_H
+#define BSP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum bsp_status {
+  BSP_OK = 0,
+  BSP_ERR_NULL = -1,        /* a required pointer is null */
+  BSP_ERR_SHAPE = -2,       /* a size is non-positive, inconsistent, or the output is empty */
+  BSP_ERR_MASK = -3,        /* a Gamma byte is neither 0 nor 1 */
+  BSP_ERR_INDEX = -4,       /* row_ptr not monotone / col_idx not ascending or out of range */
+  BSP_ERR_DTYPE = -5,       /* unknown element type, or a combination not offered */
+  BSP_ERR_UNSUPPORTED = -6, /* block granularity outside {8x8, 4x16, 16x4} */
+  BSP_ERR_CAPACITY = -7,    /* an output buffer is too small */
+  BSP_ERR_HIP = -8,         /* the HIP runtime reported an error at launch */
+  BSP_ERR_ALIGN = -9        /* a device pointer is not 16-byte aligned */
+};
+
+enum bsp_dtype { BSP_F32 = 0, BSP_BF16 = 1 };
+
+/* Static, never-null description of a status code. */
+const char* bsp_strerror(int code);
+
+/* ABI revision of this header. */
+int bsp_version(void);
+
+/* ------------------------------------------------------------------ host side
+ * The packer: Gamma + dense W -> block-compressed weights.  Paper Section II
+ * ("the zeros are shuffled in ... we shall compact the blocks"), Section III
+ * (compressed block row / index storage of Gamma) and Section V-B (weights are
+ * compressed so that every move is a whole number of blocks, dense or sparse
+ * alike).  All pointers are HOST memory.
+ */
+
+/* Number of kept blocks, so the caller can size col_idx and payload.
+ * gamma: [ceil(O/bo)][ceil(I/bi)] bytes.  Errors: NULL, SHAPE, UNSUPPORTED, MASK. */
+int bsp_pack_count(const uint8_t* gamma, int32_t O, int32_t I, int32_t bo, int32_t bi,
+                   int64_t* nnzb);
+
+/* Build row_ptr / col_idx / payload.
+ *   W               dense weights [O][H][K][I], element type w_dtype (BSP_F32, or
+ *                   BSP_BF16 as raw 16-bit patterns)
+ *   payload_dtype   BSP_F32 or BSP_BF16.  fp32 -> bf16 rounds to nearest, ties to
+ *                   even; bf16 -> fp32 widens exactly.
+ *   row_ptr         out, ceil(O/bo)+1 entries
+ *   col_idx         out, nnzb entries
+ *   payload         out, nnzb*bo*H*K*bi elements of payload_dtype
+ *   payload_capacity_bytes / col_capacity   sizes of the two out buffers
+ * Structure follows Gamma only: a kept block of zeros is stored, a zeroed
+ * block is dropped whatever W holds there.
+ * Errors: NULL, SHAPE, UNSUPPORTED, MASK, DTYPE, CAPACITY. */
+int bsp_pack(const void* W, int32_t w_dtype, const uint8_t* gamma,
+             int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo, int32_t bi,
+             int32_t payload_dtype,
+             int32_t* row_ptr, int32_t* col_idx, int64_t col_capacity,
+             void* payload, int64_t payload_capacity_bytes);
+
+/* Inverse of bsp_pack onto a dense [O][H][K][I] tensor of element type
+ * w_dtype == payload_dtype (zeroed blocks become +0).  Validates the index
+ * arrays first.  Errors: NULL, SHAPE, UNSUPPORTED, DTYPE, INDEX. */
+int bsp_unpack(const int32_t* row_ptr, const int32_t* col_idx, const void* payload,
+               int32_t payload_dtype,
+               int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo, int32_t bi,
+               void* W);
+
+/* Check row_ptr / col_idx: row_ptr[0] == 0, non-decreasing, col_idx strictly
+ * ascending inside each row and < ceil(I/bi).  Errors: NULL, SHAPE,
+ * UNSUPPORTED, INDEX. */
+int bsp_validate(const int32_t* row_ptr, const int32_t* col_idx,
+                 int32_t O, int32_t I, int32_t bo, int32_t bi);
+
+/* Launch plan.  The kernels walk strips of 16 output channels; for each strip
+ * the plan lists which 8-wide groups of input channels carry at least one kept
+ * block and where in `payload` each kept block of the strip starts.  It is
+ * derived from row_ptr / col_idx alone (weights are prepared once, ahead of
+ * inference: Section V), holds offsets only (position independent), and is
+ * private to this library version: build it, copy the bytes to the device,
+ * pass the device pointer in bsp_weights.plan.
+ * bsp_plan_size  -> bytes needed.   bsp_plan_build -> fills `plan`.
+ * Errors: NULL, SHAPE, UNSUPPORTED, INDEX, CAPACITY. */
+int bsp_plan_size(const int32_t* row_ptr, const int32_t* col_idx,
+                  int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo, int32_t bi,
+                  int64_t* bytes);
+int bsp_plan_build(const int32_t* row_ptr, const int32_t* col_idx,
+                   int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo, int32_t bi,
+                   void* plan, int64_t capacity_bytes);
+
+/* ---------------------------------------------------------------- device side
+ * Block-compressed weights as the kernels see them.  The caller fills the
+ * struct (host memory) with DEVICE pointers; all of them 16-byte aligned.
+ */
+typedef struct bsp_weights {
+  int32_t O, I, H, K;       /* layer shape (H = K = 1 for a fully-connected layer) */
+  int32_t bo, bi;           /* block granularity: 8x8, 4x16 or 16x4 */
+  int32_t dtype;            /* element type of payload, X and Y: BSP_F32 or BSP_BF16 */
+  int32_t reserved;         /* set to 0 */
+  int64_t nnzb;             /* kept blocks */
+  const int32_t* row_ptr;   /* device, may be null (not read by the kernels) */
+  const int32_t* col_idx;   /* device, may be null (not read by the kernels) */
+  const void* payload;      /* device [nnzb][bo][H][K][bi] */
+  const void* plan;         /* device copy of bsp_plan_build's output */
+  int64_t plan_bytes;
+} bsp_weights;
+
+/* Fully-connected layer Y[B][O] = X[B][I] . (Gamma W-bar)^T + bias, work done
+ * for kept blocks only.  Paper Section III: a GEMM is handled as a 1x1
+ * convolution; Section I, advantages 3-4: zero blocks are skipped and the
+ * operation count is proportional to the kept blocks.
+ *   X, Y     device, element type w->dtype; bias device float[O] or null (no bias)
+ *   stream   a hipStream_t passed as void* (null = default stream)
+ * Accumulation is fp32; bias is added in fp32; the result is rounded once
+ * (nearest-even) to w->dtype.  Asynchronous: returns after the launch.
+ * Errors: NULL, SHAPE, UNSUPPORTED, DTYPE, ALIGN, HIP. */
+int bsp_fc(const bsp_weights* w, const void* X, const float* bias, void* Y,
+           int32_t B, void* stream);
+
+/* Convolution Y[B][M][N][O] = (Gamma W) * X[B][L][J][I] + bias (Section I),
+ * cross-correlation with zero padding, work done for kept blocks only.
+ * Dilation and groups are not expressible.  Same types, rounding, stream and
+ * error conventions as bsp_fc; SHAPE if M or N would be < 1. */
+int bsp_conv2d(const bsp_weights* w, const void* X, const float* bias, void* Y,
+               int32_t B, int32_t L, int32_t J,
+               int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+               void* stream);
+
+/* Same layer, but always through the general-shape kernel (no shape-specialised
+ * fast path).  For testing and for timing the dispatcher's choice. */
+int bsp_conv2d_general(const bsp_weights* w, const void* X, const float* bias, void* Y,
+                       int32_t B, int32_t L, int32_t J,
+                       int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                       void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BSP_H */

@@ -1,0 +1,26 @@
+"""Block-sparse convolution / fully-connected inference for AMD MI355X.
+
+A thin binding over libbsp.so (C ABI in include/bsp.h): argument marshalling
+only.  There is no CPU or PyTorch fallback: importing the device entry points
+without the built library raises.
+"""
+from .binding import (  # noqa: F401
+    BSP_BF16,
+    BSP_F32,
+    BspError,
+    BspLayer,
+    bsp_conv2d,
+    bsp_conv2d_general,
+    bsp_fc,
+    bsp_pack,
+    bsp_pack_count,
+    bsp_plan_build,
+    bsp_plan_size,
+    bsp_strerror,
+    bsp_unpack,
+    bsp_validate,
+    bsp_version,
+    bsp_weights,
+    lib_path,
+    load_library,
+)

@@ -1,0 +1,267 @@
+"""ctypes binding of libbsp.so: same names as the C ABI, marshalling only.
+
+Host functions take and return numpy arrays.  Device functions take raw
+device addresses (ints) plus a ``bsp_weights`` struct; ``BspLayer`` is a small
+convenience holder that packs a layer on the host, uploads the arrays with
+torch (used for device memory and streams only) and fills the struct.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+
+BSP_F32 = 0
+BSP_BF16 = 1
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libbsp.so")
+_lib = None
+
+EXPORTS = ("bsp_strerror", "bsp_version", "bsp_pack_count", "bsp_pack", "bsp_unpack",
+           "bsp_validate", "bsp_plan_size", "bsp_plan_build", "bsp_fc", "bsp_conv2d",
+           "bsp_conv2d_general")
+
+
+class BspError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {bsp_strerror(code)} ({code})")
+
+
+class bsp_weights(ctypes.Structure):
+    _fields_ = [("O", ctypes.c_int32), ("I", ctypes.c_int32), ("H", ctypes.c_int32),
+                ("K", ctypes.c_int32), ("bo", ctypes.c_int32), ("bi", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("nnzb", ctypes.c_int64), ("row_ptr", ctypes.c_void_p),
+                ("col_idx", ctypes.c_void_p), ("payload", ctypes.c_void_p),
+                ("plan", ctypes.c_void_p), ("plan_bytes", ctypes.c_int64)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libbsp.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it with "
+            "`python -m paper_2407_09453_amd.build` (hipcc, gfx950)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+    lib.bsp_strerror.restype = ctypes.c_char_p
+    lib.bsp_strerror.argtypes = [ctypes.c_int]
+    lib.bsp_version.restype = ctypes.c_int
+    lib.bsp_version.argtypes = []
+    lib.bsp_pack_count.restype = ctypes.c_int
+    lib.bsp_pack_count.argtypes = [vp, i32, i32, i32, i32, ctypes.POINTER(i64)]
+    lib.bsp_pack.restype = ctypes.c_int
+    lib.bsp_pack.argtypes = [vp, i32, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, i64, vp, i64]
+    lib.bsp_unpack.restype = ctypes.c_int
+    lib.bsp_unpack.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]
+    lib.bsp_validate.restype = ctypes.c_int
+    lib.bsp_validate.argtypes = [vp, vp, i32, i32, i32, i32]
+    lib.bsp_plan_size.restype = ctypes.c_int
+    lib.bsp_plan_size.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, ctypes.POINTER(i64)]
+    lib.bsp_plan_build.restype = ctypes.c_int
+    lib.bsp_plan_build.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, i64]
+    wp = ctypes.POINTER(bsp_weights)
+    lib.bsp_fc.restype = ctypes.c_int
+    lib.bsp_fc.argtypes = [wp, vp, vp, vp, i32, vp]
+    for name in ("bsp_conv2d", "bsp_conv2d_general"):
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = [wp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise BspError(rc, where)
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data
+
+
+def _np_dtype(code: int):
+    if code == BSP_F32:
+        return np.float32
+    if code == BSP_BF16:
+        return np.uint16
+    raise BspError(-5, "dtype")
+
+
+# ------------------------------------------------------------------- host side
+def bsp_strerror(code: int) -> str:
+    return load_library().bsp_strerror(int(code)).decode()
+
+
+def bsp_version() -> int:
+    return load_library().bsp_version()
+
+
+def bsp_pack_count(gamma: np.ndarray, O: int, I: int, bo: int, bi: int) -> int:
+    g = np.ascontiguousarray(gamma, dtype=np.uint8)
+    n = ctypes.c_int64(0)
+    _check(load_library().bsp_pack_count(_np_ptr(g), O, I, bo, bi, ctypes.byref(n)),
+           "bsp_pack_count")
+    return n.value
+
+
+def bsp_pack(W: np.ndarray, gamma: np.ndarray, bo: int, bi: int,
+             payload_dtype: int = BSP_F32, w_dtype: Optional[int] = None
+             ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """(row_ptr, col_idx, payload[nnzb][bo][H][K][bi]).  ``W`` is float32, or
+    uint16 holding bf16 bit patterns."""
+    if w_dtype is None:
+        w_dtype = BSP_BF16 if W.dtype == np.uint16 else BSP_F32
+    W = np.ascontiguousarray(W, dtype=_np_dtype(w_dtype))
+    O, H, K, I = W.shape
+    g = np.ascontiguousarray(gamma, dtype=np.uint8)
+    nbr, nbc = -(-O // bo), -(-I // bi)
+    if g.size != nbr * nbc:
+        raise BspError(-2, "bsp_pack (mask size)")
+    nnzb = bsp_pack_count(g, O, I, bo, bi)
+    row_ptr = np.zeros(nbr + 1, dtype=np.int32)
+    col_idx = np.zeros(nnzb, dtype=np.int32)
+    payload = np.zeros((nnzb, bo, H, K, bi), dtype=_np_dtype(payload_dtype))
+    _check(load_library().bsp_pack(_np_ptr(W), w_dtype, _np_ptr(g), O, H, K, I, bo, bi,
+                                   payload_dtype, _np_ptr(row_ptr), _np_ptr(col_idx),
+                                   col_idx.size, _np_ptr(payload), payload.nbytes),
+           "bsp_pack")
+    return row_ptr, col_idx, payload
+
+
+def bsp_unpack(row_ptr, col_idx, payload, O, H, K, I, bo, bi) -> np.ndarray:
+    code = BSP_BF16 if payload.dtype == np.uint16 else BSP_F32
+    W = np.empty((O, H, K, I), dtype=payload.dtype)
+    _check(load_library().bsp_unpack(_np_ptr(np.ascontiguousarray(row_ptr, dtype=np.int32)),
+                                     _np_ptr(np.ascontiguousarray(col_idx, dtype=np.int32)),
+                                     _np_ptr(np.ascontiguousarray(payload)), code,
+                                     O, H, K, I, bo, bi, _np_ptr(W)), "bsp_unpack")
+    return W
+
+
+def bsp_validate(row_ptr, col_idx, O, I, bo, bi) -> int:
+    """Returns the status code (0 = well formed); does not raise."""
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    ci = np.ascontiguousarray(col_idx, dtype=np.int32)
+    return load_library().bsp_validate(_np_ptr(rp), _np_ptr(ci), O, I, bo, bi)
+
+
+def bsp_plan_size(row_ptr, col_idx, O, H, K, I, bo, bi) -> int:
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    ci = np.ascontiguousarray(col_idx, dtype=np.int32)
+    n = ctypes.c_int64(0)
+    _check(load_library().bsp_plan_size(_np_ptr(rp), _np_ptr(ci), O, H, K, I, bo, bi,
+                                        ctypes.byref(n)), "bsp_plan_size")
+    return n.value
+
+
+def bsp_plan_build(row_ptr, col_idx, O, H, K, I, bo, bi) -> np.ndarray:
+    """The launch plan as an int32 array (copy it to the device as is)."""
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    ci = np.ascontiguousarray(col_idx, dtype=np.int32)
+    nbytes = bsp_plan_size(rp, ci, O, H, K, I, bo, bi)
+    plan = np.zeros(nbytes // 4, dtype=np.int32)
+    _check(load_library().bsp_plan_build(_np_ptr(rp), _np_ptr(ci), O, H, K, I, bo, bi,
+                                         _np_ptr(plan), plan.nbytes), "bsp_plan_build")
+    return plan
+
+
+# ----------------------------------------------------------------- device side
+def bsp_fc(w: bsp_weights, X: int, bias: Optional[int], Y: int, B: int, stream: int = 0) -> None:
+    _check(load_library().bsp_fc(ctypes.byref(w), X, bias, Y, B, stream), "bsp_fc")
+
+
+def bsp_conv2d(w: bsp_weights, X: int, bias: Optional[int], Y: int, B: int, L: int, J: int,
+               stride=(1, 1), pad=(0, 0), stream: int = 0) -> None:
+    _check(load_library().bsp_conv2d(ctypes.byref(w), X, bias, Y, B, L, J, stride[0], stride[1],
+                                     pad[0], pad[1], stream), "bsp_conv2d")
+
+
+def bsp_conv2d_general(w: bsp_weights, X: int, bias: Optional[int], Y: int, B: int, L: int,
+                       J: int, stride=(1, 1), pad=(0, 0), stream: int = 0) -> None:
+    _check(load_library().bsp_conv2d_general(ctypes.byref(w), X, bias, Y, B, L, J, stride[0],
+                                             stride[1], pad[0], pad[1], stream),
+           "bsp_conv2d_general")
+
+
+class BspLayer:
+    """Pack one layer on the host and keep its arrays resident on a GPU.
+
+    W is float32 [O][H][K][I] (values already representable in ``dtype``),
+    gamma the block mask.  ``dtype`` is "f32" or "bf16" and is the element type
+    of payload, X and Y.
+    """
+
+    def __init__(self, W: np.ndarray, gamma: np.ndarray, bo: int, bi: int,
+                 dtype: str = "bf16", bias: Optional[np.ndarray] = None,
+                 device: str = "cuda:0"):
+        import torch
+        load_library()
+        self.code = {"f32": BSP_F32, "bf16": BSP_BF16}[dtype]
+        self.dtype = dtype
+        self.torch_dtype = torch.float32 if dtype == "f32" else torch.bfloat16
+        O, H, K, I = W.shape
+        self.O, self.H, self.K, self.I, self.bo, self.bi = O, H, K, I, bo, bi
+        self.row_ptr, self.col_idx, self.payload = bsp_pack(
+            np.ascontiguousarray(W, dtype=np.float32), gamma, bo, bi, self.code)
+        self.plan = bsp_plan_build(self.row_ptr, self.col_idx, O, H, K, I, bo, bi)
+        self.nnzb = int(self.col_idx.size)
+        self.device = torch.device(device)
+        pl = self.payload.view(np.int16) if dtype == "bf16" else self.payload
+        # one spare element so an empty payload still has a valid address
+        self.d_payload = torch.zeros(max(pl.size, 8), dtype=torch.int16 if dtype == "bf16"
+                                     else torch.float32, device=self.device)
+        if pl.size:
+            self.d_payload[:pl.size].copy_(torch.from_numpy(pl.reshape(-1)))
+        self.d_row_ptr = torch.from_numpy(self.row_ptr).to(self.device)
+        self.d_col_idx = torch.from_numpy(np.resize(self.col_idx, max(self.nnzb, 1))
+                                          if self.nnzb else np.zeros(1, np.int32)).to(self.device)
+        self.d_plan = torch.from_numpy(self.plan).to(self.device)
+        self.d_bias = None if bias is None else \
+            torch.from_numpy(np.ascontiguousarray(bias, dtype=np.float32)).to(self.device)
+        self.struct = bsp_weights(O, I, H, K, bo, bi, self.code, 0, self.nnzb,
+                                  self.d_row_ptr.data_ptr(), self.d_col_idx.data_ptr(),
+                                  self.d_payload.data_ptr(), self.d_plan.data_ptr(),
+                                  self.plan.nbytes)
+
+    def out_shape(self, B, L, J, stride, pad):
+        M = (L + 2 * pad[0] - self.H) // stride[0] + 1
+        N = (J + 2 * pad[1] - self.K) // stride[1] + 1
+        return (B, M, N, self.O)
+
+    def conv2d(self, X, stride=(1, 1), pad=(0, 0), out=None, general=False, stream=None):
+        """X: torch tensor [B][L][J][I] on the layer's device, contiguous."""
+        import torch
+        assert X.is_contiguous() and X.dtype == self.torch_dtype and X.shape[-1] == self.I
+        B, L, J, _ = X.shape
+        if out is None:
+            out = torch.empty(self.out_shape(B, L, J, stride, pad), dtype=self.torch_dtype,
+                              device=X.device)
+        st = torch.cuda.current_stream(X.device).cuda_stream if stream is None else stream
+        fn = bsp_conv2d_general if general else bsp_conv2d
+        fn(self.struct, X.data_ptr(), None if self.d_bias is None else self.d_bias.data_ptr(),
+           out.data_ptr(), B, L, J, stride, pad, st)
+        return out
+
+    def fc(self, X, out=None, stream=None):
+        """X: torch tensor [B][I]."""
+        import torch
+        assert X.is_contiguous() and X.dtype == self.torch_dtype and X.shape[-1] == self.I
+        B = X.shape[0]
+        if out is None:
+            out = torch.empty((B, self.O), dtype=self.torch_dtype, device=X.device)
+        st = torch.cuda.current_stream(X.device).cuda_stream if stream is None else stream
+        bsp_fc(self.struct, X.data_ptr(),
+               None if self.d_bias is None else self.d_bias.data_ptr(), out.data_ptr(), B, st)
+        return out

@@ -1,0 +1,87 @@
+// extern "C" device entry points: argument checks, shape arithmetic, dispatch.
+#include "bsp.h"
+#include "bsp_launch.h"
+
+#include <limits>
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int prepare(const bsp_weights* w, const void* X, const float* bias, void* Y, int32_t B,
+            int32_t L, int32_t J, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
+            ConvParams* out) {
+  if (!w || !X || !Y) return BSP_ERR_NULL;
+  if (!w->plan) return BSP_ERR_NULL;
+  if (w->nnzb > 0 && !w->payload) return BSP_ERR_NULL;
+  if (w->O <= 0 || w->I <= 0 || w->H <= 0 || w->K <= 0 || w->nnzb < 0) return BSP_ERR_SHAPE;
+  if (!((w->bo == 8 && w->bi == 8) || (w->bo == 4 && w->bi == 16) || (w->bo == 16 && w->bi == 4)))
+    return BSP_ERR_UNSUPPORTED;
+  if (w->dtype != BSP_F32 && w->dtype != BSP_BF16) return BSP_ERR_DTYPE;
+  if (B < 0 || L <= 0 || J <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return BSP_ERR_SHAPE;
+  if (L + 2 * (int64_t)ph < w->H || J + 2 * (int64_t)pw < w->K) return BSP_ERR_SHAPE;
+  const int64_t M = (L + 2 * (int64_t)ph - w->H) / sh + 1;
+  const int64_t N = (J + 2 * (int64_t)pw - w->K) / sw + 1;
+  if (M < 1 || N < 1) return BSP_ERR_SHAPE;
+  const int64_t lim = std::numeric_limits<int32_t>::max();
+  if ((int64_t)B * M * N > lim || (int64_t)B * M * N * w->O > lim * 4 ||
+      (int64_t)B * L * J * w->I > lim * 4)
+    return BSP_ERR_SHAPE;
+  if (w->plan_bytes < (int64_t)BSP_PLAN_HEADER_WORDS * 4) return BSP_ERR_CAPACITY;
+  if (!aligned16(X) || !aligned16(Y) || !aligned16(w->payload) || !aligned16(w->plan) ||
+      (reinterpret_cast<uintptr_t>(bias) & 3u))
+    return BSP_ERR_ALIGN;
+  ConvParams p;
+  p.X = X;
+  p.Y = Y;
+  p.bias = bias;
+  p.payload = w->payload;
+  p.plan = (const int32_t*)w->plan;
+  p.B = B;
+  p.L = L;
+  p.J = J;
+  p.I = w->I;
+  p.O = w->O;
+  p.H = w->H;
+  p.K = w->K;
+  p.M = (int32_t)M;
+  p.N = (int32_t)N;
+  p.sh = sh;
+  p.sw = sw;
+  p.ph = ph;
+  p.pw = pw;
+  p.P = (int32_t)((int64_t)B * M * N);
+  *out = p;
+  return BSP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bsp_conv2d_general(const bsp_weights* w, const void* X, const float* bias, void* Y,
+                       int32_t B, int32_t L, int32_t J, int32_t stride_h, int32_t stride_w,
+                       int32_t pad_h, int32_t pad_w, void* stream) {
+  ConvParams p;
+  if (int rc = prepare(w, X, bias, Y, B, L, J, stride_h, stride_w, pad_h, pad_w, &p)) return rc;
+  if (p.P == 0) return BSP_OK;
+  return bsp_launch_general(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
+}
+
+int bsp_conv2d(const bsp_weights* w, const void* X, const float* bias, void* Y, int32_t B,
+               int32_t L, int32_t J, int32_t stride_h, int32_t stride_w, int32_t pad_h,
+               int32_t pad_w, void* stream) {
+  ConvParams p;
+  if (int rc = prepare(w, X, bias, Y, B, L, J, stride_h, stride_w, pad_h, pad_w, &p)) return rc;
+  if (p.P == 0) return BSP_OK;
+  return bsp_launch_general(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
+}
+
+int bsp_fc(const bsp_weights* w, const void* X, const float* bias, void* Y, int32_t B,
+           void* stream) {
+  if (!w || !X || !Y) return BSP_ERR_NULL;
+  if (w->H != 1 || w->K != 1) return BSP_ERR_SHAPE;
+  return bsp_conv2d(w, X, bias, Y, B, 1, 1, 1, 1, 0, 0, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,298 @@
+// Host side of libbsp: the packer (mask + dense weights -> compressed block
+// rows), its inverse, index validation, and the launch-plan builder.
+// No device code and no HIP calls in this file.
+#include "bsp.h"
+#include "bsp_plan.h"
+
+#include <cstring>
+#include <limits>
+#include <vector>
+
+namespace {
+
+inline bool granularity_ok(int32_t bo, int32_t bi) {
+  return (bo == 8 && bi == 8) || (bo == 4 && bi == 16) || (bo == 16 && bi == 4);
+}
+
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// fp32 -> bf16, round to nearest, ties to even (finite values; NaN keeps a quiet pattern).
+inline uint16_t f32_to_bf16(float f) {
+  uint32_t u;
+  std::memcpy(&u, &f, 4);
+  if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (uint16_t)((u >> 16) | 0x0040u);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+inline float bf16_to_f32(uint16_t h) {
+  uint32_t u = (uint32_t)h << 16;
+  float f;
+  std::memcpy(&f, &u, 4);
+  return f;
+}
+
+int check_layer(int32_t O, int32_t I, int32_t bo, int32_t bi) {
+  if (O <= 0 || I <= 0) return BSP_ERR_SHAPE;
+  if (!granularity_ok(bo, bi)) return BSP_ERR_UNSUPPORTED;
+  return BSP_OK;
+}
+
+template <typename Src, typename Dst> inline Dst convert(Src v);
+template <> inline float convert<float, float>(float v) { return v; }
+template <> inline uint16_t convert<uint16_t, uint16_t>(uint16_t v) { return v; }
+template <> inline uint16_t convert<float, uint16_t>(float v) { return f32_to_bf16(v); }
+template <> inline float convert<uint16_t, float>(uint16_t v) { return bf16_to_f32(v); }
+
+// Copy the kept blocks of W, block row by block row, column ascending.
+template <typename Src, typename Dst>
+void compact(const Src* W, const uint8_t* gamma, int32_t O, int32_t H, int32_t K, int32_t I,
+             int32_t bo, int32_t bi, int32_t* row_ptr, int32_t* col_idx, Dst* payload) {
+  const int64_t nbr = cdiv(O, bo), nbc = cdiv(I, bi);
+  const int64_t HK = (int64_t)H * K;
+  int64_t n = 0;
+  row_ptr[0] = 0;
+  for (int64_t l = 0; l < nbr; ++l) {
+    for (int64_t c = 0; c < nbc; ++c) {
+      if (!gamma[l * nbc + c]) continue;
+      col_idx[n] = (int32_t)c;
+      Dst* blk = payload + n * bo * HK * bi;
+      const int64_t i0 = c * bi;
+      const int64_t ni = (I - i0 < bi) ? (I - i0) : bi;
+      for (int64_t r = 0; r < bo; ++r) {
+        const int64_t o = l * bo + r;
+        for (int64_t t = 0; t < HK; ++t) {
+          Dst* d = blk + (r * HK + t) * bi;
+          if (o < O) {
+            const Src* s = W + (o * HK + t) * I + i0;
+            for (int64_t j = 0; j < ni; ++j) d[j] = convert<Src, Dst>(s[j]);
+            for (int64_t j = ni; j < bi; ++j) d[j] = Dst(0);
+          } else {
+            for (int64_t j = 0; j < bi; ++j) d[j] = Dst(0);
+          }
+        }
+      }
+      ++n;
+    }
+    row_ptr[l + 1] = (int32_t)n;
+  }
+}
+
+template <typename T>
+void expand(const int32_t* row_ptr, const int32_t* col_idx, const T* payload, int32_t O,
+            int32_t H, int32_t K, int32_t I, int32_t bo, int32_t bi, T* W) {
+  const int64_t nbr = cdiv(O, bo);
+  const int64_t HK = (int64_t)H * K;
+  std::memset(W, 0, sizeof(T) * (size_t)O * HK * I);
+  for (int64_t l = 0; l < nbr; ++l)
+    for (int64_t n = row_ptr[l]; n < row_ptr[l + 1]; ++n) {
+      const int64_t i0 = (int64_t)col_idx[n] * bi;
+      const int64_t ni = (I - i0 < bi) ? (I - i0) : bi;
+      const T* blk = payload + n * bo * HK * bi;
+      for (int64_t r = 0; r < bo && l * bo + r < O; ++r)
+        for (int64_t t = 0; t < HK; ++t)
+          std::memcpy(W + ((l * bo + r) * HK + t) * I + i0, blk + (r * HK + t) * bi,
+                      sizeof(T) * (size_t)ni);
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* bsp_strerror(int code) {
+  switch (code) {
+    case BSP_OK: return "ok";
+    case BSP_ERR_NULL: return "null pointer";
+    case BSP_ERR_SHAPE: return "bad or inconsistent shape";
+    case BSP_ERR_MASK: return "mask byte is neither 0 nor 1";
+    case BSP_ERR_INDEX: return "row_ptr / col_idx malformed";
+    case BSP_ERR_DTYPE: return "element type not supported";
+    case BSP_ERR_UNSUPPORTED: return "block granularity not in {8x8, 4x16, 16x4}";
+    case BSP_ERR_CAPACITY: return "output buffer too small";
+    case BSP_ERR_HIP: return "HIP runtime error at launch";
+    case BSP_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    default: return "unknown status";
+  }
+}
+
+int bsp_version(void) { return 1; }
+
+int bsp_pack_count(const uint8_t* gamma, int32_t O, int32_t I, int32_t bo, int32_t bi,
+                   int64_t* nnzb) {
+  if (!gamma || !nnzb) return BSP_ERR_NULL;
+  if (int rc = check_layer(O, I, bo, bi)) return rc;
+  const int64_t total = cdiv(O, bo) * cdiv(I, bi);
+  int64_t n = 0;
+  for (int64_t t = 0; t < total; ++t) {
+    if (gamma[t] > 1) return BSP_ERR_MASK;
+    n += gamma[t];
+  }
+  *nnzb = n;
+  return BSP_OK;
+}
+
+int bsp_pack(const void* W, int32_t w_dtype, const uint8_t* gamma, int32_t O, int32_t H,
+             int32_t K, int32_t I, int32_t bo, int32_t bi, int32_t payload_dtype,
+             int32_t* row_ptr, int32_t* col_idx, int64_t col_capacity, void* payload,
+             int64_t payload_capacity_bytes) {
+  if (!W || !gamma || !row_ptr) return BSP_ERR_NULL;
+  if (H <= 0 || K <= 0) return BSP_ERR_SHAPE;
+  int64_t nnzb = 0;
+  if (int rc = bsp_pack_count(gamma, O, I, bo, bi, &nnzb)) return rc;
+  if ((w_dtype != BSP_F32 && w_dtype != BSP_BF16) ||
+      (payload_dtype != BSP_F32 && payload_dtype != BSP_BF16))
+    return BSP_ERR_DTYPE;
+  if (nnzb > 0 && (!col_idx || !payload)) return BSP_ERR_NULL;
+  if (nnzb > std::numeric_limits<int32_t>::max()) return BSP_ERR_SHAPE;
+  const int64_t esz = payload_dtype == BSP_F32 ? 4 : 2;
+  if (col_capacity < nnzb) return BSP_ERR_CAPACITY;
+  if (payload_capacity_bytes < nnzb * bo * bi * (int64_t)H * K * esz) return BSP_ERR_CAPACITY;
+  if (w_dtype == BSP_F32 && payload_dtype == BSP_F32)
+    compact((const float*)W, gamma, O, H, K, I, bo, bi, row_ptr, col_idx, (float*)payload);
+  else if (w_dtype == BSP_F32)
+    compact((const float*)W, gamma, O, H, K, I, bo, bi, row_ptr, col_idx, (uint16_t*)payload);
+  else if (payload_dtype == BSP_F32)
+    compact((const uint16_t*)W, gamma, O, H, K, I, bo, bi, row_ptr, col_idx, (float*)payload);
+  else
+    compact((const uint16_t*)W, gamma, O, H, K, I, bo, bi, row_ptr, col_idx,
+            (uint16_t*)payload);
+  return BSP_OK;
+}
+
+int bsp_validate(const int32_t* row_ptr, const int32_t* col_idx, int32_t O, int32_t I,
+                 int32_t bo, int32_t bi) {
+  if (!row_ptr) return BSP_ERR_NULL;
+  if (int rc = check_layer(O, I, bo, bi)) return rc;
+  const int64_t nbr = cdiv(O, bo), nbc = cdiv(I, bi);
+  if (row_ptr[0] != 0) return BSP_ERR_INDEX;
+  for (int64_t l = 0; l < nbr; ++l) {
+    const int64_t a = row_ptr[l], b = row_ptr[l + 1];
+    if (b < a || b - a > nbc) return BSP_ERR_INDEX;
+    if (b > a && !col_idx) return BSP_ERR_NULL;
+    for (int64_t n = a; n < b; ++n) {
+      if (col_idx[n] < 0 || col_idx[n] >= nbc) return BSP_ERR_INDEX;
+      if (n > a && col_idx[n] <= col_idx[n - 1]) return BSP_ERR_INDEX;
+    }
+  }
+  return BSP_OK;
+}
+
+int bsp_unpack(const int32_t* row_ptr, const int32_t* col_idx, const void* payload,
+               int32_t payload_dtype, int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo,
+               int32_t bi, void* W) {
+  if (!W) return BSP_ERR_NULL;
+  if (H <= 0 || K <= 0) return BSP_ERR_SHAPE;
+  if (int rc = bsp_validate(row_ptr, col_idx, O, I, bo, bi)) return rc;
+  if (payload_dtype != BSP_F32 && payload_dtype != BSP_BF16) return BSP_ERR_DTYPE;
+  const int64_t nnzb = row_ptr[cdiv(O, bo)];
+  if (nnzb > 0 && !payload) return BSP_ERR_NULL;
+  if (payload_dtype == BSP_F32)
+    expand(row_ptr, col_idx, (const float*)payload, O, H, K, I, bo, bi, (float*)W);
+  else
+    expand(row_ptr, col_idx, (const uint16_t*)payload, O, H, K, I, bo, bi, (uint16_t*)W);
+  return BSP_OK;
+}
+
+// ---------------------------------------------------------------- launch plan
+// One pass serves both entry points: with out == nullptr it only counts.
+static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, int32_t O, int32_t H,
+                     int32_t K, int32_t I, int32_t bo, int32_t bi, int32_t* out,
+                     int64_t capacity_words, int64_t* words_needed) {
+  if (H <= 0 || K <= 0) return BSP_ERR_SHAPE;
+  if (int rc = bsp_validate(row_ptr, col_idx, O, I, bo, bi)) return rc;
+  const int64_t nbr = cdiv(O, bo);
+  const int64_t HK = (int64_t)H * K;
+  const int64_t blk_elems = (int64_t)bo * bi * HK;
+  const int64_t nnzb = row_ptr[nbr];
+  if (nnzb * blk_elems > std::numeric_limits<int32_t>::max()) return BSP_ERR_SHAPE;
+  const int32_t nstrips = (int32_t)cdiv(O, BSP_STRIP);
+  const int32_t nxc = (int32_t)cdiv(I, BSP_CHUNK);
+  const int32_t rows_per_strip = BSP_STRIP / bo;  // 2, 4 or 1
+
+  std::vector<int32_t> src((size_t)nxc * BSP_MAXSUB);
+  std::vector<int32_t> strip_ptr((size_t)nstrips + 1, 0);
+  std::vector<int32_t> xc_list, src_list;
+  int32_t max_chunks = 0;
+  for (int32_t t = 0; t < nstrips; ++t) {
+    std::fill(src.begin(), src.end(), -1);
+    for (int32_t s = 0; s < rows_per_strip; ++s) {
+      const int64_t l = (int64_t)t * rows_per_strip + s;
+      if (l >= nbr) break;
+      for (int64_t n = row_ptr[l]; n < row_ptr[l + 1]; ++n) {
+        const int32_t c = col_idx[n];
+        const int32_t base = (int32_t)(n * blk_elems);
+        if (bi == 8) {
+          src[(size_t)c * BSP_MAXSUB + s] = base;
+        } else if (bi == 16) {
+          for (int32_t half = 0; half < 2; ++half) {
+            const int32_t xc = 2 * c + half;
+            if (xc < nxc) src[(size_t)xc * BSP_MAXSUB + s] = base + half * 8;
+          }
+        } else {  // bi == 4: two block columns share one 8-channel group
+          src[(size_t)(c / 2) * BSP_MAXSUB + (c % 2)] = base;
+        }
+      }
+    }
+    int32_t count = 0;
+    for (int32_t xc = 0; xc < nxc; ++xc) {
+      const int32_t* e = &src[(size_t)xc * BSP_MAXSUB];
+      if (e[0] < 0 && e[1] < 0 && e[2] < 0 && e[3] < 0) continue;
+      xc_list.push_back(xc);
+      src_list.insert(src_list.end(), e, e + BSP_MAXSUB);
+      ++count;
+    }
+    strip_ptr[(size_t)t + 1] = strip_ptr[t] + count;
+    if (count > max_chunks) max_chunks = count;
+  }
+  const int64_t nchunks = (int64_t)xc_list.size();
+  auto pad4 = [](int64_t w) { return (w + 3) & ~int64_t(3); };
+  const int64_t off_strip = BSP_PLAN_HEADER_WORDS;
+  const int64_t off_xc = off_strip + pad4(nstrips + 1);
+  const int64_t off_src = off_xc + pad4(nchunks);
+  const int64_t total = off_src + nchunks * BSP_MAXSUB;
+  if (total > std::numeric_limits<int32_t>::max()) return BSP_ERR_SHAPE;
+  if (words_needed) *words_needed = total;
+  if (!out) return BSP_OK;
+  if (capacity_words < total) return BSP_ERR_CAPACITY;
+  std::memset(out, 0, sizeof(int32_t) * (size_t)total);
+  out[BSP_PLAN_MAGIC_W] = BSP_PLAN_MAGIC;
+  out[BSP_PLAN_VERSION_W] = BSP_PLAN_VERSION;
+  out[BSP_PLAN_O_W] = O;
+  out[BSP_PLAN_I_W] = I;
+  out[BSP_PLAN_H_W] = H;
+  out[BSP_PLAN_K_W] = K;
+  out[BSP_PLAN_BO_W] = bo;
+  out[BSP_PLAN_BI_W] = bi;
+  out[BSP_PLAN_NSTRIPS_W] = nstrips;
+  out[BSP_PLAN_NCHUNKS_W] = (int32_t)nchunks;
+  out[BSP_PLAN_OFF_STRIP_W] = (int32_t)off_strip;
+  out[BSP_PLAN_OFF_XC_W] = (int32_t)off_xc;
+  out[BSP_PLAN_OFF_SRC_W] = (int32_t)off_src;
+  out[BSP_PLAN_TOTAL_W] = (int32_t)total;
+  out[BSP_PLAN_MAXCHUNKS_W] = max_chunks;
+  std::memcpy(out + off_strip, strip_ptr.data(), sizeof(int32_t) * strip_ptr.size());
+  if (nchunks) {
+    std::memcpy(out + off_xc, xc_list.data(), sizeof(int32_t) * xc_list.size());
+    std::memcpy(out + off_src, src_list.data(), sizeof(int32_t) * src_list.size());
+  }
+  return BSP_OK;
+}
+
+int bsp_plan_size(const int32_t* row_ptr, const int32_t* col_idx, int32_t O, int32_t H,
+                  int32_t K, int32_t I, int32_t bo, int32_t bi, int64_t* bytes) {
+  if (!bytes) return BSP_ERR_NULL;
+  int64_t words = 0;
+  if (int rc = plan_walk(row_ptr, col_idx, O, H, K, I, bo, bi, nullptr, 0, &words)) return rc;
+  *bytes = words * 4;
+  return BSP_OK;
+}
+
+int bsp_plan_build(const int32_t* row_ptr, const int32_t* col_idx, int32_t O, int32_t H,
+                   int32_t K, int32_t I, int32_t bo, int32_t bi, void* plan,
+                   int64_t capacity_bytes) {
+  if (!plan) return BSP_ERR_NULL;
+  return plan_walk(row_ptr, col_idx, O, H, K, I, bo, bi, (int32_t*)plan, capacity_bytes / 4,
+                   nullptr);
+}
+
+}  // extern "C"

@@ -1,0 +1,56 @@
+// Launch-plan blob shared by the host builder and the kernels (library private).
+//
+// The kernels tile the output channels into strips of BSP_STRIP = 16 (the
+// row count of a 16x16 MFMA tile) and the input channels into chunks of
+// BSP_CHUNK = 8 (what one lane feeds a bf16 MFMA).  A strip covers two 8x8
+// block rows, four 4x16 block rows or one 16x4 block row; a chunk is one 8x8
+// block column, half a 4x16 block column or two 16x4 block columns.  For each
+// strip the plan lists, in ascending order, the chunks in which at least one
+// block of the strip is kept, and for each of the up to BSP_MAXSUB blocks that
+// meet in a (strip, chunk) cell the element offset of its first needed entry
+// inside the payload array, or -1 if that block is zeroed.
+//
+// Words (int32):
+//   [0..15]                header, see enum below
+//   [off_strip ..]         strip_ptr[nstrips+1]    first chunk of each strip
+//   [off_xc ..]            chunk_xc[nchunks]       chunk index (input channel / 8)
+//   [off_src ..]           chunk_src[nchunks][4]   payload element offsets or -1
+//
+// Meaning of chunk_src[c][s] by granularity (element offset of row 0, tap 0):
+//   8x8   s = 0,1   block row 2*strip+s, block column xc
+//   4x16  s = 0..3  block row 4*strip+s, block column xc/2, already advanced by
+//                   8*(xc%2) to the half of the block this chunk covers
+//   16x4  s = 0,1   block row strip, block column 2*xc+s (channels 4s..4s+3 of the chunk)
+#ifndef BSP_PLAN_H
+#define BSP_PLAN_H
+
+#include <stdint.h>
+
+enum {
+  BSP_STRIP = 16,
+  BSP_CHUNK = 8,
+  BSP_MAXSUB = 4,
+  BSP_PLAN_HEADER_WORDS = 16,
+  BSP_PLAN_MAGIC = 0x42535031,
+  BSP_PLAN_VERSION = 1,
+};
+
+enum {
+  BSP_PLAN_MAGIC_W = 0,
+  BSP_PLAN_VERSION_W = 1,
+  BSP_PLAN_O_W = 2,
+  BSP_PLAN_I_W = 3,
+  BSP_PLAN_H_W = 4,
+  BSP_PLAN_K_W = 5,
+  BSP_PLAN_BO_W = 6,
+  BSP_PLAN_BI_W = 7,
+  BSP_PLAN_NSTRIPS_W = 8,
+  BSP_PLAN_NCHUNKS_W = 9,
+  BSP_PLAN_OFF_STRIP_W = 10,
+  BSP_PLAN_OFF_XC_W = 11,
+  BSP_PLAN_OFF_SRC_W = 12,
+  BSP_PLAN_TOTAL_W = 13,
+  BSP_PLAN_MAXCHUNKS_W = 14,
+};
+
+#endif
