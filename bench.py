@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-sparse convolution hot path on one MI355X.
+
+A step is one launch of bsp_conv2d (activation staging, gathered block-row
+contraction, bias epilogue) on one batch of the named workload, inputs and the
+packed weights already resident in HBM.  Packing (host, once per layer) is
+timed separately and reported as ``pack_ms``.  Prints ONE JSON line.
+
+  python bench.py [--steps K] [--warmup W] [--workload c1|c2|...]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
+
+
+def algorithmic_bytes(c, nnzb: int) -> int:
+    """Bytes the method itself must move for one launch: X read once, Y written
+    once, kept blocks + indices + bias read once."""
+    es = 4 if c.dtype == "f32" else 2
+    nbr = -(-c.O // c.bo)
+    return (c.B * c.L * c.J * c.I * es + c.P * c.O * es
+            + nnzb * c.bo * c.bi * c.H * c.K * es + 4 * (nnzb + nbr + 1) + 4 * c.O)
+
+
+def flops_nonzero(c, nnzb: int) -> int:
+    return 2 * c.P * nnzb * c.bo * c.bi * c.H * c.K
+
+
+def pick_case(name: str):
+    from synthetic import config_cases
+    if name == "c1":
+        return next(config_cases(1)), "config1: conv3x3 s1 p1, X 32x56x56x64 NHWC bf16, W 64x3x3x64, 8x8 blocks, 32 of 64 kept"
+    if name == "c0":
+        return next(config_cases(0)), "config0: FC fp32 64x256 -> 256, 8x8 blocks, Bernoulli(0.5)"
+    if name.startswith("c2"):
+        want = name[3:] if len(name) > 2 else "8x8.d0.5"
+        for c in config_cases(2):
+            if c.name.endswith(want):
+                return c, f"config2: conv1x1 256->1024 @14x14 batch 32 bf16, {want}"
+    raise SystemExit(f"unknown workload {name}")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default="c1")
+    ap.add_argument("--sets", type=int, default=0,
+                    help="distinct X/Y buffer sets cycled through (0 = enough to exceed 256 MB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--general", action="store_true", help="force the general-shape kernel")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); "
+              "multi-GPU figures are not produced", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2407_09453_amd as bsp
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    c, workload = pick_case(args.workload)
+    tdt = torch.float32 if c.dtype == "f32" else torch.bfloat16
+
+    t0 = time.perf_counter()
+    layer = bsp.BspLayer(c.W, c.gamma, c.bo, c.bi, c.dtype, bias=c.bias)
+    pack_ms = (time.perf_counter() - t0) * 1e3
+    dense = bsp.BspLayer(c.W, np.ones_like(c.gamma), c.bo, c.bi, c.dtype, bias=c.bias)
+
+    nbytes = algorithmic_bytes(c, layer.nnzb)
+    nsets = args.sets or max(2, int(np.ceil(300e6 / nbytes)))
+    X0 = torch.from_numpy(c.X).to(tdt).to(dev)
+    Xs = [X0] + [X0.clone() for _ in range(nsets - 1)]
+    Ys = [torch.empty(layer.out_shape(c.B, c.L, c.J, c.stride, c.pad), dtype=tdt, device=dev)
+          for _ in range(nsets)]
+    stream = torch.cuda.current_stream(dev)
+
+    def step(lay, i):
+        lay.conv2d(Xs[i % nsets], c.stride, c.pad, out=Ys[i % nsets], general=args.general)
+
+    def timed(lay, steps, warmup):
+        for i in range(warmup):
+            step(lay, i)
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        t = time.perf_counter()
+        e0.record(stream)
+        for i in range(steps):
+            step(lay, i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t
+        return wall * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+    def per_launch_us(lay, steps):
+        """Average duration of one kernel launch from HIP events recorded on the
+        launch stream right before and after each launch."""
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(steps)]
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(evs):
+            a.record(stream)
+            step(lay, i)
+            b.record(stream)
+        torch.cuda.synchronize()
+        d = np.array([a.elapsed_time(b) for a, b in evs]) * 1e3
+        return float(d.mean()), float(np.median(d)), float(d.min())
+
+    ms_wall, ms_ev = timed(layer, args.steps, args.warmup)
+    ms_wall_d, ms_ev_d = timed(dense, args.steps, args.warmup)
+    k_avg, k_med, k_min = per_launch_us(layer, args.steps)
+    kd_avg, kd_med, kd_min = per_launch_us(dense, args.steps)
+
+    fl = flops_nonzero(c, layer.nnzb)
+    value = fl / (ms_wall * 1e-3) / 1e12
+    achieved = nbytes / (k_avg * 1e-6) / 1e9
+    out = {
+        "metric": "effective nonzero TFLOP/s (2*P*nnzb*bo*bi*H*K / t), 50% 8x8 block-sparse conv",
+        "value": round(value, 4),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_wall, 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": c.dtype,
+        "data": "synthetic",
+        "config": {"workload": workload, "block": f"{c.bo}x{c.bi}", "nnzb": layer.nnzb,
+                   "density": round(layer.nnzb / c.gamma.size, 4), "buffer_sets": nsets,
+                   "kernel": "general" if args.general else "dispatch"},
+        "speedup_vs_dense_mask": round(ms_wall_d / ms_wall, 4),
+        "dense_mask_ms_per_step": round(ms_wall_d, 6),
+        "event_ms_per_step": round(ms_ev, 6),
+        "kernel_us": {"avg": round(k_avg, 3), "median": round(k_med, 3), "min": round(k_min, 3),
+                      "dense_mask_avg": round(kd_avg, 3)},
+        "mfma_frac_of_peak": round(fl / (k_avg * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5)
+        if c.dtype == "bf16" else None,
+        "pack_ms": round(pack_ms, 3),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
+                     "traffic": None, "algorithmic_bytes": nbytes},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        t = time.perf_counter()
+        _, used = oracle.conv2d(c.X, c.W, c.bias, c.gamma, c.bo, c.bi, c.stride, c.pad,
+                                return_threads=True)
+        dt = time.perf_counter() - t
+        out["cpu_baseline"] = {"value": round(fl / dt / 1e12, 6), "unit": "TFLOP/s",
+                               "cores": int(used), "kind": "oracle",
+                               "sample": f"the full workload once ({dt:.2f} s; the oracle does the "
+                                         "dense masked sum and skips nothing)"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
