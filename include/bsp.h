@@ -105,17 +105,23 @@ int bsp_validate(const int32_t* row_ptr, const int32_t* col_idx,
 
 /* Launch plan.  The kernels walk strips of 16 output channels; for each strip
  * the plan lists which 8-wide groups of input channels carry at least one kept
- * block and where in `payload` each kept block of the strip starts.  It is
- * derived from row_ptr / col_idx alone (weights are prepared once, ahead of
- * inference: Section V), holds offsets only (position independent), and is
- * private to this library version: build it, copy the bytes to the device,
- * pass the device pointer in bsp_weights.plan.
+ * block and where in `payload` each kept block of the strip starts.  For bf16
+ * it also holds a copy of the kept weights re-ordered into the exact order in
+ * which the matrix-core kernels consume them (the paper's compiler likewise
+ * lays weights out per sub-volume ahead of time, Sections III and V-B), so
+ * that every weight read on the device is one contiguous, aligned run.  The
+ * plan is derived from row_ptr / col_idx / payload alone (weights are prepared
+ * once, ahead of inference), holds offsets only (position independent), and is
+ * private to this library version: build it on the host, copy the bytes to
+ * the device, pass the device pointer in bsp_weights.plan.
+ *   payload, payload_dtype   the arrays bsp_pack produced (HOST pointers)
  * bsp_plan_size  -> bytes needed.   bsp_plan_build -> fills `plan`.
- * Errors: NULL, SHAPE, UNSUPPORTED, INDEX, CAPACITY. */
+ * Errors: NULL, SHAPE, UNSUPPORTED, DTYPE, INDEX, CAPACITY. */
 int bsp_plan_size(const int32_t* row_ptr, const int32_t* col_idx,
                   int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo, int32_t bi,
-                  int64_t* bytes);
+                  int32_t payload_dtype, int64_t* bytes);
 int bsp_plan_build(const int32_t* row_ptr, const int32_t* col_idx,
+                   const void* payload, int32_t payload_dtype,
                    int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo, int32_t bi,
                    void* plan, int64_t capacity_bytes);
 

@@ -68,9 +68,9 @@ def load_library():
     lib.bsp_validate.restype = ctypes.c_int
     lib.bsp_validate.argtypes = [vp, vp, i32, i32, i32, i32]
     lib.bsp_plan_size.restype = ctypes.c_int
-    lib.bsp_plan_size.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, ctypes.POINTER(i64)]
+    lib.bsp_plan_size.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, ctypes.POINTER(i64)]
     lib.bsp_plan_build.restype = ctypes.c_int
-    lib.bsp_plan_build.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, i64]
+    lib.bsp_plan_build.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, i64]
     wp = ctypes.POINTER(bsp_weights)
     lib.bsp_fc.restype = ctypes.c_int
     lib.bsp_fc.argtypes = [wp, vp, vp, vp, i32, vp]
@@ -157,23 +157,30 @@ def bsp_validate(row_ptr, col_idx, O, I, bo, bi) -> int:
     return load_library().bsp_validate(_np_ptr(rp), _np_ptr(ci), O, I, bo, bi)
 
 
-def bsp_plan_size(row_ptr, col_idx, O, H, K, I, bo, bi) -> int:
+def _payload_code(payload: np.ndarray) -> int:
+    return BSP_BF16 if payload.dtype == np.uint16 else BSP_F32
+
+
+def bsp_plan_size(row_ptr, col_idx, O, H, K, I, bo, bi, payload_dtype: int) -> int:
     rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
     ci = np.ascontiguousarray(col_idx, dtype=np.int32)
     n = ctypes.c_int64(0)
     _check(load_library().bsp_plan_size(_np_ptr(rp), _np_ptr(ci), O, H, K, I, bo, bi,
-                                        ctypes.byref(n)), "bsp_plan_size")
+                                        payload_dtype, ctypes.byref(n)), "bsp_plan_size")
     return n.value
 
 
-def bsp_plan_build(row_ptr, col_idx, O, H, K, I, bo, bi) -> np.ndarray:
+def bsp_plan_build(row_ptr, col_idx, payload, O, H, K, I, bo, bi) -> np.ndarray:
     """The launch plan as an int32 array (copy it to the device as is)."""
     rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
     ci = np.ascontiguousarray(col_idx, dtype=np.int32)
-    nbytes = bsp_plan_size(rp, ci, O, H, K, I, bo, bi)
+    pl = np.ascontiguousarray(payload)
+    code = _payload_code(pl)
+    nbytes = bsp_plan_size(rp, ci, O, H, K, I, bo, bi, code)
     plan = np.zeros(nbytes // 4, dtype=np.int32)
-    _check(load_library().bsp_plan_build(_np_ptr(rp), _np_ptr(ci), O, H, K, I, bo, bi,
-                                         _np_ptr(plan), plan.nbytes), "bsp_plan_build")
+    _check(load_library().bsp_plan_build(_np_ptr(rp), _np_ptr(ci), _np_ptr(pl), code,
+                                         O, H, K, I, bo, bi, _np_ptr(plan), plan.nbytes),
+           "bsp_plan_build")
     return plan
 
 
@@ -215,7 +222,7 @@ class BspLayer:
         self.O, self.H, self.K, self.I, self.bo, self.bi = O, H, K, I, bo, bi
         self.row_ptr, self.col_idx, self.payload = bsp_pack(
             np.ascontiguousarray(W, dtype=np.float32), gamma, bo, bi, self.code)
-        self.plan = bsp_plan_build(self.row_ptr, self.col_idx, O, H, K, I, bo, bi)
+        self.plan = bsp_plan_build(self.row_ptr, self.col_idx, self.payload, O, H, K, I, bo, bi)
         self.nnzb = int(self.col_idx.size)
         self.device = torch.device(device)
         pl = self.payload.view(np.int16) if dtype == "bf16" else self.payload

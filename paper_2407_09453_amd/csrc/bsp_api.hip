@@ -74,6 +74,10 @@ int bsp_conv2d(const bsp_weights* w, const void* X, const float* bias, void* Y, 
   ConvParams p;
   if (int rc = prepare(w, X, bias, Y, B, L, J, stride_h, stride_w, pad_h, pad_w, &p)) return rc;
   if (p.P == 0) return BSP_OK;
+  if (bsp_tile_supported(p, w->dtype)) {
+    const int rc = bsp_launch_tile(p, w->dtype, (hipStream_t)stream);
+    if (rc != BSP_ERR_UNSUPPORTED) return rc;
+  }
   return bsp_launch_general(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
 }
 

@@ -195,10 +195,12 @@ int bsp_unpack(const int32_t* row_ptr, const int32_t* col_idx, const void* paylo
 
 // ---------------------------------------------------------------- launch plan
 // One pass serves both entry points: with out == nullptr it only counts.
-static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, int32_t O, int32_t H,
-                     int32_t K, int32_t I, int32_t bo, int32_t bi, int32_t* out,
-                     int64_t capacity_words, int64_t* words_needed) {
+static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, const void* payload,
+                     int32_t dtype, int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo,
+                     int32_t bi, int32_t* out, int64_t capacity_words, int64_t* words_needed) {
   if (H <= 0 || K <= 0) return BSP_ERR_SHAPE;
+  if (dtype != BSP_F32 && dtype != BSP_BF16) return BSP_ERR_DTYPE;
+  if (H > 255 || K > 255) return BSP_ERR_SHAPE;
   if (int rc = bsp_validate(row_ptr, col_idx, O, I, bo, bi)) return rc;
   const int64_t nbr = cdiv(O, bo);
   const int64_t HK = (int64_t)H * K;
@@ -208,11 +210,17 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, int32_t O, 
   const int32_t nstrips = (int32_t)cdiv(O, BSP_STRIP);
   const int32_t nxc = (int32_t)cdiv(I, BSP_CHUNK);
   const int32_t rows_per_strip = BSP_STRIP / bo;  // 2, 4 or 1
+  const bool steps_wanted = dtype == BSP_BF16;
+  const int32_t slab = bsp_slab_channels(I, H, K);
+  const int32_t slab_chunks = slab / BSP_CHUNK;
+  const int32_t nslabs = (int32_t)cdiv(nxc, slab_chunks);
 
   std::vector<int32_t> src((size_t)nxc * BSP_MAXSUB);
   std::vector<int32_t> strip_ptr((size_t)nstrips + 1, 0);
   std::vector<int32_t> xc_list, src_list;
-  int32_t max_chunks = 0;
+  std::vector<int32_t> slab_ptr;  // [nstrips][nslabs+1]
+  int32_t max_chunks = 0, max_steps = 0;
+  int64_t nsteps = 0;
   for (int32_t t = 0; t < nstrips; ++t) {
     std::fill(src.begin(), src.end(), -1);
     for (int32_t s = 0; s < rows_per_strip; ++s) {
@@ -234,26 +242,46 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, int32_t O, 
       }
     }
     int32_t count = 0;
+    const int64_t strip_first_step = nsteps;
+    int32_t next_slab = 0, in_slab = 0;
+    auto close_slabs_upto = [&](int32_t sl) {  // finish slabs < sl
+      while (next_slab < sl) {
+        if (next_slab == 0) slab_ptr.push_back((int32_t)nsteps);
+        nsteps += cdiv((int64_t)in_slab * HK, 4);
+        slab_ptr.push_back((int32_t)nsteps);
+        in_slab = 0;
+        ++next_slab;
+      }
+    };
     for (int32_t xc = 0; xc < nxc; ++xc) {
       const int32_t* e = &src[(size_t)xc * BSP_MAXSUB];
       if (e[0] < 0 && e[1] < 0 && e[2] < 0 && e[3] < 0) continue;
+      close_slabs_upto(xc / slab_chunks);
       xc_list.push_back(xc);
       src_list.insert(src_list.end(), e, e + BSP_MAXSUB);
       ++count;
+      ++in_slab;
     }
+    close_slabs_upto(nslabs);
     strip_ptr[(size_t)t + 1] = strip_ptr[t] + count;
     if (count > max_chunks) max_chunks = count;
+    if (nsteps - strip_first_step > max_steps) max_steps = (int32_t)(nsteps - strip_first_step);
   }
+  if (!steps_wanted) nsteps = 0;
   const int64_t nchunks = (int64_t)xc_list.size();
   auto pad4 = [](int64_t w) { return (w + 3) & ~int64_t(3); };
   const int64_t off_strip = BSP_PLAN_HEADER_WORDS;
   const int64_t off_xc = off_strip + pad4(nstrips + 1);
   const int64_t off_src = off_xc + pad4(nchunks);
-  const int64_t total = off_src + nchunks * BSP_MAXSUB;
+  const int64_t off_slab = off_src + nchunks * BSP_MAXSUB;
+  const int64_t off_xdesc = off_slab + (steps_wanted ? pad4((int64_t)nstrips * (nslabs + 1)) : 0);
+  const int64_t off_wfrag = off_xdesc + nsteps * 4;
+  const int64_t total = off_wfrag + nsteps * 64 * 8 / 2;  // bf16: two elements per word
   if (total > std::numeric_limits<int32_t>::max()) return BSP_ERR_SHAPE;
   if (words_needed) *words_needed = total;
   if (!out) return BSP_OK;
   if (capacity_words < total) return BSP_ERR_CAPACITY;
+  if (steps_wanted && nnzb > 0 && !payload) return BSP_ERR_NULL;
   std::memset(out, 0, sizeof(int32_t) * (size_t)total);
   out[BSP_PLAN_MAGIC_W] = BSP_PLAN_MAGIC;
   out[BSP_PLAN_VERSION_W] = BSP_PLAN_VERSION;
@@ -270,29 +298,76 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, int32_t O, 
   out[BSP_PLAN_OFF_SRC_W] = (int32_t)off_src;
   out[BSP_PLAN_TOTAL_W] = (int32_t)total;
   out[BSP_PLAN_MAXCHUNKS_W] = max_chunks;
+  out[BSP_PLAN_DTYPE_W] = dtype;
+  out[BSP_PLAN_SLAB_W] = slab;
+  out[BSP_PLAN_NSLABS_W] = nslabs;
+  out[BSP_PLAN_NSTEPS_W] = (int32_t)nsteps;
+  out[BSP_PLAN_OFF_SLAB_W] = (int32_t)off_slab;
+  out[BSP_PLAN_OFF_XDESC_W] = (int32_t)off_xdesc;
+  out[BSP_PLAN_OFF_WFRAG_W] = (int32_t)off_wfrag;
+  out[BSP_PLAN_MAXSTEPS_W] = steps_wanted ? max_steps : 0;
   std::memcpy(out + off_strip, strip_ptr.data(), sizeof(int32_t) * strip_ptr.size());
   if (nchunks) {
     std::memcpy(out + off_xc, xc_list.data(), sizeof(int32_t) * xc_list.size());
     std::memcpy(out + off_src, src_list.data(), sizeof(int32_t) * src_list.size());
   }
+  if (!steps_wanted) return BSP_OK;
+
+  // Step section: re-order the kept bf16 weights into MFMA operand order.
+  std::memcpy(out + off_slab, slab_ptr.data(), sizeof(int32_t) * slab_ptr.size());
+  const uint16_t* pl = (const uint16_t*)payload;
+  int32_t* xdesc = out + off_xdesc;
+  uint16_t* wfrag = (uint16_t*)(out + off_wfrag);
+  for (int32_t t = 0; t < nstrips; ++t) {
+    int32_t e = strip_ptr[t];  // walks the strip's chunks in slab order
+    for (int32_t sl = 0; sl < nslabs; ++sl) {
+      const int32_t e0 = e;
+      while (e < strip_ptr[(size_t)t + 1] && xc_list[e] / slab_chunks == sl) ++e;
+      const int64_t pairs = (int64_t)(e - e0) * HK;
+      const int64_t s0 = slab_ptr[(size_t)t * (nslabs + 1) + sl];
+      for (int64_t q = 0; q < pairs; ++q) {
+        const int64_t step = s0 + q / 4;
+        const int32_t g = (int32_t)(q % 4);
+        const int32_t ce = e0 + (int32_t)(q / HK);
+        const int32_t tap = (int32_t)(q % HK);
+        const int32_t xc = xc_list[ce];
+        xdesc[step * 4 + g] = (xc - sl * slab_chunks) | ((tap / K) << 16) | ((tap % K) << 24);
+        const int32_t* sr = &src_list[(size_t)ce * BSP_MAXSUB];
+        for (int32_t j = 0; j < BSP_STRIP; ++j) {
+          uint16_t* d = wfrag + ((step * 64) + g * 16 + j) * 8;
+          if (bi >= 8) {
+            const int32_t so = sr[j / bo];
+            if (so >= 0) std::memcpy(d, pl + so + ((int64_t)(j % bo) * HK + tap) * bi, 16);
+          } else {
+            for (int32_t s = 0; s < 2; ++s)
+              if (sr[s] >= 0)
+                std::memcpy(d + 4 * s, pl + sr[s] + ((int64_t)j * HK + tap) * 4, 8);
+          }
+        }
+      }
+    }
+  }
   return BSP_OK;
 }
 
 int bsp_plan_size(const int32_t* row_ptr, const int32_t* col_idx, int32_t O, int32_t H,
-                  int32_t K, int32_t I, int32_t bo, int32_t bi, int64_t* bytes) {
+                  int32_t K, int32_t I, int32_t bo, int32_t bi, int32_t payload_dtype,
+                  int64_t* bytes) {
   if (!bytes) return BSP_ERR_NULL;
   int64_t words = 0;
-  if (int rc = plan_walk(row_ptr, col_idx, O, H, K, I, bo, bi, nullptr, 0, &words)) return rc;
+  if (int rc = plan_walk(row_ptr, col_idx, nullptr, payload_dtype, O, H, K, I, bo, bi, nullptr,
+                         0, &words))
+    return rc;
   *bytes = words * 4;
   return BSP_OK;
 }
 
-int bsp_plan_build(const int32_t* row_ptr, const int32_t* col_idx, int32_t O, int32_t H,
-                   int32_t K, int32_t I, int32_t bo, int32_t bi, void* plan,
-                   int64_t capacity_bytes) {
+int bsp_plan_build(const int32_t* row_ptr, const int32_t* col_idx, const void* payload,
+                   int32_t payload_dtype, int32_t O, int32_t H, int32_t K, int32_t I,
+                   int32_t bo, int32_t bi, void* plan, int64_t capacity_bytes) {
   if (!plan) return BSP_ERR_NULL;
-  return plan_walk(row_ptr, col_idx, O, H, K, I, bo, bi, (int32_t*)plan, capacity_bytes / 4,
-                   nullptr);
+  return plan_walk(row_ptr, col_idx, payload, payload_dtype, O, H, K, I, bo, bi,
+                   (int32_t*)plan, capacity_bytes / 4, nullptr);
 }
 
 }  // extern "C"

@@ -9,4 +9,9 @@
 
 int bsp_launch_general(const ConvParams& p, int dtype, int bo, int bi, hipStream_t st);
 
+// LDS-tiled bf16 kernels (need the plan's step section and I % 8 == 0).
+// BSP_ERR_UNSUPPORTED means "use the general kernel", nothing was launched.
+bool bsp_tile_supported(const ConvParams& p, int dtype);
+int bsp_launch_tile(const ConvParams& p, int dtype, hipStream_t st);
+
 #endif

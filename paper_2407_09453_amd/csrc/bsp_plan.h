@@ -11,16 +11,30 @@
 // inside the payload array, or -1 if that block is zeroed.
 //
 // Words (int32):
-//   [0..15]                header, see enum below
+//   [0..31]                header, see enum below
 //   [off_strip ..]         strip_ptr[nstrips+1]    first chunk of each strip
 //   [off_xc ..]            chunk_xc[nchunks]       chunk index (input channel / 8)
 //   [off_src ..]           chunk_src[nchunks][4]   payload element offsets or -1
+//   bf16 payloads only (the "step" section, used by the LDS-tiled kernels):
+//   [off_slab ..]          slab_ptr[nstrips][nslabs+1]  first step of each (strip, slab)
+//   [off_xdesc ..]         xdesc[nsteps][4]        per 16-lane group: which activation
+//                                                  chunk and tap it multiplies
+//   [off_wfrag ..]         wfrag[nsteps][64][8]    bf16 weights in MFMA operand order
 //
 // Meaning of chunk_src[c][s] by granularity (element offset of row 0, tap 0):
 //   8x8   s = 0,1   block row 2*strip+s, block column xc
 //   4x16  s = 0..3  block row 4*strip+s, block column xc/2, already advanced by
 //                   8*(xc%2) to the half of the block this chunk covers
 //   16x4  s = 0,1   block row strip, block column 2*xc+s (channels 4s..4s+3 of the chunk)
+//
+// Step section.  The input channels are cut into slabs of `slab` channels (what
+// the kernel keeps in LDS at a time).  Inside one (strip, slab) the contraction
+// index is the list of pairs (chunk, tap), chunk-major over the strip's kept
+// chunks that fall in the slab; one step = four consecutive pairs = one MFMA
+// 16x16x32, pair 4*step+g going to lanes 16g..16g+15.  The last step of a
+// (strip, slab) is padded with null pairs (zero weights).
+//   xdesc = (chunk index within the slab) | tap_row << 16 | tap_col << 24
+//   wfrag[step][16g + j][0..7] = W[16*strip + j][tap][8*chunk .. 8*chunk+7] or 0
 #ifndef BSP_PLAN_H
 #define BSP_PLAN_H
 
@@ -30,9 +44,9 @@ enum {
   BSP_STRIP = 16,
   BSP_CHUNK = 8,
   BSP_MAXSUB = 4,
-  BSP_PLAN_HEADER_WORDS = 16,
-  BSP_PLAN_MAGIC = 0x42535031,
-  BSP_PLAN_VERSION = 1,
+  BSP_PLAN_HEADER_WORDS = 32,
+  BSP_PLAN_MAGIC = 0x42535032,
+  BSP_PLAN_VERSION = 2,
 };
 
 enum {
@@ -51,6 +65,22 @@ enum {
   BSP_PLAN_OFF_SRC_W = 12,
   BSP_PLAN_TOTAL_W = 13,
   BSP_PLAN_MAXCHUNKS_W = 14,
+  BSP_PLAN_DTYPE_W = 15,
+  BSP_PLAN_SLAB_W = 16,       // channels per slab
+  BSP_PLAN_NSLABS_W = 17,
+  BSP_PLAN_NSTEPS_W = 18,     // 0 when there is no step section
+  BSP_PLAN_OFF_SLAB_W = 19,
+  BSP_PLAN_OFF_XDESC_W = 20,
+  BSP_PLAN_OFF_WFRAG_W = 21,
+  BSP_PLAN_MAXSTEPS_W = 22,   // most steps in any one strip
 };
+
+// Channels kept in LDS at a time, as a function of the layer shape alone so
+// that the plan builder and the launcher agree without talking to each other.
+static inline int32_t bsp_slab_channels(int32_t I, int32_t H, int32_t K) {
+  const int32_t i8 = (I + 7) / 8 * 8;
+  const int32_t cap = (H * K > 1) ? 128 : 256;
+  return i8 < cap ? i8 : cap;
+}
 
 #endif

@@ -25,6 +25,12 @@ SHAPES = [
     (5, 17, 17, 160, 192, 1, 1, (1, 1), (0, 0)),    # several tiles + ragged pixel tail
     (2, 14, 14, 72, 1000 // 8 * 8, 3, 3, (1, 1), (1, 1)),
     (1, 3, 3, 20, 12, 3, 3, (1, 1), (1, 1)),        # ragged O and I
+    (2, 14, 14, 272, 48, 3, 3, (1, 1), (1, 1)),     # three channel slabs
+    (1, 28, 28, 320, 64, 1, 1, (1, 1), (0, 0)),     # two slabs, pointwise
+    (2, 15, 15, 136, 32, 3, 3, (2, 2), (1, 1)),     # two slabs, strided
+    (1, 9, 9, 512, 32, 1, 1, (2, 2), (0, 0)),       # strided pointwise, two slabs
+    (1, 20, 33, 64, 64, 3, 3, (1, 1), (1, 1)),      # tiles hang over both image edges
+    (1, 8, 8, 16, 16, 1, 1, (1, 1), (1, 1)),        # padded pointwise
 ]
 
 

@@ -114,7 +114,7 @@ def test_error_codes():
     assert bsp.bsp_validate([0, 2, 4], [0, 0, 0, 1], 16, 16, 8, 8) == -4
     assert "granularity" in bsp.bsp_strerror(-6)
     with pytest.raises(bsp.BspError):
-        bsp.bsp_plan_build([0, 3, 2], [0, 1, 0, 1], 16, 1, 1, 16, 8, 8)
+        bsp.bsp_plan_build([0, 3, 2], [0, 1, 0, 1], np.zeros(4 * 64, np.float32), 16, 1, 1, 16, 8, 8)
     # device entry points validate before touching the GPU
     w = bsp.bsp_weights()
     assert lib.bsp_fc(None, 16, None, 16, 1, None) == -1
@@ -138,8 +138,8 @@ def _decode_plan(plan, payload, O, H, K, I, bo, bi):
     """Rebuild dense weights from the plan's offsets alone (test-side reading
     of the plan format: strips of 16 output channels, chunks of 8 input
     channels, up to four sources per cell)."""
-    hdr = plan[:16]
-    assert hdr[0] == 0x42535031
+    hdr = plan[:32]
+    assert hdr[0] == 0x42535032
     nstrips, nchunks = hdr[8], hdr[9]
     sp = plan[hdr[10]:hdr[10] + nstrips + 1]
     xc = plan[hdr[11]:hdr[11] + nchunks]
@@ -176,8 +176,9 @@ def _decode_plan(plan, payload, O, H, K, I, bo, bi):
 def test_plan_addresses_exactly_the_kept_weights(bo, bi, O, I, H, K):
     c = _case(O, I, H, K, bo, bi, seed=O + I + bo)
     rp, ci, pl = bsp.bsp_pack(c.W, c.gamma, bo, bi)
-    plan = bsp.bsp_plan_build(rp, ci, O, H, K, I, bo, bi)
-    assert plan.nbytes == bsp.bsp_plan_size(rp, ci, O, H, K, I, bo, bi)
+    plan = bsp.bsp_plan_build(rp, ci, pl, O, H, K, I, bo, bi)
+    assert plan.nbytes == bsp.bsp_plan_size(rp, ci, O, H, K, I, bo, bi, bsp.BSP_F32)
+    assert plan[18] == 0                      # fp32: no step section
     Wd, visited = _decode_plan(plan, pl, O, H, K, I, bo, bi)
     Wm = oracle.apply_mask(c.W, c.gamma, bo, bi)
     assert (Wd.view(np.uint32) == Wm.view(np.uint32)).all()
@@ -191,5 +192,62 @@ def test_plan_of_empty_and_full_masks():
     for kind in ("zeros", "ones"):
         c = _case(32, 32, 1, 1, 8, 8, seed=1, kind=kind)
         rp, ci, pl = bsp.bsp_pack(c.W, c.gamma, 8, 8)
-        plan = bsp.bsp_plan_build(rp, ci, 32, 1, 1, 32, 8, 8)
+        plan = bsp.bsp_plan_build(rp, ci, pl, 32, 1, 1, 32, 8, 8)
         assert plan[9] == (0 if kind == "zeros" else 2 * 4)
+
+
+def _decode_steps(plan, O, H, K, I):
+    """Rebuild dense bf16 weights from the step section alone: slab_ptr gives
+    each (strip, slab) its steps, xdesc says which (chunk, tap) each 16-lane
+    group of a step multiplies, wfrag holds the 16 x 8 weights for it."""
+    hdr = plan[:32]
+    nstrips, slab, nslabs, nsteps = hdr[8], hdr[16], hdr[17], hdr[18]
+    sp = plan[hdr[19]:hdr[19] + nstrips * (nslabs + 1)].reshape(nstrips, nslabs + 1)
+    xd = plan[hdr[20]:hdr[20] + 4 * nsteps].reshape(nsteps, 4)
+    wf = plan[hdr[21]:hdr[21] + nsteps * 256].view(np.uint16).reshape(nsteps, 4, 16, 8)
+    W = np.zeros((16 * nstrips, H, K, 8 * (-(-I // 8))), dtype=np.uint16)
+    seen = np.zeros((16 * nstrips, H, K, W.shape[3] // 8), dtype=np.int32)
+    assert sp[0, 0] == 0 and sp[-1, -1] == nsteps
+    assert (np.diff(sp.reshape(-1)) >= 0).all()
+    nonnull = 0
+    for t in range(nstrips):
+        for sl in range(nslabs):
+            for st in range(sp[t, sl], sp[t, sl + 1]):
+                for g in range(4):
+                    frag = wf[st, g]
+                    d = int(xd[st, g])
+                    xc, th, tw = (d & 0xFFFF) + sl * (slab // 8), (d >> 16) & 0xFF, (d >> 24) & 0xFF
+                    if not frag.any() and d == 0:
+                        continue            # padding pair (or a genuinely all-zero chunk 0, tap 0)
+                    assert (d & 0xFFFF) < slab // 8 and th < H and tw < K
+                    W[16 * t:16 * t + 16, th, tw, 8 * xc:8 * xc + 8] = frag
+                    seen[16 * t:16 * t + 16, th, tw, xc] += 1
+                    nonnull += 1
+    assert seen.max() <= 1
+    return W[:O, :, :, :I], nonnull
+
+
+@pytest.mark.parametrize("bo,bi", GRANS)
+@pytest.mark.parametrize("O,I,H,K", [(64, 64, 3, 3), (40, 24, 1, 1), (48, 320, 1, 1),
+                                     (32, 272, 3, 3), (1000, 40, 1, 1), (20, 16, 2, 1)])
+def test_step_section_holds_exactly_the_kept_weights(bo, bi, O, I, H, K):
+    c = _case(O, I, H, K, bo, bi, seed=O + I + bo + 1)
+    rp, ci, pl = bsp.bsp_pack(c.W, c.gamma, bo, bi, bsp.BSP_BF16)
+    plan = bsp.bsp_plan_build(rp, ci, pl, O, H, K, I, bo, bi)
+    assert plan.nbytes == bsp.bsp_plan_size(rp, ci, O, H, K, I, bo, bi, bsp.BSP_BF16)
+    hdr = plan[:32]
+    assert hdr[16] == min(-(-I // 8) * 8, 128 if H * K > 1 else 256)
+    assert hdr[17] == -(-(-(-I // 8)) // (hdr[16] // 8))
+    Wd, nonnull = _decode_steps(plan, O, H, K, I)
+    Wm = oracle.bf16_bits_rne(oracle.apply_mask(c.W, c.gamma, bo, bi)).reshape(c.W.shape)
+    assert (Wd == Wm).all()
+    # steps are the pairs of each (strip, slab) rounded up to fours, nothing more
+    nstrips, nslabs = hdr[8], hdr[17]
+    sp = plan[hdr[10]:hdr[10] + nstrips + 1]
+    xc = plan[hdr[11]:hdr[11] + hdr[9]]
+    want = 0
+    for t in range(nstrips):
+        cols = xc[sp[t]:sp[t + 1]] // (hdr[16] // 8)
+        for sl in range(nslabs):
+            want += -(-int((cols == sl).sum()) * H * K // 4)
+    assert hdr[18] == want
