@@ -49,11 +49,12 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_LIB_PATH):
+    path = os.environ.get("BSP_LIBRARY", _LIB_PATH)   # override: a differently built libbsp.so
+    if not os.path.exists(path):
         raise RuntimeError(
-            f"{_LIB_PATH} is missing: build it with "
+            f"{path} is missing: build it with "
             "`python -m paper_2407_09453_amd.build` (hipcc, gfx950)")
-    lib = ctypes.CDLL(_LIB_PATH)
+    lib = ctypes.CDLL(path)
     i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
     lib.bsp_strerror.restype = ctypes.c_char_p
     lib.bsp_strerror.argtypes = [ctypes.c_int]

@@ -16,13 +16,14 @@ def sources():
     return sorted(glob.glob(os.path.join(c, "*.cpp")) + glob.glob(os.path.join(c, "*.hip")))
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     """Always recompiles; returns the path of the shared library."""
+    LIB = out
     cmd = ["hipcc", "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
            # packed fp32 arithmetic is kept out of all device code
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
-           "-o", LIB + ".tmp"] + sources()
+           "-o", LIB + ".tmp"] + list(extra_flags) + sources()
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines()
                     if "packed-fp32-ops' is not a recognized feature" not in l)
@@ -35,4 +36,9 @@ def build(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("-o", "--out", default=LIB)
+    ap.add_argument("flags", nargs="*", help="extra hipcc flags, e.g. -DNAME")
+    a, unknown = ap.parse_known_args()
+    print(build(verbose=True, extra_flags=a.flags + unknown, out=os.path.abspath(a.out)))
