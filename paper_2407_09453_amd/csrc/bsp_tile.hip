@@ -1,18 +1,22 @@
 // LDS-tiled block-sparse implicit-GEMM convolution, bf16 in / fp32 accumulate.
 //
-// Persistent workgroups (4 waves) walk a list of work items; an item is a
-// TH x TW tile of output pixels of one image times a group of strips (16 output
-// channels each).  The input patch a tile needs (halo included, zero-filled
-// where it leaves the image, so padding costs no branches in the hot loop) is
-// staged into LDS one slab of input channels at a time and reused by every
-// strip of the group; the global loads for the NEXT slab or tile are issued
-// before the current one is computed and land in registers meanwhile.  A wave
-// takes a strip and walks its steps from the plan: per step one contiguous
-// 1 KB weight fragment (already in MFMA operand order, prefetched several
-// steps ahead) and, per 16-pixel tile, one 16-byte LDS read per lane gathered
-// by the step's (chunk, tap) descriptor, feeding v_mfma_f32_16x16x32_bf16.
-// Only kept blocks have steps (paper Section I, advantages 3-4); the epilogue
-// adds the fp32 bias and rounds once to bf16.
+// One workgroup (4 waves) owns a TH x TW tile of output pixels of one image and
+// a group of strips (16 output channels each).  The input patch the tile needs
+// (halo included, zero-filled where it leaves the image, so padding costs no
+// branches in the hot loop) is staged into LDS, one slab of input channels at
+// a time, and reused by every strip of the group.  A wave takes a strip and
+// walks its steps from the plan: per step one contiguous 1 KB weight fragment
+// (already in MFMA operand order, fetched four steps ahead) and, per 16-pixel
+// tile, one 16-byte LDS read per lane gathered by the step's (chunk, tap)
+// descriptor (issued one step ahead), feeding v_mfma_f32_16x16x32_bf16.  Only
+// kept blocks have steps (paper Section I, advantages 3-4); the epilogue adds
+// the fp32 bias and rounds once to bf16.
+//
+// Latency is what bounds small layers, so everything that does not depend on
+// the activations (step ranges, first weight fragments, bias) is requested
+// while the patch is still in flight, and a strip's successor is requested
+// before the strip's own results are stored (vector memory operations retire
+// in issue order, so a load issued behind a store would wait for it).
 #include "bsp_device.h"
 #include "bsp_launch.h"
 
@@ -21,6 +25,20 @@
 #include <mutex>
 
 namespace {
+
+// x / d for small x by one multiply-high: mul = floor(2^32 / d) + 1 (exact while x * d < 2^32).
+struct FastDiv {
+  uint32_t d, mul;
+};
+FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f;
+  f.d = d;
+  f.mul = d > 1 ? (uint32_t)((0x100000000ull / d) + 1) : 0u;
+  return f;
+}
+__device__ __forceinline__ uint32_t fdiv(uint32_t x, FastDiv f) {
+  return f.d == 1 ? x : __umulhi(x, f.mul);
+}
 
 struct TileCfg {
   int32_t TH, TW;            // output tile, pixels
@@ -32,14 +50,17 @@ struct TileCfg {
   int32_t pitch;             // LDS bytes per staged patch row (TPW*row_bytes + pad)
   int32_t tile2x8;           // 1: a 16-pixel tile is 2 rows x 8 columns, 0: 16 consecutive pixels
   int32_t slab, nslabs;      // channels per slab, slabs
-  int32_t spc;               // strips per work item (4 when nslabs > 1)
+  int32_t spc;               // strips per workgroup (4 when nslabs > 1)
   int32_t nstrips;
   int32_t ntiles;            // B * tiles_y * tiles_x
-  int32_t nitems;            // ntiles * strip groups
+  FastDiv d_pp, d_tpw, d_tw, d_tpr, d_ntiles, d_tpi, d_tiles_x;
 };
 
-constexpr int kStagePieces = 8;  // 16-byte pieces a thread keeps in flight while staging
-constexpr int kWDepth = 4;       // weight fragments prefetched ahead
+constexpr int kStageBatch = 8;  // 16-byte pieces a thread keeps in flight while staging
+#ifndef BSP_WDEPTH
+#define BSP_WDEPTH 8
+#endif
+constexpr int kWDepth = BSP_WDEPTH;  // weight fragments fetched ahead
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
@@ -49,188 +70,223 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
-// One step: a = weight fragment, d = its descriptor.  Every pixel tile of the
-// wave reads its 16 bytes of activations at the step's gathered offset.
+// The activations one step needs: every pixel tile of the wave reads its 16
+// bytes at the offset the step's descriptor d (chunk, tap) selects.
 template <int NT>
-__device__ __forceinline__ void mma_step(f32x4_t (&acc)[NT], const u32x4_t a, const int d,
-                                         const unsigned char* lds, const int (&base)[NT],
-                                         const int pitch, const int row_bytes) {
+__device__ __forceinline__ void load_b(u32x4_t (&b)[NT], const int d, const unsigned char* lds,
+                                       const int (&base)[NT], const int pitch,
+                                       const int row_bytes) {
   const int xoff = ((d >> 16) & 0xFF) * pitch + ((d >> 24) & 0xFF) * row_bytes + (d & 0xFFFF) * 16;
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const u32x4_t b = *(const u32x4_t*)(lds + base[nt] + xoff);
-    acc[nt] = mfma_bf16_16x16x32(a, b, acc[nt]);
+  for (int nt = 0; nt < NT; ++nt) b[nt] = *(const u32x4_t*)(lds + base[nt] + xoff);
+}
+template <int NT>
+__device__ __forceinline__ void do_mma(f32x4_t (&acc)[NT], const u32x4_t a,
+                                       const u32x4_t (&b)[NT]) {
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) acc[nt] = mfma_bf16_16x16x32(a, b[nt], acc[nt]);
+}
+
+// Ring of the next kWDepth (weight fragment, descriptor) pairs of a strip.
+struct Ring {
+  u32x4_t w[kWDepth];
+  int d[kWDepth];
+};
+__device__ __forceinline__ void ring_fill(Ring& r, const u32x4_t* __restrict__ wf,
+                                          const int32_t* __restrict__ xd, const int s0,
+                                          const int s1, const int lane, const int g) {
+  if (s0 >= s1) return;
+#pragma unroll
+  for (int u = 0; u < kWDepth; ++u) {
+    const int i = min(s0 + u, s1 - 1);
+    r.w[u] = wf[(int64_t)i * 64 + lane];
+    r.d[u] = xd[i * 4 + g];
   }
 }
 
-// All steps [s0, s1) of one (strip, slab); fragments are fetched kWDepth steps ahead.
+// All steps [s0, s1) of one (strip, slab); r holds steps s0 .. s0+kWDepth-1 on
+// entry.  The LDS reads of step s+1 are issued before the MFMAs of step s (two
+// register sets), and the slot a step frees is refilled with the fragment
+// kWDepth steps further on.
 template <int NT>
-__device__ __forceinline__ void run_steps(f32x4_t (&acc)[NT], const u32x4_t* __restrict__ wf,
+__device__ __forceinline__ void run_steps(f32x4_t (&acc)[NT], Ring& r,
+                                          const u32x4_t* __restrict__ wf,
                                           const int32_t* __restrict__ xd, const int s0,
                                           const int s1, const int lane, const int g,
                                           const unsigned char* lds, const int (&base)[NT],
                                           const int pitch, const int row_bytes) {
+  static_assert(kWDepth % 2 == 0, "two activation register sets alternate");
   if (s0 >= s1) return;
   const int last = s1 - 1;
-  u32x4_t w[kWDepth];
-  int d[kWDepth];
-#pragma unroll
-  for (int u = 0; u < kWDepth; ++u) {
-    const int i = min(s0 + u, last);
-    w[u] = wf[(int64_t)i * 64 + lane];
-    d[u] = xd[i * 4 + g];
-  }
+  u32x4_t b[2][NT];
+  load_b<NT>(b[0], r.d[0], lds, base, pitch, row_bytes);
   int s = s0;
   for (; s + kWDepth <= s1; s += kWDepth) {
 #pragma unroll
     for (int u = 0; u < kWDepth; ++u) {
-      const u32x4_t a = w[u];
-      const int dd = d[u];
+      const u32x4_t a = r.w[u];
+      load_b<NT>(b[(u + 1) & 1], r.d[(u + 1) % kWDepth], lds, base, pitch, row_bytes);
       const int i = min(s + u + kWDepth, last);
-      w[u] = wf[(int64_t)i * 64 + lane];
-      d[u] = xd[i * 4 + g];
-      mma_step<NT>(acc, a, dd, lds, base, pitch, row_bytes);
+      r.w[u] = wf[(int64_t)i * 64 + lane];
+      r.d[u] = xd[i * 4 + g];
+      do_mma<NT>(acc, a, b[u & 1]);
     }
   }
-  const int rem = s1 - s;
+  const int rem = s1 - s;  // fewer than kWDepth steps left; b[0] holds step s
 #pragma unroll
-  for (int u = 0; u < kWDepth - 1; ++u)
-    if (u < rem) mma_step<NT>(acc, w[u], d[u], lds, base, pitch, row_bytes);
+  for (int u = 0; u < kWDepth - 1; ++u) {
+    if (u < rem) {
+      if (u + 1 < rem) load_b<NT>(b[(u + 1) & 1], r.d[u + 1], lds, base, pitch, row_bytes);
+      do_mma<NT>(acc, r.w[u], b[u & 1]);
+    }
+  }
 }
 
 template <int NT>
-__global__ __launch_bounds__(256) void conv_tile_bf16(ConvParams p, TileCfg t) {
+__global__ __launch_bounds__(256, 2) void conv_tile_bf16(ConvParams p, TileCfg t) {
   extern __shared__ __align__(16) unsigned char lds[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int jn = lane & 15, g = lane >> 4;
+
+  // workgroup -> (strip group, image, tile)
+  const uint32_t bid = blockIdx.x;
+  const int sg = (int)fdiv(bid, t.d_ntiles);
+  const uint32_t tile = bid - (uint32_t)sg * t.ntiles;
+  const int n = (int)fdiv(tile, t.d_tpi);
+  const uint32_t trem = tile - (uint32_t)n * (t.tiles_y * t.tiles_x);
+  const int tyi = (int)fdiv(trem, t.d_tiles_x);
+  const int oy0 = tyi * t.TH, ox0 = (int)(trem - tyi * t.tiles_x) * t.TW;
+  const int iy_org = oy0 * p.sh - p.ph, ix_org = ox0 * p.sw - p.pw;
 
   const int32_t* plan = p.plan;
   const int32_t* slab_ptr = plan + plan[BSP_PLAN_OFF_SLAB_W];
   const int32_t* xdesc = plan + plan[BSP_PLAN_OFF_XDESC_W];
   const u32x4_t* wfrag = (const u32x4_t*)(plan + plan[BSP_PLAN_OFF_WFRAG_W]);
   const uint16_t* X = (const uint16_t*)p.X;
+  const int64_t img = (int64_t)n * p.L;
 
-  // ---- per-thread staging map: piece u of this thread -> LDS offset, patch pixel, channel
+  Ring ring;
+  int s0 = 0, s1 = 0;
+  float bias_next[4] = {0.f, 0.f, 0.f, 0.f};
+  // everything about (strip, slab) that can be requested before activations are there
+  auto request = [&](int strip, int sl) {
+    s0 = slab_ptr[strip * (t.nslabs + 1) + sl];
+    s1 = slab_ptr[strip * (t.nslabs + 1) + sl + 1];
+    ring_fill(ring, wfrag, xdesc, s0, s1, lane, g);
+    if (sl == 0) {
+      const int ch = strip * BSP_STRIP + 4 * g;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) bias_next[r] = (p.bias && ch + r < p.O) ? p.bias[ch + r] : 0.f;
+    }
+  };
+
+  // stage one slab: global -> registers -> LDS in batches; `early` runs once the
+  // first batch of loads is in flight
   const int PP = t.slab / BSP_CHUNK;  // 16-byte pieces per staged pixel
   const int npieces = t.TPH * t.TPW * PP;
-  int sdst[kStagePieces], sinfo[kStagePieces];
+  auto stage = [&](int sl, auto&& early) {
+    for (int b0 = 0; b0 < npieces; b0 += 256 * kStageBatch) {
+      u32x4_t sv[kStageBatch];
+      int sdst[kStageBatch];
 #pragma unroll
-  for (int u = 0; u < kStagePieces; ++u) {
-    const int idx = tid + u * 256;
-    const int pix = idx / PP, part = idx - pix * PP;
-    const int py = pix / t.TPW, px = pix - py * t.TPW;
-    sdst[u] = idx < npieces ? py * t.pitch + px * t.row_bytes + part * 16 : -1;
-    sinfo[u] = (py * t.gsh) | ((px * t.gsw) << 10) | (part << 20);
-  }
-  // ---- per-lane output pixel map
+      for (int u = 0; u < kStageBatch; ++u) {
+        const int idx = b0 + tid + u * 256;
+        const uint32_t pix = fdiv((uint32_t)idx, t.d_pp);
+        const int part = idx - (int)pix * PP;
+        const int py = (int)fdiv(pix, t.d_tpw);
+        const int px = (int)pix - py * t.TPW;
+        sdst[u] = idx < npieces ? py * t.pitch + px * t.row_bytes + part * 16 : -1;
+        const int iy = iy_org + py * t.gsh, ix = ix_org + px * t.gsw;
+        const int ch = sl * t.slab + part * BSP_CHUNK;
+        sv[u] = u32x4_t{0u, 0u, 0u, 0u};
+        if (sdst[u] >= 0 && (unsigned)iy < (unsigned)p.L && (unsigned)ix < (unsigned)p.J && ch < p.I)
+          sv[u] = *(const u32x4_t*)(X + ((img + iy) * p.J + ix) * p.I + ch);
+      }
+      if (b0 == 0) early();
+#pragma unroll
+      for (int u = 0; u < kStageBatch; ++u)
+        if (sdst[u] >= 0) *(u32x4_t*)(lds + sdst[u]) = sv[u];
+    }
+  };
+
+  int strip = sg * t.spc + wave;
+  const int strip_end = min((sg + 1) * t.spc, t.nstrips);
+  bool valid = strip < strip_end;
+
+  stage(0, [&] {
+    if (valid) request(strip, 0);
+  });
+
+  // per-lane output pixel map
   int pyx[NT], base[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    const int pi = nt * 16 + jn;
     int ty, tx;
     if (t.tile2x8) {  // pixel tiles are 2 rows x 8 columns
-      const int tpr = t.TW >> 3;
-      const int tr = nt / tpr, tc = nt - tr * tpr;
+      const int tr = (int)fdiv((uint32_t)nt, t.d_tpr), tc = nt - tr * (t.TW >> 3);
       ty = tr * 2 + (jn >> 3);
       tx = tc * 8 + (jn & 7);
     } else {
-      ty = pi / t.TW;
+      const int pi = nt * 16 + jn;
+      ty = (int)fdiv((uint32_t)pi, t.d_tw);
       tx = pi - ty * t.TW;
     }
     const bool in_tile = ty < t.TH && tx < t.TW;
     pyx[nt] = in_tile ? (ty | (tx << 16)) : -1;
     base[nt] = in_tile ? (ty * t.lsh) * t.pitch + (tx * t.lsw) * t.row_bytes : 0;
   }
-
-  // work units: (item, slab) pairs in order; unit -> where its patch comes from
-  const int tpi = t.tiles_y * t.tiles_x;
-  auto decode = [&](int item, int* n, int* oy0, int* ox0, int* sg) {
-    const int tile = item % t.ntiles;
-    *sg = item / t.ntiles;
-    *n = tile / tpi;
-    const int trem = tile - *n * tpi;
-    const int tyi = trem / t.tiles_x;
-    *oy0 = tyi * t.TH;
-    *ox0 = (trem - tyi * t.tiles_x) * t.TW;
-  };
-  u32x4_t sv[kStagePieces];
-  auto issue_loads = [&](int item, int sl) {
-    int n, oy0, ox0, sg;
-    decode(item, &n, &oy0, &ox0, &sg);
-    const int iy_org = oy0 * p.sh - p.ph, ix_org = ox0 * p.sw - p.pw;
-    const int64_t img = (int64_t)n * p.L;
-#pragma unroll
-    for (int u = 0; u < kStagePieces; ++u) {
-      sv[u] = u32x4_t{0u, 0u, 0u, 0u};
-      const int iy = iy_org + (sinfo[u] & 0x3FF), ix = ix_org + ((sinfo[u] >> 10) & 0x3FF);
-      const int ch = sl * t.slab + (sinfo[u] >> 20) * BSP_CHUNK;
-      if (sdst[u] >= 0 && (unsigned)iy < (unsigned)p.L && (unsigned)ix < (unsigned)p.J && ch < p.I)
-        sv[u] = *(const u32x4_t*)(X + ((img + iy) * p.J + ix) * p.I + ch);
-    }
-  };
-
   f32x4_t acc[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  int item = blockIdx.x;
-  if (item >= t.nitems) return;
-  issue_loads(item, 0);
+  __syncthreads();
+
   int sl = 0;
   while (true) {
-    // registers -> LDS (the previous unit's readers are past the barrier below)
-#pragma unroll
-    for (int u = 0; u < kStagePieces; ++u)
-      if (sdst[u] >= 0) *(u32x4_t*)(lds + sdst[u]) = sv[u];
-    __syncthreads();
-    // next unit's loads fly while this one is computed
-    int nitem = item, nsl = sl + 1;
-    if (nsl == t.nslabs) {
-      nsl = 0;
-      nitem = item + gridDim.x;
+    if (valid)
+      run_steps<NT>(acc, ring, wfrag, xdesc, s0, s1, lane, g, lds, base, t.pitch, t.row_bytes);
+    if (sl + 1 < t.nslabs) {  // same strip, next slab of input channels (spc == 4 here)
+      ++sl;
+      __syncthreads();  // everyone is done reading LDS before it is overwritten
+      stage(sl, [&] {
+        if (valid) request(strip, sl);
+      });
+      __syncthreads();
+      continue;
     }
-    const bool more = nitem < t.nitems;
-    if (more) issue_loads(nitem, nsl);
-
-    int n, oy0, ox0, sg;
-    decode(item, &n, &oy0, &ox0, &sg);
-    for (int si = wave; si < t.spc; si += 4) {
-      const int strip = sg * t.spc + si;
-      if (strip >= t.nstrips) break;
-      const int s0 = slab_ptr[strip * (t.nslabs + 1) + sl];
-      const int s1 = slab_ptr[strip * (t.nslabs + 1) + sl + 1];
-      run_steps<NT>(acc, wfrag, xdesc, s0, s1, lane, g, lds, base, t.pitch, t.row_bytes);
-      if (sl == t.nslabs - 1) {
-        // epilogue: lane holds channels 4g..4g+3 of pixel jn of every pixel tile
-        const int ch = strip * BSP_STRIP + 4 * g;
-        float bv[4];
+    // strip finished: request its successor first, then store
+    float bv[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) bv[r] = (p.bias && ch + r < p.O) ? p.bias[ch + r] : 0.f;
-        uint16_t* Y = (uint16_t*)p.Y;
+    for (int r = 0; r < 4; ++r) bv[r] = bias_next[r];
+    const int nstrip = strip + 4;
+    const bool nvalid = valid && nstrip < strip_end;
+    if (nvalid) request(nstrip, 0);
+    if (valid) {
+      // lane holds channels 4g..4g+3 of pixel jn of every pixel tile
+      const int ch = strip * BSP_STRIP + 4 * g;
+      uint16_t* Y = (uint16_t*)p.Y;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          const int oy = oy0 + (pyx[nt] & 0xFFFF), ox = ox0 + (pyx[nt] >> 16);
-          u32x2_t v;
-          v.x = pack_bf16x2(acc[nt][0] + bv[0], acc[nt][1] + bv[1]);
-          v.y = pack_bf16x2(acc[nt][2] + bv[2], acc[nt][3] + bv[3]);
-          acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-          if (pyx[nt] < 0 || oy >= p.M || ox >= p.N) continue;
-          const int64_t pid = ((int64_t)n * p.M + oy) * p.N + ox;
-          uint16_t* yp = Y + pid * p.O + ch;
-          if ((p.O % 4) == 0 && ch + 3 < p.O) {
-            *(u32x2_t*)yp = v;
-          } else {
-            if (ch + 0 < p.O) yp[0] = (uint16_t)(v.x & 0xFFFF);
-            if (ch + 1 < p.O) yp[1] = (uint16_t)(v.x >> 16);
-            if (ch + 2 < p.O) yp[2] = (uint16_t)(v.y & 0xFFFF);
-            if (ch + 3 < p.O) yp[3] = (uint16_t)(v.y >> 16);
-          }
+      for (int nt = 0; nt < NT; ++nt) {
+        const int oy = oy0 + (pyx[nt] & 0xFFFF), ox = ox0 + (pyx[nt] >> 16);
+        u32x2_t v;
+        v.x = pack_bf16x2(acc[nt][0] + bv[0], acc[nt][1] + bv[1]);
+        v.y = pack_bf16x2(acc[nt][2] + bv[2], acc[nt][3] + bv[3]);
+        acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (pyx[nt] < 0 || oy >= p.M || ox >= p.N) continue;
+        const int64_t pid = ((int64_t)n * p.M + oy) * p.N + ox;
+        uint16_t* yp = Y + pid * p.O + ch;
+        if ((p.O % 4) == 0 && ch + 3 < p.O) {
+          *(u32x2_t*)yp = v;
+        } else {
+          if (ch + 0 < p.O) yp[0] = (uint16_t)(v.x & 0xFFFF);
+          if (ch + 1 < p.O) yp[1] = (uint16_t)(v.x >> 16);
+          if (ch + 2 < p.O) yp[2] = (uint16_t)(v.y & 0xFFFF);
+          if (ch + 3 < p.O) yp[3] = (uint16_t)(v.y >> 16);
         }
       }
     }
-    if (!more) break;
-    item = nitem;
-    sl = nsl;
-    __syncthreads();  // everyone is done reading LDS before it is overwritten
+    if (!nvalid) break;
+    strip = nstrip;
   }
 }
 
@@ -294,8 +350,6 @@ bool choose_tile(const ConvParams& p, int slab, int* NT, TileCfg* out) {
         t.gsw = pointwise ? p.sw : 1;
         t.TPH = (t.TH - 1) * t.lsh + (pointwise ? 1 : p.H);
         t.TPW = (t.TW - 1) * t.lsw + (pointwise ? 1 : p.K);
-        if (t.TPH * t.gsh >= 1024 || t.TPW * t.gsw >= 1024) continue;
-        if ((int64_t)t.TPH * t.TPW * (slab / BSP_CHUNK) > 256 * kStagePieces) continue;
         t.tiles_y = (p.M + t.TH - 1) / t.TH;
         t.tiles_x = (p.N + t.TW - 1) / t.TW;
         // paddings: fewest conflicts first, then least LDS
@@ -329,19 +383,6 @@ bool choose_tile(const ConvParams& p, int slab, int* NT, TileCfg* out) {
         }
       }
   return best >= 0.0;
-}
-
-int device_cus() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-      cus = v;
-    else
-      cus = 256;
-  }
-  return cus;
 }
 
 }  // namespace
@@ -394,14 +435,21 @@ int bsp_launch_tile(const ConvParams& p_in, int dtype, hipStream_t st) {
   }
   t.spc = 4 * sw;
   const int64_t groups = (t.nstrips + t.spc - 1) / t.spc;
-  const int64_t nitems = ntiles * groups;
-  if (nitems > 0x7FFFFFFF) return BSP_ERR_SHAPE;
+  const int64_t nwg = ntiles * groups;
+  // the multiply-high divisions are exact only while dividend * divisor < 2^32
+  const int64_t npieces = (int64_t)t.TPH * t.TPW * (t.slab / BSP_CHUNK);
+  if (nwg >= (1 << 30) || nwg * ntiles >= (1ll << 32) ||
+      (npieces + 2048) * (t.slab / BSP_CHUNK) >= (1ll << 32) ||
+      (npieces + 2048) * t.TPW >= (1ll << 32))
+    return BSP_ERR_UNSUPPORTED;
   t.ntiles = (int32_t)ntiles;
-  t.nitems = (int32_t)nitems;
-  // persistent grid: at most two workgroups per CU, every workgroup the same item count
-  const int64_t max_wg = 2 * (int64_t)device_cus();
-  const int64_t per = (nitems + max_wg - 1) / max_wg;
-  const int64_t nwg = (nitems + per - 1) / per;
+  t.d_pp = make_fastdiv(t.slab / BSP_CHUNK);
+  t.d_tpw = make_fastdiv(t.TPW);
+  t.d_tw = make_fastdiv(t.TW);
+  t.d_tpr = make_fastdiv(t.TW >= 8 ? t.TW >> 3 : 1);
+  t.d_ntiles = make_fastdiv((uint32_t)ntiles);
+  t.d_tpi = make_fastdiv(t.tiles_y * t.tiles_x);
+  t.d_tiles_x = make_fastdiv(t.tiles_x);
   dim3 grid((unsigned)nwg), block(256);
   const size_t ldsb = (size_t)t.TPH * t.pitch;
   switch (NT) {
