@@ -140,6 +140,11 @@ typedef struct bsp_weights {
   const void* payload;      /* device [nnzb][bo][H][K][bi] */
   const void* plan;         /* device copy of bsp_plan_build's output */
   int64_t plan_bytes;
+  const void* plan_host;    /* optional: the HOST copy of the same plan bytes.  When given,
+                               the launcher reads the plan's step counts from it and can pick
+                               kernels that keep a layer's weights resident in LDS; when null
+                               only the streaming kernels are used.  Must stay valid during
+                               the call, not after. */
 } bsp_weights;
 
 /* Fully-connected layer Y[B][O] = X[B][I] . (Gamma W-bar)^T + bias, work done

@@ -37,7 +37,8 @@ class bsp_weights(ctypes.Structure):
                 ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("nnzb", ctypes.c_int64), ("row_ptr", ctypes.c_void_p),
                 ("col_idx", ctypes.c_void_p), ("payload", ctypes.c_void_p),
-                ("plan", ctypes.c_void_p), ("plan_bytes", ctypes.c_int64)]
+                ("plan", ctypes.c_void_p), ("plan_bytes", ctypes.c_int64),
+                ("plan_host", ctypes.c_void_p)]
 
 
 def lib_path() -> str:
@@ -241,7 +242,7 @@ class BspLayer:
         self.struct = bsp_weights(O, I, H, K, bo, bi, self.code, 0, self.nnzb,
                                   self.d_row_ptr.data_ptr(), self.d_col_idx.data_ptr(),
                                   self.d_payload.data_ptr(), self.d_plan.data_ptr(),
-                                  self.plan.nbytes)
+                                  self.plan.nbytes, self.plan.ctypes.data)
 
     def out_shape(self, B, L, J, stride, pad):
         M = (L + 2 * pad[0] - self.H) // stride[0] + 1

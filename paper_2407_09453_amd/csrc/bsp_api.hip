@@ -2,9 +2,22 @@
 #include "bsp.h"
 #include "bsp_launch.h"
 
+#include <cstdlib>
+#include <cstring>
 #include <limits>
 
 namespace {
+
+// BSP_KERNEL=general|tile|wres narrows the dispatcher's choice (tuning aid): "tile" skips
+// the weights-resident kernel, "general" skips both LDS-tiled kernels.
+int kernel_limit() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = std::getenv("BSP_KERNEL");
+    v = !e ? 2 : !std::strcmp(e, "general") ? 0 : !std::strcmp(e, "tile") ? 1 : 2;
+  }
+  return v;
+}
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -74,8 +87,11 @@ int bsp_conv2d(const bsp_weights* w, const void* X, const float* bias, void* Y, 
   ConvParams p;
   if (int rc = prepare(w, X, bias, Y, B, L, J, stride_h, stride_w, pad_h, pad_w, &p)) return rc;
   if (p.P == 0) return BSP_OK;
-  if (bsp_tile_supported(p, w->dtype)) {
-    const int rc = bsp_launch_tile(p, w->dtype, (hipStream_t)stream);
+  if (bsp_tile_supported(p, w->dtype) && kernel_limit() >= 1) {
+    int rc = BSP_ERR_UNSUPPORTED;
+    if (kernel_limit() >= 2) rc = bsp_launch_wres(p, w->dtype, w->plan_host, (hipStream_t)stream);
+    if (rc != BSP_ERR_UNSUPPORTED) return rc;
+    rc = bsp_launch_tile(p, w->dtype, (hipStream_t)stream);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
   }
   return bsp_launch_general(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);

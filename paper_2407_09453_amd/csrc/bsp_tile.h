@@ -1,0 +1,76 @@
+// Pieces shared by the LDS-tiled bf16 kernels: tile geometry, cheap integer
+// division, MFMA step helpers (library private).
+#ifndef BSP_TILE_H
+#define BSP_TILE_H
+
+#include "bsp_device.h"
+
+// x / d for small x by one multiply-high: mul = floor(2^32 / d) + 1 (exact while x * d < 2^32).
+struct FastDiv {
+  uint32_t d, mul;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f;
+  f.d = d;
+  f.mul = d > 1 ? (uint32_t)((0x100000000ull / d) + 1) : 0u;
+  return f;
+}
+__device__ __forceinline__ uint32_t fdiv(uint32_t x, FastDiv f) {
+  return f.d == 1 ? x : __umulhi(x, f.mul);
+}
+
+struct TileCfg {
+  int32_t TH, TW;            // output tile, pixels
+  int32_t TPH, TPW;          // staged input patch, pixels
+  int32_t lsh, lsw;          // LDS pixels per output pixel step
+  int32_t gsh, gsw;          // input pixels per LDS pixel step
+  int32_t tiles_y, tiles_x;  // tiles per image
+  int32_t row_bytes;         // LDS bytes per staged pixel (slab*2 + pad)
+  int32_t pitch;             // LDS bytes per staged patch row (TPW*row_bytes + pad)
+  int32_t tile2x8;           // 1: a 16-pixel tile is 2 rows x 8 columns, 0: 16 consecutive pixels
+  int32_t slab, nslabs;      // channels per slab, slabs
+  int32_t spc;               // strips per workgroup (4 when nslabs > 1)
+  int32_t nstrips;
+  int32_t ntiles;            // B * tiles_y * tiles_x
+  FastDiv d_pp, d_tpw, d_tw, d_tpr, d_ntiles, d_tpi, d_tiles_x;
+};
+
+constexpr int kStageBatch = 8;  // 16-byte pieces a thread keeps in flight while staging
+#ifndef BSP_WDEPTH
+#define BSP_WDEPTH 8
+#endif
+constexpr int kWDepth = BSP_WDEPTH;  // weight fragments fetched ahead
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+// two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// The activations one step needs: every pixel tile of the wave reads its 16
+// bytes at the offset the step's descriptor d (chunk, tap) selects.
+template <int NT>
+__device__ __forceinline__ void load_b(u32x4_t (&b)[NT], const int d, const unsigned char* lds,
+                                       const int (&base)[NT], const int pitch,
+                                       const int row_bytes) {
+  const int xoff = ((d >> 16) & 0xFF) * pitch + ((d >> 24) & 0xFF) * row_bytes + (d & 0xFFFF) * 16;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) b[nt] = *(const u32x4_t*)(lds + base[nt] + xoff);
+}
+template <int NT>
+__device__ __forceinline__ void do_mma(f32x4_t (&acc)[NT], const u32x4_t a,
+                                       const u32x4_t (&b)[NT]) {
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) acc[nt] = mfma_bf16_16x16x32(a, b[nt], acc[nt]);
+}
+
+
+// Pick the output tile for a layer (most useful pixels per MFMA pixel slot,
+// least halo, no LDS bank conflicts) and the LDS paddings; false if nothing fits
+// in max_lds bytes.  Fills everything in *out except spc, ntiles and the dividers.
+bool bsp_choose_tile(const ConvParams& p, int slab, int64_t max_lds, int max_pieces, int* NT,
+                     TileCfg* out);
+
+#endif

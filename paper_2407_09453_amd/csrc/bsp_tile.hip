@@ -17,75 +17,14 @@
 // while the patch is still in flight, and a strip's successor is requested
 // before the strip's own results are stored (vector memory operations retire
 // in issue order, so a load issued behind a store would wait for it).
-#include "bsp_device.h"
 #include "bsp_launch.h"
+#include "bsp_tile.h"
 
 #include <array>
 #include <map>
 #include <mutex>
 
 namespace {
-
-// x / d for small x by one multiply-high: mul = floor(2^32 / d) + 1 (exact while x * d < 2^32).
-struct FastDiv {
-  uint32_t d, mul;
-};
-FastDiv make_fastdiv(uint32_t d) {
-  FastDiv f;
-  f.d = d;
-  f.mul = d > 1 ? (uint32_t)((0x100000000ull / d) + 1) : 0u;
-  return f;
-}
-__device__ __forceinline__ uint32_t fdiv(uint32_t x, FastDiv f) {
-  return f.d == 1 ? x : __umulhi(x, f.mul);
-}
-
-struct TileCfg {
-  int32_t TH, TW;            // output tile, pixels
-  int32_t TPH, TPW;          // staged input patch, pixels
-  int32_t lsh, lsw;          // LDS pixels per output pixel step
-  int32_t gsh, gsw;          // input pixels per LDS pixel step
-  int32_t tiles_y, tiles_x;  // tiles per image
-  int32_t row_bytes;         // LDS bytes per staged pixel (slab*2 + pad)
-  int32_t pitch;             // LDS bytes per staged patch row (TPW*row_bytes + pad)
-  int32_t tile2x8;           // 1: a 16-pixel tile is 2 rows x 8 columns, 0: 16 consecutive pixels
-  int32_t slab, nslabs;      // channels per slab, slabs
-  int32_t spc;               // strips per workgroup (4 when nslabs > 1)
-  int32_t nstrips;
-  int32_t ntiles;            // B * tiles_y * tiles_x
-  FastDiv d_pp, d_tpw, d_tw, d_tpr, d_ntiles, d_tpi, d_tiles_x;
-};
-
-constexpr int kStageBatch = 8;  // 16-byte pieces a thread keeps in flight while staging
-#ifndef BSP_WDEPTH
-#define BSP_WDEPTH 8
-#endif
-constexpr int kWDepth = BSP_WDEPTH;  // weight fragments fetched ahead
-
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-typedef __attribute__((ext_vector_type(2))) float f32x2_t;
-// two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  const f32x2_t v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-}
-
-// The activations one step needs: every pixel tile of the wave reads its 16
-// bytes at the offset the step's descriptor d (chunk, tap) selects.
-template <int NT>
-__device__ __forceinline__ void load_b(u32x4_t (&b)[NT], const int d, const unsigned char* lds,
-                                       const int (&base)[NT], const int pitch,
-                                       const int row_bytes) {
-  const int xoff = ((d >> 16) & 0xFF) * pitch + ((d >> 24) & 0xFF) * row_bytes + (d & 0xFFFF) * 16;
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) b[nt] = *(const u32x4_t*)(lds + base[nt] + xoff);
-}
-template <int NT>
-__device__ __forceinline__ void do_mma(f32x4_t (&acc)[NT], const u32x4_t a,
-                                       const u32x4_t (&b)[NT]) {
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) acc[nt] = mfma_bf16_16x16x32(a, b[nt], acc[nt]);
-}
 
 // Ring of the next kWDepth (weight fragment, descriptor) pairs of a strip.
 struct Ring {
@@ -320,11 +259,12 @@ int conflict_excess(const TileCfg& t, int NT) {
   return excess;
 }
 
-constexpr int kMaxLds = 64 * 1024;
-
 // Pick the output tile: most useful pixels per MFMA pixel slot, least halo, no
 // LDS bank conflicts; then the LDS paddings that achieve the latter.
-bool choose_tile(const ConvParams& p, int slab, int* NT, TileCfg* out) {
+}  // namespace
+
+bool bsp_choose_tile(const ConvParams& p, int slab, int64_t max_lds, int max_pieces, int* NT,
+                     TileCfg* out) {
   const bool pointwise = p.H == 1 && p.K == 1;
   static const int nts[] = {4, 7, 8};
   static const int tws[] = {4, 7, 8, 14, 16, 24, 28, 32, 56, 64, 112, 128};
@@ -352,6 +292,7 @@ bool choose_tile(const ConvParams& p, int slab, int* NT, TileCfg* out) {
         t.TPW = (t.TW - 1) * t.lsw + (pointwise ? 1 : p.K);
         t.tiles_y = (p.M + t.TH - 1) / t.TH;
         t.tiles_x = (p.N + t.TW - 1) / t.TW;
+        if (max_pieces > 0 && (int64_t)t.TPH * t.TPW * (slab / BSP_CHUNK) > max_pieces) continue;
         // paddings: fewest conflicts first, then least LDS
         int best_ex = 1 << 30;
         int64_t best_lds = 0;
@@ -361,7 +302,7 @@ bool choose_tile(const ConvParams& p, int slab, int* NT, TileCfg* out) {
             t.row_bytes = slab * 2 + rp;
             t.pitch = t.TPW * t.row_bytes + pp;
             const int64_t ldsb = (int64_t)t.TPH * t.pitch;
-            if (ldsb > kMaxLds) continue;
+            if (ldsb > max_lds) continue;
             const int ex = conflict_excess(t, nt);
             if (ex < best_ex || (ex == best_ex && ldsb < best_lds)) {
               best_ex = ex;
@@ -384,8 +325,6 @@ bool choose_tile(const ConvParams& p, int slab, int* NT, TileCfg* out) {
       }
   return best >= 0.0;
 }
-
-}  // namespace
 
 bool bsp_tile_supported(const ConvParams& p, int dtype) {
   return dtype == BSP_BF16 && (p.I % 8) == 0 && p.H <= 255 && p.K <= 255;
@@ -414,7 +353,7 @@ int bsp_launch_tile(const ConvParams& p_in, int dtype, hipStream_t st) {
       t.slab = bsp_slab_channels(p.I, p.H, p.K);
       t.nslabs = ((p.I + 7) / 8 + t.slab / 8 - 1) / (t.slab / 8);
       t.nstrips = (p.O + BSP_STRIP - 1) / BSP_STRIP;
-      if (!choose_tile(p, t.slab, &NT, &t)) NT = 0;
+      if (!bsp_choose_tile(p, t.slab, 64 * 1024, 0, &NT, &t)) NT = 0;
       if (memo.size() > 4096) memo.clear();
       it = memo.emplace(key, std::make_pair(NT, t)).first;
     }
