@@ -46,11 +46,81 @@ def pick_case(name: str):
     if name == "c0":
         return next(config_cases(0)), "config0: FC fp32 64x256 -> 256, 8x8 blocks, Bernoulli(0.5)"
     if name.startswith("c2"):
-        want = name[3:] if len(name) > 2 else "8x8.d0.5"
+        want = name[3:] if len(name) > 3 else "8x8.d0.5"
         for c in config_cases(2):
             if c.name.endswith(want):
                 return c, f"config2: conv1x1 256->1024 @14x14 batch 32 bf16, {want}"
     raise SystemExit(f"unknown workload {name}")
+
+
+def bench_network(args, net: str) -> int:
+    """Per-layer timing of a whole network-shaped stack: every layer on its own
+    resident N(0,1) input (layers are independent: glue such as pooling is not
+    part of the path), kept-block mask vs all-ones mask through the same
+    dispatcher.  A step is one launch of every layer."""
+    import torch
+    import paper_2407_09453_amd as bsp
+    from synthetic import config_cases
+
+    dev = torch.device("cuda:0")
+    cfg = 3 if net == "resnet50" else 4
+    stream = torch.cuda.current_stream(dev)
+    rows = []
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(2407)
+    for c in config_cases(cfg, draw_x=False):
+        if c.meta.get("net") != net:
+            continue
+        sparse = bsp.BspLayer(c.W, c.gamma, c.bo, c.bi, c.dtype, bias=c.bias)
+        dense = bsp.BspLayer(c.W, np.ones_like(c.gamma), c.bo, c.bi, c.dtype, bias=c.bias)
+        X = torch.randn((c.B, c.L, c.J, c.I), device=dev, generator=gen).to(torch.bfloat16)
+        Y = torch.empty(sparse.out_shape(c.B, c.L, c.J, c.stride, c.pad), dtype=torch.bfloat16,
+                        device=dev)
+        res = {}
+        for name, lay in (("sparse", sparse), ("dense", dense)):
+            for _ in range(args.warmup):
+                lay.conv2d(X, c.stride, c.pad, out=Y, general=args.general)
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                   for _ in range(args.steps)]
+            torch.cuda.synchronize()
+            for a, b in evs:
+                a.record(stream)
+                lay.conv2d(X, c.stride, c.pad, out=Y, general=args.general)
+                b.record(stream)
+            torch.cuda.synchronize()
+            res[name] = float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e3
+        fl = flops_nonzero(c, sparse.nnzb)
+        by = algorithmic_bytes(c, sparse.nnzb)
+        rows.append({"layer": c.name, "I": c.I, "O": c.O, "HxK": f"{c.H}x{c.K}", "in": f"{c.L}x{c.J}",
+                     "stride": c.stride[0], "nnzb": sparse.nnzb, "blocks": int(c.gamma.size),
+                     "us": round(res["sparse"], 2), "us_dense_mask": round(res["dense"], 2),
+                     "speedup": round(res["dense"] / res["sparse"], 3),
+                     "TFLOPs_nz": round(fl / res["sparse"] / 1e6, 2),
+                     "GBs": round(by / res["sparse"] / 1e3, 1), "flops_nz": fl, "bytes": by})
+        del sparse, dense, X, Y
+    tot = sum(r["us"] for r in rows)
+    totd = sum(r["us_dense_mask"] for r in rows)
+    fl = sum(r["flops_nz"] for r in rows)
+    print(f"{'layer':28s} {'I':>5s} {'O':>5s} {'HxK':>4s} {'in':>8s} {'us':>8s} {'dense':>8s} {'x':>6s} "
+          f"{'TF/s':>7s} {'GB/s':>7s}", file=sys.stderr)
+    for r in rows:
+        print(f"{r['layer']:28s} {r['I']:5d} {r['O']:5d} {r['HxK']:>4s} {r['in']:>8s} {r['us']:8.1f} "
+              f"{r['us_dense_mask']:8.1f} {r['speedup']:6.2f} {r['TFLOPs_nz']:7.1f} {r['GBs']:7.0f}",
+              file=sys.stderr)
+    out = {
+        "metric": "effective nonzero TFLOP/s (2*P*nnzb*bo*bi*H*K / t), 50% 8x8 block-sparse layers",
+        "value": round(fl / tot / 1e6, 4), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(tot / 1e3, 6), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{net}-shaped conv+FC stack, batch {rows and 32 if net == 'resnet50' else 16}, "
+                               "8x8 blocks, half the blocks kept per layer (first conv dense)",
+                   "layers": len(rows), "timing": "median of per-launch HIP event pairs, summed over layers"},
+        "speedup_vs_dense_mask": round(totd / tot, 4),
+        "dense_mask_ms_per_step": round(totd / 1e3, 6),
+        "layers": rows,
+    }
+    print(json.dumps(out))
+    return 0
 
 
 def main() -> int:
@@ -58,7 +128,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="c1")
+    ap.add_argument("--workload", default="c1",
+                    help="c1 (default), c0, c2:<bo>x<bi>.d<density>, resnet50, vgg16, inception_v3")
     ap.add_argument("--sets", type=int, default=0,
                     help="distinct X/Y buffer sets cycled through (0 = enough to exceed 256 MB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -68,6 +139,10 @@ def main() -> int:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); "
               "multi-GPU figures are not produced", file=sys.stderr)
         return 2
+    if args.workload in ("resnet50", "vgg16", "inception_v3"):
+        if args.steps == 400:
+            args.steps, args.warmup = 30, 5
+        return bench_network(args, args.workload)
 
     import torch
     import paper_2407_09453_amd as bsp

@@ -24,6 +24,10 @@
 #include <map>
 #include <mutex>
 
+#ifndef BSP_TILE_OCC
+#define BSP_TILE_OCC 2
+#endif
+
 namespace {
 
 // Ring of the next kWDepth (weight fragment, descriptor) pairs of a strip.
@@ -82,7 +86,7 @@ __device__ __forceinline__ void run_steps(f32x4_t (&acc)[NT], Ring& r,
 }
 
 template <int NT>
-__global__ __launch_bounds__(256, 2) void conv_tile_bf16(ConvParams p, TileCfg t) {
+__global__ __launch_bounds__(256, BSP_TILE_OCC) void conv_tile_bf16(ConvParams p, TileCfg t) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -270,6 +274,9 @@ bool bsp_choose_tile(const ConvParams& p, int slab, int64_t max_lds, int max_pie
   static const int tws[] = {4, 7, 8, 14, 16, 24, 28, 32, 56, 64, 112, 128};
   double best = -1.0;
   for (int nt : nts)
+#ifdef BSP_FORCE_NT
+    if (nt == BSP_FORCE_NT)
+#endif
     for (int tw : tws)
       for (int mode = 0; mode < 2; ++mode) {
         TileCfg t = *out;

@@ -31,6 +31,10 @@ SHAPES = [
     (1, 9, 9, 512, 32, 1, 1, (2, 2), (0, 0)),       # strided pointwise, two slabs
     (1, 20, 33, 64, 64, 3, 3, (1, 1), (1, 1)),      # tiles hang over both image edges
     (1, 8, 8, 16, 16, 1, 1, (1, 1), (1, 1)),        # padded pointwise
+    (16, 1, 1, 1024, 200, 1, 1, (1, 1), (0, 0)),    # FC, one batch tile, ragged strip count
+    (33, 1, 1, 520, 64, 1, 1, (1, 1), (0, 0)),      # FC, batch over three tiles
+    (2, 5, 5, 256, 48, 1, 1, (1, 1), (0, 0)),       # 50 pixels: weight-streaming path
+    (64, 1, 1, 4096, 32, 1, 1, (1, 1), (0, 0)),     # FC, long strips split over waves
 ]
 
 
