@@ -70,7 +70,9 @@ __device__ __forceinline__ void do_mma(f32x4_t (&acc)[NT], const u32x4_t a,
 // Pick the output tile for a layer (most useful pixels per MFMA pixel slot,
 // least halo, no LDS bank conflicts) and the LDS paddings; false if nothing fits
 // in max_lds bytes.  Fills everything in *out except spc, ntiles and the dividers.
-bool bsp_choose_tile(const ConvParams& p, int slab, int64_t max_lds, int max_pieces, int* NT,
-                     TileCfg* out);
+// The tile holds nt_scale * NT pixel tiles (nt_scale waves share a strip) and the LDS
+// budget also has to cover out_row_bytes per output pixel (results staging), if any.
+bool bsp_choose_tile(const ConvParams& p, int slab, int64_t max_lds, int max_pieces, int nt_scale,
+                     int out_row_bytes, int* NT, TileCfg* out);
 
 #endif

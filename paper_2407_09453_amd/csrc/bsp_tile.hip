@@ -267,18 +267,16 @@ int conflict_excess(const TileCfg& t, int NT) {
 // LDS bank conflicts; then the LDS paddings that achieve the latter.
 }  // namespace
 
-bool bsp_choose_tile(const ConvParams& p, int slab, int64_t max_lds, int max_pieces, int* NT,
-                     TileCfg* out) {
+bool bsp_choose_tile(const ConvParams& p, int slab, int64_t max_lds, int max_pieces, int nt_scale,
+                     int out_row_bytes, int* NT, TileCfg* out) {
   const bool pointwise = p.H == 1 && p.K == 1;
   static const int nts[] = {4, 7, 8};
-  static const int tws[] = {4, 7, 8, 14, 16, 24, 28, 32, 56, 64, 112, 128};
+  static const int tws[] = {4, 7, 8, 14, 16, 24, 28, 32, 56, 64, 112, 128, 224, 256};
   double best = -1.0;
-  for (int nt : nts)
-#ifdef BSP_FORCE_NT
-    if (nt == BSP_FORCE_NT)
-#endif
+  for (int nt1 : nts)
     for (int tw : tws)
       for (int mode = 0; mode < 2; ++mode) {
+        const int nt = nt1 * nt_scale;
         TileCfg t = *out;
         t.tile2x8 = mode;
         if (tw > nt * 16) continue;
@@ -308,7 +306,7 @@ bool bsp_choose_tile(const ConvParams& p, int slab, int64_t max_lds, int max_pie
           for (int pp = 0; pp <= 240; pp += 16) {
             t.row_bytes = slab * 2 + rp;
             t.pitch = t.TPW * t.row_bytes + pp;
-            const int64_t ldsb = (int64_t)t.TPH * t.pitch;
+            const int64_t ldsb = (int64_t)t.TPH * t.pitch + (int64_t)nt * 16 * out_row_bytes;
             if (ldsb > max_lds) continue;
             const int ex = conflict_excess(t, nt);
             if (ex < best_ex || (ex == best_ex && ldsb < best_lds)) {
@@ -326,7 +324,7 @@ bool bsp_choose_tile(const ConvParams& p, int slab, int64_t max_lds, int max_pie
         const double score = util - 0.02 * halo - 0.05 * best_ex / nt + 0.001 * nt;
         if (score > best) {
           best = score;
-          *NT = nt;
+          *NT = nt1;
           *out = t;
         }
       }
@@ -360,7 +358,7 @@ int bsp_launch_tile(const ConvParams& p_in, int dtype, hipStream_t st) {
       t.slab = bsp_slab_channels(p.I, p.H, p.K);
       t.nslabs = ((p.I + 7) / 8 + t.slab / 8 - 1) / (t.slab / 8);
       t.nstrips = (p.O + BSP_STRIP - 1) / BSP_STRIP;
-      if (!bsp_choose_tile(p, t.slab, 64 * 1024, 0, &NT, &t)) NT = 0;
+      if (!bsp_choose_tile(p, t.slab, 64 * 1024, 0, 1, 0, &NT, &t)) NT = 0;
       if (memo.size() > 4096) memo.clear();
       it = memo.emplace(key, std::make_pair(NT, t)).first;
     }

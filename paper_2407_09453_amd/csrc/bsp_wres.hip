@@ -31,7 +31,8 @@ struct WresCfg {
   FastDiv d_groups;
 };
 
-constexpr int kWBatch = 20;  // weight fragments a lane keeps in flight while copying
+constexpr int kWBatch = 12;   // per wave; the waves sharing a strip split its fragments
+constexpr int kPH = 2;        // waves per strip, each taking a share of the tile's pixel tiles  // weight fragments a lane keeps in flight while copying
 
 template <int NT>
 __device__ __forceinline__ void load_b_at(u32x4_t (&b)[NT], const int xoff,
@@ -40,11 +41,14 @@ __device__ __forceinline__ void load_b_at(u32x4_t (&b)[NT], const int xoff,
   for (int nt = 0; nt < NT; ++nt) b[nt] = *(const u32x4_t*)(lds + base[nt] + xoff);
 }
 
-template <int NT>
-__global__ __launch_bounds__(256, 1) void conv_wres_bf16(ConvParams p, TileCfg t, WresCfg c) {
+template <int NT, int PH>
+__global__ __launch_bounds__(256 * PH, 1) void conv_wres_bf16(ConvParams p, TileCfg t, WresCfg c) {
+  constexpr int kThreads = 256 * PH;
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave = wave_all & 3;   // which strip of the group
+  const int half = wave_all >> 2;  // which share of the tile's pixel tiles
   const int jn = lane & 15, g = lane >> 4;
 
   const uint32_t bid = blockIdx.x;
@@ -62,7 +66,7 @@ __global__ __launch_bounds__(256, 1) void conv_wres_bf16(ConvParams p, TileCfg t
   int sdst[kStageBatch], sinfo[kStageBatch], soff[kStageBatch];
 #pragma unroll
   for (int u = 0; u < kStageBatch; ++u) {
-    const int idx = tid + u * 256;
+    const int idx = tid + u * kThreads;
     const uint32_t pix = fdiv((uint32_t)idx, t.d_pp);
     const int part = idx - (int)pix * PP;
     const int py = (int)fdiv(pix, t.d_tpw);
@@ -127,26 +131,27 @@ __global__ __launch_bounds__(256, 1) void conv_wres_bf16(ConvParams p, TileCfg t
     int dsc[2] = {0, 0};  // descriptors of (step, group) pairs lane and lane + 64
 #pragma unroll
     for (int k = 0; k < 2; ++k)
-      if (lane + 64 * k < nst * 4) dsc[k] = xdesc[s0 * 4 + lane + 64 * k];
+      if (half == 0 && lane + 64 * k < nst * 4) dsc[k] = xdesc[s0 * 4 + lane + 64 * k];
 #pragma unroll
     for (int r = 0; r < 4; ++r) bv[r] = (p.bias && ch + r < p.O) ? p.bias[ch + r] : 0.f;
-    for (int b0 = 0; b0 < nst; b0 += kWBatch) {
+    // the PH waves that share this strip copy alternate fragments
+    for (int b0 = half; b0 < nst; b0 += kWBatch * PH) {
       u32x4_t wv[kWBatch];
 #pragma unroll
       for (int u = 0; u < kWBatch; ++u)
-        if (b0 + u < nst) wv[u] = wfrag[(int64_t)(s0 + b0 + u) * 64 + lane];
+        if (b0 + u * PH < nst) wv[u] = wfrag[(int64_t)(s0 + b0 + u * PH) * 64 + lane];
 #pragma unroll
       for (int u = 0; u < kWBatch; ++u)
-        if (b0 + u < nst) wl[(b0 + u) * 64 + lane] = wv[u];
+        if (b0 + u * PH < nst) wl[(b0 + u * PH) * 64 + lane] = wv[u];
     }
 #pragma unroll
     for (int k = 0; k < 2; ++k)
-      if (lane + 64 * k < nst * 4) {
+      if (half == 0 && lane + 64 * k < nst * 4) {
         const int d = dsc[k];
         xo[lane + 64 * k] =
             ((d >> 16) & 0xFF) * t.pitch + ((d >> 24) & 0xFF) * t.row_bytes + (d & 0xFFFF) * 16;
       }
-    for (int i = lane + 128; i < nst * 4; i += 64) {  // strips longer than 32 steps
+    for (int i = lane + 128; half == 0 && i < nst * 4; i += 64) {  // strips longer than 32 steps
       const int d = xdesc[s0 * 4 + i];
       xo[i] = ((d >> 16) & 0xFF) * t.pitch + ((d >> 24) & 0xFF) * t.row_bytes + (d & 0xFFFF) * 16;
     }
@@ -156,13 +161,14 @@ __global__ __launch_bounds__(256, 1) void conv_wres_bf16(ConvParams p, TileCfg t
   int base[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
+    const int gt = half * NT + nt;  // pixel tile within the workgroup's tile
     int ty, tx;
     if (t.tile2x8) {
-      const int tr = (int)fdiv((uint32_t)nt, t.d_tpr), tc = nt - tr * (t.TW >> 3);
+      const int tr = (int)fdiv((uint32_t)gt, t.d_tpr), tc = gt - tr * (t.TW >> 3);
       ty = tr * 2 + (jn >> 3);
       tx = tc * 8 + (jn & 7);
     } else {
-      const int pi = nt * 16 + jn;
+      const int pi = gt * 16 + jn;
       ty = (int)fdiv((uint32_t)pi, t.d_tw);
       tx = pi - ty * t.TW;
     }
@@ -176,11 +182,11 @@ __global__ __launch_bounds__(256, 1) void conv_wres_bf16(ConvParams p, TileCfg t
   // ---- cooperative store map: the tile's results leave LDS as whole 16-byte pieces, eight
   // consecutive lanes covering the 64 output channels (128 bytes) of one pixel
   constexpr int kOutRow = 4 * BSP_STRIP * 2 + 16;        // bytes per pixel in the staging tile
-  constexpr int kOutPieces = (NT * 16 * 8 + 255) / 256;  // pieces per thread
+  constexpr int kOutPieces = (NT * PH * 16 * 8 + kThreads - 1) / kThreads;  // pieces per thread
   int csrc[kOutPieces], cpyx[kOutPieces], coff[kOutPieces];
 #pragma unroll
   for (int k = 0; k < kOutPieces; ++k) {
-    const int q = tid + k * 256;
+    const int q = tid + k * kThreads;
     const int pi = q >> 3, part = q & 7;
     const int nt = pi >> 4, j = pi & 15;
     int ty, tx;
@@ -192,13 +198,13 @@ __global__ __launch_bounds__(256, 1) void conv_wres_bf16(ConvParams p, TileCfg t
       ty = (int)fdiv((uint32_t)pi, t.d_tw);
       tx = pi - ty * t.TW;
     }
-    const bool live = nt < NT && ty < t.TH && tx < t.TW && sg * 64 + part * 8 < p.O;
+    const bool live = nt < NT * PH && ty < t.TH && tx < t.TW && sg * 64 + part * 8 < p.O;
     csrc[k] = c.obuf_off + pi * kOutRow + part * 16;
     cpyx[k] = live ? (ty | (tx << 16)) : -1;
     coff[k] = (ty * p.N + tx) * p.O + sg * 64 + part * 8;
   }
   // where this lane's four channels of pixel jn of pixel tile nt go in the staging tile
-  const int orow = c.obuf_off + jn * kOutRow + wave * (BSP_STRIP * 2) + g * 8;
+  const int orow = c.obuf_off + (half * NT * 16 + jn) * kOutRow + wave * (BSP_STRIP * 2) + g * 8;
 
   store_patch();
   __syncthreads();
@@ -282,18 +288,18 @@ int device_cus() {
 
 constexpr int64_t kLdsPerCu = 160 * 1024;
 
-template <int NT>
+template <int NT, int PH>
 int launch(const ConvParams& p, const TileCfg& t, const WresCfg& c, dim3 grid, size_t ldsb,
            hipStream_t st) {
   static bool raised = false;  // dynamic LDS above 64 KB has to be allowed once per kernel
   if (!raised) {
-    if (hipFuncSetAttribute((const void*)conv_wres_bf16<NT>,
+    if (hipFuncSetAttribute((const void*)conv_wres_bf16<NT, PH>,
                             hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)kLdsPerCu) != hipSuccess)
       return BSP_ERR_HIP;
     raised = true;
   }
-  hipLaunchKernelGGL(conv_wres_bf16<NT>, grid, dim3(256), ldsb, st, p, t, c);
+  hipLaunchKernelGGL((conv_wres_bf16<NT, PH>), grid, dim3(256 * PH), ldsb, st, p, t, c);
   return hipGetLastError() == hipSuccess ? BSP_OK : BSP_ERR_HIP;
 }
 
@@ -334,10 +340,10 @@ int bsp_launch_wres(const ConvParams& p_in, int dtype, const void* plan_host, hi
       t.nslabs = 1;
       t.nstrips = (p.O + BSP_STRIP - 1) / BSP_STRIP;
       // two workgroups per CU if the patch leaves room for that, else one
-      const int64_t obuf_max = 8 * 16 * (4 * BSP_STRIP * 2 + 16);
-      if (!bsp_choose_tile(p, t.slab, kLdsPerCu / 2 - wbytes - obuf_max, 256 * kStageBatch, &NT,
-                           &t) &&
-          !bsp_choose_tile(p, t.slab, kLdsPerCu - wbytes - obuf_max, 256 * kStageBatch, &NT, &t))
+      // eight waves (two per strip) and one workgroup per CU; the LDS left after the
+      // weights holds the patch and the results staging tile
+      if (!bsp_choose_tile(p, t.slab, kLdsPerCu - wbytes, 512 * kStageBatch, kPH,
+                           4 * BSP_STRIP * 2 + 16, &NT, &t))
         NT = 0;
       if (memo.size() > 4096) memo.clear();
       it = memo.emplace(key, std::make_pair(NT, t)).first;
@@ -350,17 +356,17 @@ int bsp_launch_wres(const ConvParams& p_in, int dtype, const void* plan_host, hi
   const int64_t ntiles = (int64_t)p.B * t.tiles_y * t.tiles_x;
   c.xbuf_bytes = (t.TPH * t.pitch + 15) & ~15;
   c.obuf_off = c.xbuf_bytes + (int32_t)wbytes;
-  const size_t ldsb = (size_t)c.obuf_off + (size_t)NT * 16 * (4 * BSP_STRIP * 2 + 16);
+  const size_t ldsb = (size_t)c.obuf_off + (size_t)NT * kPH * 16 * (4 * BSP_STRIP * 2 + 16);
   if ((int64_t)ldsb > kLdsPerCu) return BSP_ERR_UNSUPPORTED;
   c.groups = (t.nstrips + 3) / 4;
   // persistent grid: as many workgroups as fit at once, every one the same tile count
-  const int64_t per_cu = (int64_t)ldsb * 2 <= kLdsPerCu ? 2 : 1;
+  const int64_t per_cu = 1;
   int64_t slots = per_cu * device_cus() / c.groups;
   if (slots < 1) slots = 1;
   c.wg_per_group = (int32_t)(ntiles < slots ? ntiles : slots);
   const int64_t nwg = (int64_t)c.wg_per_group * c.groups;
   const int64_t npieces = (int64_t)t.TPH * t.TPW * (t.slab / BSP_CHUNK);
-  if (nwg >= (1 << 24) || ntiles >= (1 << 24) || npieces > 256 * kStageBatch ||
+  if (nwg >= (1 << 24) || ntiles >= (1 << 24) || npieces > 512 * kStageBatch ||
       (npieces + 2048) * t.TPW >= (1ll << 32))
     return BSP_ERR_UNSUPPORTED;
   t.spc = 4;
@@ -378,9 +384,9 @@ int bsp_launch_wres(const ConvParams& p_in, int dtype, const void* plan_host, hi
   c.off_wfrag = hdr[BSP_PLAN_OFF_WFRAG_W];
   dim3 grid((unsigned)nwg);
   switch (NT) {
-    case 4: return launch<4>(p, t, c, grid, ldsb, st);
-    case 7: return launch<7>(p, t, c, grid, ldsb, st);
-    case 8: return launch<8>(p, t, c, grid, ldsb, st);
+    case 4: return launch<4, kPH>(p, t, c, grid, ldsb, st);
+    case 7: return launch<7, kPH>(p, t, c, grid, ldsb, st);
+    case 8: return launch<8, kPH>(p, t, c, grid, ldsb, st);
     default: return BSP_ERR_UNSUPPORTED;
   }
 }
