@@ -8,8 +8,8 @@
 
 namespace {
 
-// BSP_KERNEL=general|tile|wres narrows the dispatcher's choice (tuning aid): "tile" skips
-// the weights-resident kernel, "general" skips both LDS-tiled kernels.
+// BSP_KERNEL=general|tile|lds narrows the dispatcher's choice (tuning aid): "tile" skips
+// the LDS-resident kernel, "general" skips both LDS-tiled kernels.
 int kernel_limit() {
   static int v = -1;
   if (v < 0) {
@@ -90,7 +90,7 @@ int bsp_conv2d(const bsp_weights* w, const void* X, const float* bias, void* Y, 
   if (bsp_tile_supported(p, w->dtype) && kernel_limit() >= 1) {
     int rc = bsp_launch_fc_stream(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
-    if (kernel_limit() >= 2) rc = bsp_launch_wres(p, w->dtype, w->plan_host, (hipStream_t)stream);
+    if (kernel_limit() >= 2) rc = bsp_launch_lds(p, w->dtype, w->plan_host, (hipStream_t)stream);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
     rc = bsp_launch_tile(p, w->dtype, (hipStream_t)stream);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;

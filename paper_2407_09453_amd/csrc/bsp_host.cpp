@@ -219,7 +219,7 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, const void*
   std::vector<int32_t> strip_ptr((size_t)nstrips + 1, 0);
   std::vector<int32_t> xc_list, src_list;
   std::vector<int32_t> slab_ptr;  // [nstrips][nslabs+1]
-  int32_t max_chunks = 0, max_steps = 0;
+  int32_t max_chunks = 0, max_steps = 0, max_slab_steps = 0;
   int64_t nsteps = 0;
   for (int32_t t = 0; t < nstrips; ++t) {
     std::fill(src.begin(), src.end(), -1);
@@ -247,7 +247,9 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, const void*
     auto close_slabs_upto = [&](int32_t sl) {  // finish slabs < sl
       while (next_slab < sl) {
         if (next_slab == 0) slab_ptr.push_back((int32_t)nsteps);
-        nsteps += cdiv((int64_t)in_slab * HK, 4);
+        const int64_t st = cdiv((int64_t)in_slab * HK, 4);
+        if (st > max_slab_steps) max_slab_steps = (int32_t)st;
+        nsteps += st;
         slab_ptr.push_back((int32_t)nsteps);
         in_slab = 0;
         ++next_slab;
@@ -306,6 +308,7 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, const void*
   out[BSP_PLAN_OFF_XDESC_W] = (int32_t)off_xdesc;
   out[BSP_PLAN_OFF_WFRAG_W] = (int32_t)off_wfrag;
   out[BSP_PLAN_MAXSTEPS_W] = steps_wanted ? max_steps : 0;
+  out[BSP_PLAN_MAXSLABSTEPS_W] = steps_wanted ? max_slab_steps : 0;
   std::memcpy(out + off_strip, strip_ptr.data(), sizeof(int32_t) * strip_ptr.size());
   if (nchunks) {
     std::memcpy(out + off_xc, xc_list.data(), sizeof(int32_t) * xc_list.size());

@@ -17,8 +17,8 @@ int bsp_launch_tile(const ConvParams& p, int dtype, hipStream_t st);
 // Weight-streaming kernel for 1x1 layers with at most 64 output pixels (FC layers).
 int bsp_launch_fc_stream(const ConvParams& p, int dtype, int bo, int bi, hipStream_t st);
 
-// Weights-resident LDS kernel for short, single-slab strips; needs the host copy
+// LDS-resident kernel (weights and activations of a slab both in LDS); needs the host copy
 // of the plan to size LDS.  BSP_ERR_UNSUPPORTED = not applicable, nothing launched.
-int bsp_launch_wres(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);
+int bsp_launch_lds(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);
 
 #endif

@@ -46,7 +46,7 @@ enum {
   BSP_MAXSUB = 4,
   BSP_PLAN_HEADER_WORDS = 32,
   BSP_PLAN_MAGIC = 0x42535032,
-  BSP_PLAN_VERSION = 2,
+  BSP_PLAN_VERSION = 3,
 };
 
 enum {
@@ -73,13 +73,14 @@ enum {
   BSP_PLAN_OFF_XDESC_W = 20,
   BSP_PLAN_OFF_WFRAG_W = 21,
   BSP_PLAN_MAXSTEPS_W = 22,   // most steps in any one strip
+  BSP_PLAN_MAXSLABSTEPS_W = 23,  // most steps in any one (strip, slab)
 };
 
 // Channels kept in LDS at a time, as a function of the layer shape alone so
 // that the plan builder and the launcher agree without talking to each other.
 static inline int32_t bsp_slab_channels(int32_t I, int32_t H, int32_t K) {
   const int32_t i8 = (I + 7) / 8 * 8;
-  const int32_t cap = (H * K > 1) ? 128 : 256;
+  const int32_t cap = (H * K > 1) ? 64 : 256;
   return i8 < cap ? i8 : cap;
 }
 

@@ -236,7 +236,7 @@ def test_step_section_holds_exactly_the_kept_weights(bo, bi, O, I, H, K):
     plan = bsp.bsp_plan_build(rp, ci, pl, O, H, K, I, bo, bi)
     assert plan.nbytes == bsp.bsp_plan_size(rp, ci, O, H, K, I, bo, bi, bsp.BSP_BF16)
     hdr = plan[:32]
-    assert hdr[16] == min(-(-I // 8) * 8, 128 if H * K > 1 else 256)
+    assert hdr[16] == min(-(-I // 8) * 8, 64 if H * K > 1 else 256)
     assert hdr[17] == -(-(-(-I // 8)) // (hdr[16] // 8))
     Wd, nonnull = _decode_steps(plan, O, H, K, I)
     Wm = oracle.bf16_bits_rne(oracle.apply_mask(c.W, c.gamma, bo, bi)).reshape(c.W.shape)
@@ -245,9 +245,12 @@ def test_step_section_holds_exactly_the_kept_weights(bo, bi, O, I, H, K):
     nstrips, nslabs = hdr[8], hdr[17]
     sp = plan[hdr[10]:hdr[10] + nstrips + 1]
     xc = plan[hdr[11]:hdr[11] + hdr[9]]
-    want = 0
+    want = worst = 0
     for t in range(nstrips):
         cols = xc[sp[t]:sp[t + 1]] // (hdr[16] // 8)
         for sl in range(nslabs):
-            want += -(-int((cols == sl).sum()) * H * K // 4)
+            st = -(-int((cols == sl).sum()) * H * K // 4)
+            want += st
+            worst = max(worst, st)
     assert hdr[18] == want
+    assert hdr[23] == worst
