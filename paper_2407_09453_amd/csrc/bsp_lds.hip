@@ -26,10 +26,13 @@
 
 namespace {
 
-constexpr int kPH = 2;             // waves per strip, each taking a share of the tile's pixel tiles
-constexpr int kThreads = 256 * kPH;
-constexpr int kXBatch = 8;         // 16-byte patch pieces a thread keeps in flight
-constexpr int kWBatch = 10;        // weight fragments a lane keeps in flight (its share of a slab)
+constexpr int kPH = 2;              // compute waves per strip, each taking a share of the pixel tiles
+constexpr int kComputeThreads = 256 * kPH;
+constexpr int kLoaderWaves = 4;     // one per strip of the group
+constexpr int kLoaderThreads = 64 * kLoaderWaves;
+constexpr int kThreads = kComputeThreads + kLoaderThreads;
+constexpr int kXBatch = 12;         // 16-byte patch pieces a loader thread keeps in flight
+constexpr int kWHalf = 10;         // weight fragments a loader lane keeps in flight (one slab of a strip)
 constexpr int kMaxSlabs = 32;
 constexpr int kOutRow = 4 * BSP_STRIP * 2 + 16;  // bytes per pixel in the results staging tile
 
@@ -37,11 +40,18 @@ struct LdsCfg {
   int32_t wbuf_off;       // LDS offset of the weight regions (after the patch)
   int32_t region_bytes;   // per strip: maxsteps fragments + maxsteps offset quads
   int32_t obuf_off;       // LDS offset of the results staging tile
-  int32_t sp_off;         // LDS offset of the step-range table [4][nslabs + 1]
   int32_t maxsteps;       // most steps any (strip, slab) has
+  int32_t nsteps;         // steps in the whole plan
   int32_t groups;         // strip groups (of four)
   int32_t wg_per_group;   // workgroups sharing one strip group
   int32_t off_slab, off_xdesc, off_wfrag;  // plan sections, in words (read on the host)
+  // advancing a thread's patch piece by the number of loader threads: uniform steps of
+  // (channel part, patch column), of the LDS offset, of the element offset from the patch
+  // origin and of the image row / column, then what a carry out of the channel parts
+  // (cp_*) and out of the patch columns (cx_*) adds
+  int32_t s_part, s_px, s_l, s_g, s_iy, s_ix;
+  int32_t cp_l, cp_g;
+  int32_t cx_l, cx_g, cx_ix;
   FastDiv d_groups;
 };
 
@@ -52,14 +62,35 @@ __device__ __forceinline__ void load_b_at(u32x4_t (&b)[NT], const int xoff,
   for (int nt = 0; nt < NT; ++nt) b[nt] = *(const u32x4_t*)(lds + base[nt] + xoff);
 }
 
+// position (row, column) inside the workgroup's tile of pixel j of pixel tile gt
+__device__ __forceinline__ void tile_pos(const TileCfg& t, int gt, int j, int* ty, int* tx) {
+  if (t.tile2x8) {
+    const int tr = (int)fdiv((uint32_t)gt, t.d_tpr), tc = gt - tr * (t.TW >> 3);
+    *ty = tr * 2 + (j >> 3);
+    *tx = tc * 8 + (j & 7);
+  } else {
+    const int pi = gt * 16 + j;
+    *ty = (int)fdiv((uint32_t)pi, t.d_tw);
+    *tx = pi - *ty * t.TW;
+  }
+}
+
+// Twelve waves, two roles.  Waves 0-7 compute: wave w owns strip w & 3 of the group and
+// share w >> 2 of the tile's pixel tiles; during a unit (one slab of one tile) it touches
+// nothing but LDS and the matrix cores, apart from having its share of the strip's next
+// weight fragments in flight into spare registers.  Waves 8-11 move data: while a unit is
+// computed they have the next unit's patch in flight into their registers, after the
+// barrier they write it into LDS, and they carry finished results from the LDS staging
+// tile to global memory.  Barriers per unit, taken by all twelve waves:
+//   A  the unit's patch and weights are in LDS
+//   E  (single-slab layers only) the staging tile has been drained, results may go in
+//   B  the compute waves are done reading the patch and weights
 template <int NT>
 __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileCfg t, LdsCfg c) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wave = wave_all & 3;   // which strip of the group
-  const int half = wave_all >> 2;  // which share of the tile's pixel tiles
-  const int jn = lane & 15, g = lane >> 4;
+  const bool loader = wave_all >= 4 * kPH;
 
   const uint32_t bid = blockIdx.x;
   const int cidx = (int)fdiv(bid, c.d_groups);
@@ -67,208 +98,205 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
   int tile = cidx;
   if (tile >= t.ntiles) return;
 
-  const uint16_t* X = (const uint16_t*)p.X;
-  const int32_t* plan = p.plan;
-  const int32_t* slab_ptr = plan + c.off_slab;
-  const int32_t* xdesc = plan + c.off_xdesc;
-  const u32x4_t* wfrag = (const u32x4_t*)(plan + c.off_wfrag);
   const int tpi = t.tiles_y * t.tiles_x;
+  const int nsl1 = t.nslabs + 1;
+  const bool reload_w = t.nslabs > 1;
+  const int32_t* plan = p.plan;
+
+  // which tile / slab follows (tile, sl), and whether there is one
+  auto advance = [&](int tl, int sl, int* ntl, int* nsl) {
+    *ntl = tl;
+    *nsl = sl + 1;
+    if (*nsl == t.nslabs) {
+      *nsl = 0;
+      *ntl = tl + c.wg_per_group;
+    }
+    return *ntl < t.ntiles;
+  };
+
+  if (loader) {
+    // =================================================================== data movers
+    // few instructions, but everything waits on them: issue ahead of the compute waves
+    __builtin_amdgcn_s_setprio(3);
+    const int ltid = tid - kComputeThreads;
+    const uint16_t* X = (const uint16_t*)p.X;
+    // The patch is cut into 16-byte pieces (pixel-major, 8 channels each); this thread
+    // moves pieces ltid, ltid + 256, ...  Piece -> (channel part, patch column, patch row)
+    // is found once for the first piece and then advanced by the uniform step, with two
+    // carries, so that the per-unit address arithmetic has no division or multiplication.
+    const int PP = t.slab / BSP_CHUNK;
+    const int npieces = t.TPH * t.TPW * PP;
+    int part0, px0, py0;
+    {
+      const int pix = (int)fdiv((uint32_t)ltid, t.d_pp);
+      part0 = ltid - pix * PP;
+      py0 = (int)fdiv((uint32_t)pix, t.d_tpw);
+      px0 = pix - py0 * t.TPW;
+    }
+    const int l0 = py0 * t.pitch + px0 * t.row_bytes + part0 * 16;  // LDS offset
+    // element offset from the patch origin
+    const int g0 = (py0 * t.gsh * p.J + px0 * t.gsw) * p.I + part0 * BSP_CHUNK;
+    const int iy0 = py0 * t.gsh, ix0 = px0 * t.gsw;
+    // the results staging tile: piece q = ltid + 256 k is channels 8 (q & 7).. of pixel q >> 3
+    int fpos[NT], foff[NT];
+#pragma unroll
+    for (int k = 0; k < NT; ++k) {
+      const int pi = (ltid >> 3) + 32 * k;
+      int ty, tx;
+      tile_pos(t, pi >> 4, pi & 15, &ty, &tx);
+      fpos[k] = (ty < t.TH && tx < t.TW && sg * 64 + (ltid & 7) * 8 < p.O) ? (ty << 16 | tx) : -1;
+      foff[k] = (ty * p.N + tx) * p.O + (ltid & 7) * 8;
+    }
+
+    u32x4_t xv[kXBatch];
+    // X + origin of the patch may point before the image (padding); only in-image pieces are read
+    auto issue_patch = [&](int tl, int sl) {
+      const int n = (int)fdiv((uint32_t)tl, t.d_tpi);
+      const int trem = tl - n * tpi;
+      const int tyi = (int)fdiv((uint32_t)trem, t.d_tiles_x);
+      const int iy_org = tyi * t.TH * p.sh - p.ph;
+      const int ix_org = (trem - tyi * t.tiles_x) * t.TW * p.sw - p.pw;
+      const int ch0 = sl * t.slab;
+      const uint16_t* org = X + (((int64_t)n * p.L + iy_org) * p.J + ix_org) * p.I + ch0;
+      int part = part0, px = px0, iy = iy_org + iy0, ix = ix_org + ix0;
+      uint32_t g = (uint32_t)g0;
+#pragma unroll
+      for (int u = 0; u < kXBatch; ++u) {
+        xv[u] = u32x4_t{0u, 0u, 0u, 0u};
+        if (ltid + u * kLoaderThreads < npieces && (unsigned)iy < (unsigned)p.L &&
+            (unsigned)ix < (unsigned)p.J && ch0 + part * BSP_CHUNK < p.I)
+          xv[u] = *(const u32x4_t*)(org + g);
+        part += c.s_part; px += c.s_px; g += (uint32_t)c.s_g; iy += c.s_iy; ix += c.s_ix;
+        if (part >= PP) { part -= PP; px += 1; g += (uint32_t)c.cp_g; ix += t.gsw; }
+        if (px >= t.TPW) { px -= t.TPW; g += (uint32_t)c.cx_g; iy += t.gsh; ix -= c.cx_ix; }
+      }
+    };
+    auto commit_patch = [&]() {
+      int part = part0, px = px0, l = l0;
+#pragma unroll
+      for (int u = 0; u < kXBatch; ++u) {
+        if (ltid + u * kLoaderThreads < npieces) *(u32x4_t*)(lds + l) = xv[u];
+        part += c.s_part; px += c.s_px; l += c.s_l;
+        if (part >= PP) { part -= PP; px += 1; l += c.cp_l; }
+        if (px >= t.TPW) { px -= t.TPW; l += c.cx_l; }
+      }
+    };
+    // results of tile tl: LDS staging tile -> Y as whole 16-byte pieces, eight consecutive
+    // lanes covering the 64 output channels (128 bytes) of one pixel
+    uint16_t* Y = (uint16_t*)p.Y;
+    auto flush = [&](int tl) {
+      const int n = (int)fdiv((uint32_t)tl, t.d_tpi);
+      const int trem = tl - n * tpi;
+      const int tyi = (int)fdiv((uint32_t)trem, t.d_tiles_x);
+      const int oy0 = tyi * t.TH, ox0 = (trem - tyi * t.tiles_x) * t.TW;
+      uint16_t* yorg = Y + (((int64_t)n * p.M + oy0) * p.N + ox0) * p.O + sg * 64;
+      const int my = p.M - oy0, mx = p.N - ox0;  // rows / columns of the tile inside the image
+      u32x4_t ov[NT];
+#pragma unroll
+      for (int k = 0; k < NT; ++k)
+        ov[k] = *(const u32x4_t*)(lds + c.obuf_off + ((ltid >> 3) + 32 * k) * kOutRow + (ltid & 7) * 16);
+#pragma unroll
+      for (int k = 0; k < NT; ++k) {
+        const int f = fpos[k];
+        if (f >= 0 && (f >> 16) < my && (f & 0xFFFF) < mx) *(u32x4_t*)(yorg + foff[k]) = ov[k];
+      }
+    };
+
+    int sl = 0;
+    issue_patch(tile, 0);
+    commit_patch();
+    __syncthreads();  // A: first unit is in LDS
+    int flush_tile = -1;
+    while (true) {
+      if (flush_tile >= 0) flush(flush_tile);  // while the compute waves work on (tile, sl)
+      int ntile, nsl;
+      const bool more = advance(tile, sl, &ntile, &nsl);
+      if (more) issue_patch(ntile, nsl);  // lands in registers during the compute phase
+      flush_tile = sl == t.nslabs - 1 ? tile : -1;
+      if (!reload_w) __syncthreads();  // E
+      __syncthreads();                 // B: compute waves are done with the LDS patch
+      if (!more) break;
+      commit_patch();
+      __syncthreads();  // A: next unit is in LDS
+      tile = ntile;
+      sl = nsl;
+    }
+    flush(tile);
+    return;
+  }
+
+  // ===================================================================== compute waves
+  const int wave = wave_all & 3;   // which strip of the group
+  const int half = wave_all >> 2;  // which share of the tile's pixel tiles
+  const int jn = lane & 15, g = lane >> 4;
   const int strip = sg * 4 + wave;
   const bool valid = strip < t.nstrips;
-  const int nsl1 = t.nslabs + 1;
-
-  // ---- step ranges of the group's four strips, all slabs: LDS table sp[4][nslabs+1]
-  int* sp = (int*)(lds + c.sp_off);
-  if (tid < 4 * nsl1) {
-    const int w = tid / nsl1, k = tid - w * nsl1;
-    const int st = sg * 4 + w;
-    sp[tid] = st < t.nstrips ? slab_ptr[st * nsl1 + k] : 0;
-  }
-
-  // ---- per-thread patch map (same for every unit): piece u -> LDS offset, patch pixel, offset in X
-  const int PP = t.slab / BSP_CHUNK;
-  const int npieces = t.TPH * t.TPW * PP;
-  int sdst[kXBatch], sinfo[kXBatch], soff[kXBatch];
-#pragma unroll
-  for (int u = 0; u < kXBatch; ++u) {
-    const int idx = tid + u * kThreads;
-    const uint32_t pix = fdiv((uint32_t)idx, t.d_pp);
-    const int part = idx - (int)pix * PP;
-    const int py = (int)fdiv(pix, t.d_tpw);
-    const int px = (int)pix - py * t.TPW;
-    sdst[u] = idx < npieces ? py * t.pitch + px * t.row_bytes + part * 16 : -1;
-    sinfo[u] = idx < npieces ? ((py * t.gsh) | ((px * t.gsw) << 16) | (part << 26)) : -1;
-    soff[u] = ((py * t.gsh) * p.J + px * t.gsw) * p.I + part * BSP_CHUNK;  // elements from the patch origin
-  }
-
-  // ---- registers the next unit's data lands in
-  u32x4_t xv[kXBatch], wv[kWBatch];
-  int dsc[2] = {0, 0};
-  int w_nst = 0;  // steps of the (strip, slab) in flight
+  const int32_t* slab_ptr = plan + c.off_slab + (valid ? strip : 0) * nsl1;
+  const int32_t* xdesc = plan + c.off_xdesc;
+  const u32x4_t* wfrag = (const u32x4_t*)(plan + c.off_wfrag);
   u32x4_t* wl = (u32x4_t*)(lds + c.wbuf_off + wave * c.region_bytes);
   int* xo = (int*)(lds + c.wbuf_off + wave * c.region_bytes + c.maxsteps * 1024);
 
-  // X + origin of the patch may point before the image (padding); only in-image pieces are read
-  auto issue_patch = [&](int tl, int sl) {
-    const int n = (int)fdiv((uint32_t)tl, t.d_tpi);
-    const int trem = tl - n * tpi;
-    const int tyi = (int)fdiv((uint32_t)trem, t.d_tiles_x);
-    const int iy_org = tyi * t.TH * p.sh - p.ph;
-    const int ix_org = (trem - tyi * t.tiles_x) * t.TW * p.sw - p.pw;
-    const int ch0 = sl * t.slab;
-    const uint16_t* org = X + (((int64_t)n * p.L + iy_org) * p.J + ix_org) * p.I + ch0;
-    const bool interior = iy_org >= 0 && ix_org >= 0 && iy_org + (t.TPH - 1) * t.gsh < p.L &&
-                          ix_org + (t.TPW - 1) * t.gsw < p.J && ch0 + t.slab <= p.I;
-    if (interior) {
+  // The strip's weight fragments of a slab go global -> registers -> LDS, this wave moving
+  // steps [half * kWHalf, half * kWHalf + kWHalf) of them, and with them the LDS offsets
+  // the steps' activation fragments are read at.
+  u32x4_t wv[kWHalf];
+  int dsc = 0, w_n = 0;
+  // All kWHalf loads are always issued, in one straight line so that they are in flight
+  // together; those past the wave's share repeat its last fragment and are dropped.
+  auto issue_weights = [&](int s0, int s1) {
+    w_n = max(0, min(s1 - s0 - half * kWHalf, kWHalf));
+    const int f = s0 + half * kWHalf;
+    const int last = min(max(f + w_n, s0 + 1), c.nsteps) - 1;  // a fragment that exists
 #pragma unroll
-      for (int u = 0; u < kXBatch; ++u) {
-        xv[u] = u32x4_t{0u, 0u, 0u, 0u};
-        if (sinfo[u] >= 0) xv[u] = *(const u32x4_t*)(org + soff[u]);
-      }
-    } else {
-#pragma unroll
-      for (int u = 0; u < kXBatch; ++u) {
-        xv[u] = u32x4_t{0u, 0u, 0u, 0u};
-        const int iy = iy_org + (sinfo[u] & 0x3FF), ix = ix_org + ((sinfo[u] >> 16) & 0x3FF);
-        const int ch = ch0 + (sinfo[u] >> 26) * BSP_CHUNK;
-        if (sinfo[u] >= 0 && (unsigned)iy < (unsigned)p.L && (unsigned)ix < (unsigned)p.J && ch < p.I)
-          xv[u] = *(const u32x4_t*)(org + soff[u]);
-      }
-    }
-  };
-  // this wave's share of its strip's fragments of a slab (alternate steps) and, on the
-  // first of the two waves, the step descriptors; s0 / steps come from the LDS table
-  auto issue_weights = [&](int s0, int nst) {
-    w_nst = nst;
-#pragma unroll
-    for (int u = 0; u < kWBatch; ++u)
-      if (half + u * kPH < nst) wv[u] = wfrag[(int64_t)(s0 + half + u * kPH) * 64 + lane];
-#pragma unroll
-    for (int k = 0; k < 2; ++k)
-      if (half == 0 && lane + 64 * k < nst * 4) dsc[k] = xdesc[s0 * 4 + lane + 64 * k];
-  };
-  auto commit_patch = [&]() {
-#pragma unroll
-    for (int u = 0; u < kXBatch; ++u)
-      if (sdst[u] >= 0) *(u32x4_t*)(lds + sdst[u]) = xv[u];
+    for (int u = 0; u < kWHalf; ++u) wv[u] = wfrag[(int64_t)min(f + u, last) * 64 + lane];
+    if (lane < w_n * 4) dsc = xdesc[f * 4 + lane];
   };
   auto commit_weights = [&]() {
 #pragma unroll
-    for (int u = 0; u < kWBatch; ++u)
-      if (half + u * kPH < w_nst) wl[(half + u * kPH) * 64 + lane] = wv[u];
-#pragma unroll
-    for (int k = 0; k < 2; ++k)
-      if (half == 0 && lane + 64 * k < w_nst * 4) {
-        const int d = dsc[k];
-        xo[lane + 64 * k] =
-            ((d >> 16) & 0xFF) * t.pitch + ((d >> 24) & 0xFF) * t.row_bytes + (d & 0xFFFF) * 16;
-      }
+    for (int u = 0; u < kWHalf; ++u)
+      if (u < w_n) wl[(half * kWHalf + u) * 64 + lane] = wv[u];
+    if (lane < w_n * 4)
+      xo[half * kWHalf * 4 + lane] = ((dsc >> 16) & 0xFF) * t.pitch +
+                                     ((dsc >> 24) & 0xFF) * t.row_bytes + (dsc & 0xFFFF) * 16;
   };
 
-  // ---- first unit: patch first (needs nothing from the plan), then weights
-  issue_patch(tile, 0);
-  __syncthreads();  // step-range table visible
-  const bool reload_w = t.nslabs > 1;
-  if (valid) issue_weights(sp[wave * nsl1], sp[wave * nsl1 + 1] - sp[wave * nsl1]);
+  int s_lo = valid ? slab_ptr[0] : 0, s_hi = valid ? slab_ptr[1] : 0;  // steps of the current slab
+  issue_weights(s_lo, s_hi);
+
   float bv[4] = {0.f, 0.f, 0.f, 0.f};
   const int ch = strip * BSP_STRIP + 4 * g;
   if (valid) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) bv[r] = (p.bias && ch + r < p.O) ? p.bias[ch + r] : 0.f;
   }
-
-  // ---- per-lane pixel map: LDS base of each of this wave's pixel tiles
-  int base[NT];
+  int base[NT];  // LDS base of this lane's pixel in each of the wave's pixel tiles
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    const int gt = half * NT + nt;  // pixel tile within the workgroup's tile
     int ty, tx;
-    if (t.tile2x8) {
-      const int tr = (int)fdiv((uint32_t)gt, t.d_tpr), tc = gt - tr * (t.TW >> 3);
-      ty = tr * 2 + (jn >> 3);
-      tx = tc * 8 + (jn & 7);
-    } else {
-      const int pi = gt * 16 + jn;
-      ty = (int)fdiv((uint32_t)pi, t.d_tw);
-      tx = pi - ty * t.TW;
-    }
-    const bool in_tile = ty < t.TH && tx < t.TW;
-    base[nt] = in_tile ? (ty * t.lsh) * t.pitch + (tx * t.lsw) * t.row_bytes : 0;
-  }
-  // ---- cooperative store map: results leave LDS as whole 16-byte pieces, eight
-  // consecutive lanes covering the 64 output channels (128 bytes) of one pixel
-  constexpr int kOutPieces = (NT * kPH * 16 * 8 + kThreads - 1) / kThreads;
-  int csrc[kOutPieces], cpyx[kOutPieces], coff[kOutPieces];
-#pragma unroll
-  for (int k = 0; k < kOutPieces; ++k) {
-    const int q = tid + k * kThreads;
-    const int pi = q >> 3, part = q & 7;
-    const int nt = pi >> 4, j = pi & 15;
-    int ty, tx;
-    if (t.tile2x8) {
-      const int tr = (int)fdiv((uint32_t)nt, t.d_tpr), tc = nt - tr * (t.TW >> 3);
-      ty = tr * 2 + (j >> 3);
-      tx = tc * 8 + (j & 7);
-    } else {
-      ty = (int)fdiv((uint32_t)pi, t.d_tw);
-      tx = pi - ty * t.TW;
-    }
-    const bool live = nt < NT * kPH && ty < t.TH && tx < t.TW && sg * 64 + part * 8 < p.O;
-    csrc[k] = c.obuf_off + pi * kOutRow + part * 16;
-    cpyx[k] = live ? (ty | (tx << 16)) : -1;
-    coff[k] = (ty * p.N + tx) * p.O + sg * 64 + part * 8;
+    tile_pos(t, half * NT + nt, jn, &ty, &tx);
+    base[nt] = (ty < t.TH && tx < t.TW) ? (ty * t.lsh) * t.pitch + (tx * t.lsw) * t.row_bytes : 0;
   }
   // where this lane's four channels of pixel jn of pixel tile nt go in the staging tile
   const int orow = c.obuf_off + (half * NT * 16 + jn) * kOutRow + wave * (BSP_STRIP * 2) + g * 8;
-
-  uint16_t* Y = (uint16_t*)p.Y;
-  auto flush = [&](int tl) {
-    const int n = (int)fdiv((uint32_t)tl, t.d_tpi);
-    const int trem = tl - n * tpi;
-    const int tyi = (int)fdiv((uint32_t)trem, t.d_tiles_x);
-    const int oy0 = tyi * t.TH, ox0 = (trem - tyi * t.tiles_x) * t.TW;
-    uint16_t* yorg = Y + (((int64_t)n * p.M + oy0) * p.N + ox0) * p.O;
-    const bool whole = oy0 + t.TH <= p.M && ox0 + t.TW <= p.N;
-#pragma unroll
-    for (int k = 0; k < kOutPieces; ++k) {
-      if (cpyx[k] < 0) continue;
-      if (!whole && (oy0 + (cpyx[k] & 0xFFFF) >= p.M || ox0 + (cpyx[k] >> 16) >= p.N)) continue;
-      *(u32x4_t*)(yorg + coff[k]) = *(const u32x4_t*)(lds + csrc[k]);
-    }
-  };
 
   f32x4_t acc[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   int sl = 0;
-  bool w_pending = true;  // weights for the unit about to start are in registers, not yet in LDS
+  commit_weights();
+  __syncthreads();  // A
   while (true) {
-    // ---- registers -> LDS for this unit
-    commit_patch();
-    if (w_pending && valid) commit_weights();
-    const int nst = valid ? sp[wave * nsl1 + sl + 1] - sp[wave * nsl1 + sl] : 0;
-    __syncthreads();
-
-    // ---- next unit's loads fly while this one is computed
-    int ntile = tile, nsl = sl + 1;
-    if (nsl == t.nslabs) {
-      nsl = 0;
-      ntile = tile + c.wg_per_group;
+    int ntile, nsl;
+    const bool more = advance(tile, sl, &ntile, &nsl);
+    const int nst = s_hi - s_lo;
+    if (reload_w && more) {  // next slab's fragments: in flight while this one is computed
+      s_lo = valid ? slab_ptr[nsl] : 0;
+      s_hi = valid ? slab_ptr[nsl + 1] : 0;
+      issue_weights(s_lo, s_hi);
     }
-    const bool more = ntile < t.ntiles;
-    // The two waves that share a SIMD go through "fetch the next unit" and "compute this
-    // one" in opposite order, so one's address traffic overlaps the other's MFMAs.
-    auto fetch_next = [&]() {
-      if (!more) return;
-      issue_patch(ntile, nsl);
-      if (reload_w && valid)
-        issue_weights(sp[wave * nsl1 + nsl], sp[wave * nsl1 + nsl + 1] - sp[wave * nsl1 + nsl]);
-    };
-    if (half == 0) fetch_next();
-    w_pending = reload_w;
-
-    // ---- this slab's steps, everything from LDS and one step ahead (offsets two)
+    // this slab's steps, everything from LDS and one step ahead (offsets two)
     if (nst > 0) {
       u32x4_t a[2], b[2][NT];
       const int lastq = nst - 1;
@@ -288,10 +316,9 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
         }
       }
     }
-    if (half != 0) fetch_next();
-    const bool last_slab = sl == t.nslabs - 1;
-    if (last_slab && valid) {
-      // lane holds channels 4g..4g+3 of pixel jn of every pixel tile
+    if (!reload_w) __syncthreads();  // E
+    if (sl == t.nslabs - 1 && valid) {
+      // + bias, one rounding; lane holds channels 4g..4g+3 of pixel jn of every pixel tile
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         u32x2_t v;
@@ -301,9 +328,10 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
         *(u32x2_t*)(lds + orow + nt * 16 * kOutRow) = v;
       }
     }
-    __syncthreads();  // patch and weights may be overwritten; results are staged
-    if (last_slab) flush(tile);
+    __syncthreads();  // B
     if (!more) break;
+    if (reload_w) commit_weights();
+    __syncthreads();  // A
     tile = ntile;
     sl = nsl;
   }
@@ -358,12 +386,11 @@ int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hip
   LdsCfg c;
   c.maxsteps = hdr[BSP_PLAN_MAXSLABSTEPS_W];
   const int nslabs = hdr[BSP_PLAN_NSLABS_W];
-  // a lane copies every other step of a slab and two descriptors: bounds of this kernel
-  if (c.maxsteps < 1 || c.maxsteps > kWBatch * kPH || c.maxsteps > 32 || nslabs > kMaxSlabs)
+  // a compute wave stages half the steps of a slab of its strip, one descriptor per lane
+  if (c.maxsteps < 1 || c.maxsteps > kWHalf * kPH || c.maxsteps > 32 || nslabs > kMaxSlabs)
     return BSP_ERR_UNSUPPORTED;
   c.region_bytes = c.maxsteps * (1024 + 16);
   const int64_t wbytes = 4ll * c.region_bytes;
-  const int64_t spbytes = 4 * (kMaxSlabs + 1) * 4;
 
   TileCfg t;
   int NT = 0;
@@ -379,7 +406,7 @@ int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hip
       t.nslabs = ((p.I + 7) / 8 + t.slab / 8 - 1) / (t.slab / 8);
       t.nstrips = (p.O + BSP_STRIP - 1) / BSP_STRIP;
       // the LDS left after the weights holds the patch and the results staging tile
-      if (!bsp_choose_tile(p, t.slab, kLdsPerCu - wbytes - spbytes, kThreads * kXBatch, kPH, kOutRow,
+      if (!bsp_choose_tile(p, t.slab, kLdsPerCu - wbytes, kLoaderThreads * kXBatch, kPH, kOutRow,
                            &NT, &t))
         NT = 0;
       if (memo.size() > 4096) memo.clear();
@@ -395,8 +422,7 @@ int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hip
   const int64_t ntiles = (int64_t)p.B * t.tiles_y * t.tiles_x;
   c.wbuf_off = (t.TPH * t.pitch + 15) & ~15;
   c.obuf_off = c.wbuf_off + (int32_t)wbytes;
-  c.sp_off = c.obuf_off + NT * kPH * 16 * kOutRow;
-  const size_t ldsb = (size_t)c.sp_off + (size_t)spbytes;
+  const size_t ldsb = (size_t)c.obuf_off + (size_t)NT * kPH * 16 * kOutRow;
   if ((int64_t)ldsb > kLdsPerCu) return BSP_ERR_UNSUPPORTED;
   c.groups = (t.nstrips + 3) / 4;
   // persistent grid: one workgroup per CU, shared out among the strip groups
@@ -405,8 +431,8 @@ int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hip
   c.wg_per_group = (int32_t)(ntiles < slots ? ntiles : slots);
   const int64_t nwg = (int64_t)c.wg_per_group * c.groups;
   const int64_t npieces = (int64_t)t.TPH * t.TPW * (t.slab / BSP_CHUNK);
-  if (nwg >= (1 << 24) || ntiles >= (1 << 24) || npieces > kThreads * kXBatch ||
-      (npieces + 8 * kThreads) * t.TPW >= (1ll << 32) || (int64_t)p.L * p.J * p.I >= (1ll << 31))
+  if (nwg >= (1 << 24) || ntiles >= (1 << 24) || npieces > kLoaderThreads * kXBatch ||
+      (npieces + kXBatch * kLoaderThreads) * t.TPW >= (1ll << 32) || (int64_t)p.L * p.J * p.I >= (1ll << 31))
     return BSP_ERR_UNSUPPORTED;
   t.spc = 4;
   t.ntiles = (int32_t)ntiles;
@@ -418,6 +444,23 @@ int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hip
   t.d_tpi = make_fastdiv(t.tiles_y * t.tiles_x);
   t.d_tiles_x = make_fastdiv(t.tiles_x);
   c.d_groups = make_fastdiv(c.groups);
+  {
+    const int PP = t.slab / BSP_CHUNK;
+    const int spix = kLoaderThreads / PP;  // pixels per step, then its rows and columns
+    c.s_part = kLoaderThreads % PP;
+    const int s_py = spix / t.TPW;
+    c.s_px = spix % t.TPW;
+    c.s_l = s_py * t.pitch + c.s_px * t.row_bytes + c.s_part * 16;
+    c.s_g = (s_py * t.gsh * p.J + c.s_px * t.gsw) * p.I + c.s_part * BSP_CHUNK;
+    c.s_iy = s_py * t.gsh;
+    c.s_ix = c.s_px * t.gsw;
+    c.cp_l = t.row_bytes - PP * 16;
+    c.cp_g = t.gsw * p.I - PP * BSP_CHUNK;
+    c.cx_l = t.pitch - t.TPW * t.row_bytes;
+    c.cx_g = (t.gsh * p.J - t.TPW * t.gsw) * p.I;
+    c.cx_ix = t.TPW * t.gsw;
+  }
+  c.nsteps = hdr[BSP_PLAN_NSTEPS_W];
   c.off_slab = hdr[BSP_PLAN_OFF_SLAB_W];
   c.off_xdesc = hdr[BSP_PLAN_OFF_XDESC_W];
   c.off_wfrag = hdr[BSP_PLAN_OFF_WFRAG_W];
