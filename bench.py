@@ -24,6 +24,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
+# HBM bytes per launch of the dispatcher's kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this script, each scaled by the same counter's reading for a device copy of known
+# size (summary: profiles/conv_lds_bf16_c1_counters.md)
+MEASURED_TRAFFIC_BYTES = {"c1": 29_670_210}
 
 
 def algorithmic_bytes(c, nnzb: int) -> int:
@@ -259,7 +263,8 @@ def main() -> int:
         "pack_ms": round(pack_ms, 3),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
-                     "traffic": None, "algorithmic_bytes": nbytes},
+                     "traffic": None if args.general else MEASURED_TRAFFIC_BYTES.get(args.workload),
+                     "algorithmic_bytes": nbytes},
     }
 
     if args.copy_calibration:
