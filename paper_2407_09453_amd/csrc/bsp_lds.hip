@@ -31,7 +31,7 @@ constexpr int kComputeThreads = 256 * kPH;
 constexpr int kLoaderWaves = 4;     // one per strip of the group
 constexpr int kLoaderThreads = 64 * kLoaderWaves;
 constexpr int kThreads = kComputeThreads + kLoaderThreads;
-constexpr int kXBatch = 12;         // 16-byte patch pieces a loader thread keeps in flight
+constexpr int kXBatch = 11;         // 16-byte patch pieces a loader thread keeps in flight
 constexpr int kWHalf = 10;         // weight fragments a loader lane keeps in flight (one slab of a strip)
 constexpr int kMaxSlabs = 32;
 constexpr int kOutRow = 4 * BSP_STRIP * 2 + 16;  // bytes per pixel in the results staging tile
@@ -121,22 +121,14 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
     const int ltid = tid - kComputeThreads;
     const uint16_t* X = (const uint16_t*)p.X;
     // The patch is cut into 16-byte pieces (pixel-major, 8 channels each); this thread
-    // moves pieces ltid, ltid + 256, ...  Piece -> (channel part, patch column, patch row)
-    // is found once for the first piece and then advanced by the uniform step, with two
-    // carries, so that the per-unit address arithmetic has no division or multiplication.
+    // moves pieces ltid, ltid + 256, ...  For each of them it keeps, from the first unit
+    // on: the element offset from the patch origin (-1: no such piece), the LDS offset,
+    // and (channel part) << 20 | (image rows from the origin) << 10 | (image columns).
+    // Piece -> (channel part, patch column, patch row) is found by division for the first
+    // piece and advanced by the uniform step with two carries for the others.
     const int PP = t.slab / BSP_CHUNK;
     const int npieces = t.TPH * t.TPW * PP;
-    int part0, px0, py0;
-    {
-      const int pix = (int)fdiv((uint32_t)ltid, t.d_pp);
-      part0 = ltid - pix * PP;
-      py0 = (int)fdiv((uint32_t)pix, t.d_tpw);
-      px0 = pix - py0 * t.TPW;
-    }
-    const int l0 = py0 * t.pitch + px0 * t.row_bytes + part0 * 16;  // LDS offset
-    // element offset from the patch origin
-    const int g0 = (py0 * t.gsh * p.J + px0 * t.gsw) * p.I + part0 * BSP_CHUNK;
-    const int iy0 = py0 * t.gsh, ix0 = px0 * t.gsw;
+    int xg[kXBatch], xl[kXBatch], xq[kXBatch];
     // the results staging tile: piece q = ltid + 256 k is channels 8 (q & 7).. of pixel q >> 3
     int fpos[NT], foff[NT];
 #pragma unroll
@@ -150,36 +142,59 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
 
     u32x4_t xv[kXBatch];
     // X + origin of the patch may point before the image (padding); only in-image pieces are read
-    auto issue_patch = [&](int tl, int sl) {
+    struct Origin {
+      const uint16_t* org;
+      int iy, ix, ch0;
+    };
+    auto origin = [&](int tl, int sl) {
       const int n = (int)fdiv((uint32_t)tl, t.d_tpi);
       const int trem = tl - n * tpi;
       const int tyi = (int)fdiv((uint32_t)trem, t.d_tiles_x);
-      const int iy_org = tyi * t.TH * p.sh - p.ph;
-      const int ix_org = (trem - tyi * t.tiles_x) * t.TW * p.sw - p.pw;
-      const int ch0 = sl * t.slab;
-      const uint16_t* org = X + (((int64_t)n * p.L + iy_org) * p.J + ix_org) * p.I + ch0;
-      int part = part0, px = px0, iy = iy_org + iy0, ix = ix_org + ix0;
-      uint32_t g = (uint32_t)g0;
+      Origin o;
+      o.iy = tyi * t.TH * p.sh - p.ph;
+      o.ix = (trem - tyi * t.tiles_x) * t.TW * p.sw - p.pw;
+      o.ch0 = sl * t.slab;
+      o.org = X + (((int64_t)n * p.L + o.iy) * p.J + o.ix) * p.I + o.ch0;
+      return o;
+    };
+    auto load_piece = [&](int u, const Origin& o) {
+      xv[u] = u32x4_t{0u, 0u, 0u, 0u};
+      const int q = xq[u];
+      if (xg[u] >= 0 && (unsigned)(o.iy + ((q >> 10) & 1023)) < (unsigned)p.L &&
+          (unsigned)(o.ix + (q & 1023)) < (unsigned)p.J && o.ch0 + (q >> 20) * BSP_CHUNK < p.I)
+        xv[u] = *(const u32x4_t*)(o.org + xg[u]);
+    };
+    // first unit: build the maps piece by piece, each piece's load leaving right away
+    auto first_patch = [&](int tl) {
+      const Origin o = origin(tl, 0);
+      const int pix = (int)fdiv((uint32_t)ltid, t.d_pp);
+      int part = ltid - pix * PP;
+      const int py0 = (int)fdiv((uint32_t)pix, t.d_tpw);
+      int px = pix - py0 * t.TPW;
+      int l = py0 * t.pitch + px * t.row_bytes + part * 16;
+      uint32_t g = (uint32_t)((py0 * t.gsh * p.J + px * t.gsw) * p.I + part * BSP_CHUNK);
+      int iy = py0 * t.gsh, ix = px * t.gsw;
 #pragma unroll
       for (int u = 0; u < kXBatch; ++u) {
-        xv[u] = u32x4_t{0u, 0u, 0u, 0u};
-        if (ltid + u * kLoaderThreads < npieces && (unsigned)iy < (unsigned)p.L &&
-            (unsigned)ix < (unsigned)p.J && ch0 + part * BSP_CHUNK < p.I)
-          xv[u] = *(const u32x4_t*)(org + g);
-        part += c.s_part; px += c.s_px; g += (uint32_t)c.s_g; iy += c.s_iy; ix += c.s_ix;
-        if (part >= PP) { part -= PP; px += 1; g += (uint32_t)c.cp_g; ix += t.gsw; }
-        if (px >= t.TPW) { px -= t.TPW; g += (uint32_t)c.cx_g; iy += t.gsh; ix -= c.cx_ix; }
+        const bool exists = ltid + u * kLoaderThreads < npieces;
+        xg[u] = exists ? (int)g : -1;
+        xl[u] = l;
+        xq[u] = part << 20 | iy << 10 | ix;
+        load_piece(u, o);
+        part += c.s_part; px += c.s_px; l += c.s_l; g += (uint32_t)c.s_g; iy += c.s_iy; ix += c.s_ix;
+        if (part >= PP) { part -= PP; px += 1; l += c.cp_l; g += (uint32_t)c.cp_g; ix += t.gsw; }
+        if (px >= t.TPW) { px -= t.TPW; l += c.cx_l; g += (uint32_t)c.cx_g; iy += t.gsh; ix -= c.cx_ix; }
       }
     };
-    auto commit_patch = [&]() {
-      int part = part0, px = px0, l = l0;
+    auto issue_patch = [&](int tl, int sl) {
+      const Origin o = origin(tl, sl);
 #pragma unroll
-      for (int u = 0; u < kXBatch; ++u) {
-        if (ltid + u * kLoaderThreads < npieces) *(u32x4_t*)(lds + l) = xv[u];
-        part += c.s_part; px += c.s_px; l += c.s_l;
-        if (part >= PP) { part -= PP; px += 1; l += c.cp_l; }
-        if (px >= t.TPW) { px -= t.TPW; l += c.cx_l; }
-      }
+      for (int u = 0; u < kXBatch; ++u) load_piece(u, o);
+    };
+    auto commit_patch = [&]() {
+#pragma unroll
+      for (int u = 0; u < kXBatch; ++u)
+        if (xg[u] >= 0) *(u32x4_t*)(lds + xl[u]) = xv[u];
     };
     // results of tile tl: LDS staging tile -> Y as whole 16-byte pieces, eight consecutive
     // lanes covering the 64 output channels (128 bytes) of one pixel
@@ -191,19 +206,23 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
       const int oy0 = tyi * t.TH, ox0 = (trem - tyi * t.tiles_x) * t.TW;
       uint16_t* yorg = Y + (((int64_t)n * p.M + oy0) * p.N + ox0) * p.O + sg * 64;
       const int my = p.M - oy0, mx = p.N - ox0;  // rows / columns of the tile inside the image
-      u32x4_t ov[NT];
+      // four pieces at a time: reads first, then the stores, so that neither waits on the other
 #pragma unroll
-      for (int k = 0; k < NT; ++k)
-        ov[k] = *(const u32x4_t*)(lds + c.obuf_off + ((ltid >> 3) + 32 * k) * kOutRow + (ltid & 7) * 16);
+      for (int k0 = 0; k0 < NT; k0 += 4) {
+        u32x4_t ov[4];
 #pragma unroll
-      for (int k = 0; k < NT; ++k) {
-        const int f = fpos[k];
-        if (f >= 0 && (f >> 16) < my && (f & 0xFFFF) < mx) *(u32x4_t*)(yorg + foff[k]) = ov[k];
+        for (int k = k0; k < k0 + 4 && k < NT; ++k)
+          ov[k - k0] = *(const u32x4_t*)(lds + c.obuf_off + ((ltid >> 3) + 32 * k) * kOutRow + (ltid & 7) * 16);
+#pragma unroll
+        for (int k = k0; k < k0 + 4 && k < NT; ++k) {
+          const int f = fpos[k];
+          if (f >= 0 && (f >> 16) < my && (f & 0xFFFF) < mx) *(u32x4_t*)(yorg + foff[k]) = ov[k - k0];
+        }
       }
     };
 
     int sl = 0;
-    issue_patch(tile, 0);
+    first_patch(tile);
     commit_patch();
     __syncthreads();  // A: first unit is in LDS
     int flush_tile = -1;
