@@ -42,6 +42,7 @@ struct LdsCfg {
   int32_t obuf_off;       // LDS offset of the results staging tile
   int32_t maxsteps;       // most steps any (strip, slab) has
   int32_t nsteps;         // steps in the whole plan
+  int32_t mover_first;    // raise the data movers' wave priority
   int32_t groups;         // strip groups (of four)
   int32_t wg_per_group;   // workgroups sharing one strip group
   int32_t off_slab, off_xdesc, off_wfrag;  // plan sections, in words (read on the host)
@@ -116,8 +117,9 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
 
   if (loader) {
     // =================================================================== data movers
-    // few instructions, but everything waits on them: issue ahead of the compute waves
-    __builtin_amdgcn_s_setprio(3);
+    // few instructions, but where units are short everything waits on them: then they
+    // issue ahead of the compute waves
+    if (c.mover_first) __builtin_amdgcn_s_setprio(3);
     const int ltid = tid - kComputeThreads;
     const uint16_t* X = (const uint16_t*)p.X;
     // The patch is cut into 16-byte pieces (pixel-major, 8 channels each); this thread
@@ -479,6 +481,9 @@ int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hip
     c.cx_g = (t.gsh * p.J - t.TPW * t.gsw) * p.I;
     c.cx_ix = t.TPW * t.gsw;
   }
+  // long compute phases (windows over several slabs) hide the movers anyway, and their
+  // instructions then only take issue slots from the matrix cores
+  c.mover_first = !(p.H * p.K > 1 && nslabs > 1);
   c.nsteps = hdr[BSP_PLAN_NSTEPS_W];
   c.off_slab = hdr[BSP_PLAN_OFF_SLAB_W];
   c.off_xdesc = hdr[BSP_PLAN_OFF_XDESC_W];
