@@ -155,6 +155,7 @@ typedef struct bsp_weights {
  *   stream   a hipStream_t passed as void* (null = default stream)
  * Accumulation is fp32; bias is added in fp32; the result is rounded once
  * (nearest-even) to w->dtype.  Asynchronous: returns after the launch.
+ * B = 0 is valid and does nothing (X and Y may then be null).
  * Errors: NULL, SHAPE, UNSUPPORTED, DTYPE, ALIGN, HIP. */
 int bsp_fc(const bsp_weights* w, const void* X, const float* bias, void* Y,
            int32_t B, void* stream);

@@ -24,7 +24,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 int prepare(const bsp_weights* w, const void* X, const float* bias, void* Y, int32_t B,
             int32_t L, int32_t J, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
             ConvParams* out) {
-  if (!w || !X || !Y) return BSP_ERR_NULL;
+  if (!w || (B != 0 && (!X || !Y))) return BSP_ERR_NULL;  // an empty batch needs no X or Y
   if (!w->plan) return BSP_ERR_NULL;
   if (w->nnzb > 0 && !w->payload) return BSP_ERR_NULL;
   if (w->O <= 0 || w->I <= 0 || w->H <= 0 || w->K <= 0 || w->nnzb < 0) return BSP_ERR_SHAPE;
@@ -41,7 +41,7 @@ int prepare(const bsp_weights* w, const void* X, const float* bias, void* Y, int
       (int64_t)B * L * J * w->I > lim * 4)
     return BSP_ERR_SHAPE;
   if (w->plan_bytes < (int64_t)BSP_PLAN_HEADER_WORDS * 4) return BSP_ERR_CAPACITY;
-  if (!aligned16(X) || !aligned16(Y) || !aligned16(w->payload) || !aligned16(w->plan) ||
+  if ((B != 0 && (!aligned16(X) || !aligned16(Y))) || !aligned16(w->payload) || !aligned16(w->plan) ||
       (reinterpret_cast<uintptr_t>(bias) & 3u))
     return BSP_ERR_ALIGN;
   ConvParams p;
@@ -100,7 +100,7 @@ int bsp_conv2d(const bsp_weights* w, const void* X, const float* bias, void* Y, 
 
 int bsp_fc(const bsp_weights* w, const void* X, const float* bias, void* Y, int32_t B,
            void* stream) {
-  if (!w || !X || !Y) return BSP_ERR_NULL;
+  if (!w || (B != 0 && (!X || !Y))) return BSP_ERR_NULL;
   if (w->H != 1 || w->K != 1) return BSP_ERR_SHAPE;
   return bsp_conv2d(w, X, bias, Y, B, 1, 1, 1, 1, 0, 0, stream);
 }

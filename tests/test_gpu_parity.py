@@ -142,3 +142,68 @@ def test_config2_granularity_sweep():
         print(c.name, flush=True)
         y = gpu_conv(c)
         assert_close(y, oracle_conv(c), "bf16", c.name)
+
+
+EDGE_SHAPES = [
+    (2, 20, 20, 64, 64, 3, 3, (1, 1), (1, 1)),      # LDS-resident kernel, one slab
+    (1, 14, 14, 192, 128, 3, 3, (1, 1), (1, 1)),    # three slabs, two strip groups
+    (3, 13, 13, 128, 96, 1, 1, (1, 1), (0, 0)),     # pointwise, ragged strip group
+    (8, 1, 1, 512, 48, 1, 1, (1, 1), (0, 0)),       # weight-streaming FC
+]
+
+
+@pytest.mark.parametrize("kind,d", [("bernoulli", 0.1), ("bernoulli", 0.9), ("row_balanced", 0.5),
+                                    ("exact", 0.25)])
+def test_mask_extremes(kind, d):
+    """Very sparse masks leave whole block rows and whole strips without any kept block
+    (their outputs must be the bias alone); very dense ones fill every step."""
+    for n, shape in enumerate(EDGE_SHAPES):
+        c = _draw(shape, 2000 + n, 8, 8, "bf16", kind=kind, d=d)
+        if kind == "bernoulli" and d < 0.5:
+            c.gamma = c.gamma.copy()
+            c.gamma.reshape(-(-c.O // 8), -1)[1::3, :] = 0      # empty block rows
+            c.gamma.reshape(-(-c.O // 8), -1)[4:6, :] = 0       # one empty strip
+        print("case", n, shape, kind, d, "nnzb", int(c.gamma.sum()), flush=True)
+        assert_close(gpu_conv(c), oracle_conv(c), "bf16", f"{kind} {d} shape {n}")
+
+
+def test_nothing_is_written_outside_y():
+    """Y sits in the middle of a larger buffer filled with a sentinel; every kernel of
+    the dispatcher must leave the guard zones untouched."""
+    import torch
+    for n, shape in enumerate(SHAPES + EDGE_SHAPES):
+        c = _draw(shape, 3000 + n, 8, 8, "bf16")
+        layer = make_layer(c)
+        oshape = layer.out_shape(c.B, c.L, c.J, c.stride, c.pad)
+        numel = int(np.prod(oshape))
+        guard = 4096
+        buf = torch.full((numel + 2 * guard,), -7.0, dtype=torch.bfloat16, device="cuda")
+        Y = buf[guard:guard + numel].view(oshape)
+        layer.conv2d(to_device(c), c.stride, c.pad, out=Y)
+        torch.cuda.synchronize()
+        assert bool((buf[:guard] == -7.0).all()) and bool((buf[guard + numel:] == -7.0).all()), shape
+        assert_close(to_host(Y), oracle_conv(c), "bf16", f"guarded shape {n}")
+
+
+def test_repeated_launches_give_identical_bits():
+    import torch
+    for shape in EDGE_SHAPES:
+        c = _draw(shape, 4000, 8, 8, "bf16")
+        layer = make_layer(c)
+        X = to_device(c)
+        Y1 = layer.conv2d(X, c.stride, c.pad).clone()
+        Y2 = layer.conv2d(X, c.stride, c.pad)
+        torch.cuda.synchronize()
+        assert torch.equal(Y1, Y2)
+
+
+def test_empty_batch_is_a_no_op():
+    import torch
+    c = _draw(EDGE_SHAPES[0], 5000, 8, 8, "bf16")
+    layer = make_layer(c)
+    X = torch.zeros((1, c.L, c.J, c.I), dtype=torch.bfloat16, device="cuda")[:0]
+    Yb = torch.full(layer.out_shape(1, c.L, c.J, c.stride, c.pad), -7.0, dtype=torch.bfloat16,
+                    device="cuda")
+    Y = layer.conv2d(X, c.stride, c.pad, out=Yb[:0])
+    torch.cuda.synchronize()
+    assert Y.shape[0] == 0 and bool((Yb == -7.0).all())
