@@ -218,7 +218,10 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
 #pragma unroll
         for (int k = k0; k < k0 + 4 && k < NT; ++k) {
           const int f = fpos[k];
-          if (f >= 0 && (f >> 16) < my && (f & 0xFFFF) < mx) *(u32x4_t*)(yorg + foff[k]) = ov[k - k0];
+          // streaming store: results are not read again here, and lines left dirty in L2
+          // would all be written back in one burst when the kernel ends
+          if (f >= 0 && (f >> 16) < my && (f & 0xFFFF) < mx)
+            __builtin_nontemporal_store(ov[k - k0], (u32x4_t*)(yorg + foff[k]));
         }
       }
     };
