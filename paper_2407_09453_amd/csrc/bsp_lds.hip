@@ -132,15 +132,8 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
     const int npieces = t.TPH * t.TPW * PP;
     int xg[kXBatch], xl[kXBatch], xq[kXBatch];
     // the results staging tile: piece q = ltid + 256 k is channels 8 (q & 7).. of pixel q >> 3
+    // (filled in once the first unit's loads are on their way)
     int fpos[NT], foff[NT];
-#pragma unroll
-    for (int k = 0; k < NT; ++k) {
-      const int pi = (ltid >> 3) + 32 * k;
-      int ty, tx;
-      tile_pos(t, pi >> 4, pi & 15, &ty, &tx);
-      fpos[k] = (ty < t.TH && tx < t.TW && sg * 64 + (ltid & 7) * 8 < p.O) ? (ty << 16 | tx) : -1;
-      foff[k] = (ty * p.N + tx) * p.O + (ltid & 7) * 8;
-    }
 
     u32x4_t xv[kXBatch];
     // X + origin of the patch may point before the image (padding); only in-image pieces are read
@@ -228,6 +221,14 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
 
     int sl = 0;
     first_patch(tile);
+#pragma unroll
+    for (int k = 0; k < NT; ++k) {
+      const int pi = (ltid >> 3) + 32 * k;
+      int ty, tx;
+      tile_pos(t, pi >> 4, pi & 15, &ty, &tx);
+      fpos[k] = (ty < t.TH && tx < t.TW && sg * 64 + (ltid & 7) * 8 < p.O) ? (ty << 16 | tx) : -1;
+      foff[k] = (ty * p.N + tx) * p.O + (ltid & 7) * 8;
+    }
     commit_patch();
     __syncthreads();  // A: first unit is in LDS
     int flush_tile = -1;
