@@ -1,3 +1,5 @@
 """CPU oracle (test infrastructure only; see oracle.py)."""
 from .oracle import *  # noqa: F401,F403
 from .oracle import build  # noqa: F401
+from .quant import (conv2d_i8, fc_i8, pack_reference_i8, quantize_eq8,  # noqa: F401
+                    requant_shift)
