@@ -19,8 +19,8 @@
  * Block-compressed weights (compressed block row, Section III):
  *   row_ptr  [ceil(O/b_o)+1] int32   exclusive prefix sums of kept blocks per block row
  *   col_idx  [nnzb] int32            kept block columns of each row, ascending
- *   payload  [nnzb][b_o][H][K][b_i]  the kept blocks, fp32 or bf16; where a block
- *                                    overhangs O or I the missing entries are +0
+ *   payload  [nnzb][b_o][H][K][b_i]  the kept blocks, fp32, bf16 or int8 codes; where a
+ *                                    block overhangs O or I the missing entries are +0
  * For given (W, Gamma) these three arrays are unique, so they are compared
  * bit for bit.
  *
@@ -50,7 +50,7 @@ enum bsp_status {
   BSP_ERR_ALIGN = -9        /* a device pointer is not 16-byte aligned */
 };
 
-enum bsp_dtype { BSP_F32 = 0, BSP_BF16 = 1 };
+enum bsp_dtype { BSP_F32 = 0, BSP_BF16 = 1, BSP_I8 = 2, BSP_I32 = 3 };
 
 /* Static, never-null description of a status code. */
 const char* bsp_strerror(int code);
@@ -72,10 +72,11 @@ int bsp_pack_count(const uint8_t* gamma, int32_t O, int32_t I, int32_t bo, int32
                    int64_t* nnzb);
 
 /* Build row_ptr / col_idx / payload.
- *   W               dense weights [O][H][K][I], element type w_dtype (BSP_F32, or
- *                   BSP_BF16 as raw 16-bit patterns)
+ *   W               dense weights [O][H][K][I], element type w_dtype (BSP_F32,
+ *                   BSP_BF16 as raw 16-bit patterns, or BSP_I8 codes)
  *   payload_dtype   BSP_F32 or BSP_BF16.  fp32 -> bf16 rounds to nearest, ties to
- *                   even; bf16 -> fp32 widens exactly.
+ *                   even; bf16 -> fp32 widens exactly.  BSP_I8 codes are copied
+ *                   (w_dtype and payload_dtype must then both be BSP_I8).
  *   row_ptr         out, ceil(O/bo)+1 entries
  *   col_idx         out, nnzb entries
  *   payload         out, nnzb*bo*H*K*bi elements of payload_dtype
@@ -175,6 +176,39 @@ int bsp_conv2d_general(const bsp_weights* w, const void* X, const float* bias, v
                        int32_t B, int32_t L, int32_t J,
                        int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
                        void* stream);
+
+/* ------------------------------------------------------------- 8-bit integers
+ * The paper deploys 8-bit integer layers (Section I: "we quantize to 8-bit integer
+ * computations"; Section III: weights 8 bits, bias 32 bits; Section V: INT8 tensors
+ * with power-of-two scales).
+ */
+
+/* Host.  Round-to-nearest quantizer of Section V, Eq. (8):
+ *   Delta = max|W| / 2^(bits-1),  code = Round(W / Delta)  (ties to even),
+ * codes clamped to [-2^(bits-1), 2^(bits-1) - 1] (only +max|W| itself is clamped).
+ *   W      n floats;  codes  n int8 out;  delta  out (0 when W is all zero)
+ *   bits   2..8
+ * Errors: NULL, SHAPE (n < 0 or bits out of range). */
+int bsp_quantize(const float* W, int64_t n, int32_t bits, int8_t* codes, double* delta);
+
+/* Device.  Integer layer on packed int8 codes (bsp_pack with w_dtype = payload_dtype =
+ * BSP_I8; plan built for BSP_I8):
+ *   acc = bias + sum over kept blocks of W_code * X_code          (exact, 32 bits)
+ *   X       int8  [B][L][J][I];  bias  int32 [O] or null
+ *   y_dtype BSP_I32: Y int32 [B][M][N][O] = acc (shift ignored)
+ *           BSP_I8:  Y int8 = saturate((acc + 2^(shift-1)) >> shift), shift 0..31
+ *                    (power-of-two output scale, round to nearest, ties upward)
+ * Same shape, stream, B = 0 and error conventions as bsp_conv2d; DTYPE if the weights
+ * are not BSP_I8 or y_dtype is neither; SHAPE if shift is out of range.  X needs 8-byte,
+ * Y and the payload 16-byte alignment. */
+int bsp_conv2d_i8(const bsp_weights* w, const int8_t* X, const int32_t* bias, void* Y,
+                  int32_t y_dtype, int32_t shift, int32_t B, int32_t L, int32_t J,
+                  int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                  void* stream);
+
+/* The 1x1 case on X[B][I] (Section III: a GEMM is a 1x1 convolution). */
+int bsp_fc_i8(const bsp_weights* w, const int8_t* X, const int32_t* bias, void* Y,
+              int32_t y_dtype, int32_t shift, int32_t B, void* stream);
 
 #ifdef __cplusplus
 }

@@ -7,15 +7,21 @@ without the built library raises.
 from .binding import (  # noqa: F401
     BSP_BF16,
     BSP_F32,
+    BSP_I8,
+    BSP_I32,
     BspError,
     BspLayer,
+    BspLayerI8,
     bsp_conv2d,
     bsp_conv2d_general,
+    bsp_conv2d_i8,
     bsp_fc,
+    bsp_fc_i8,
     bsp_pack,
     bsp_pack_count,
     bsp_plan_build,
     bsp_plan_size,
+    bsp_quantize,
     bsp_strerror,
     bsp_unpack,
     bsp_validate,

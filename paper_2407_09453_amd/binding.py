@@ -15,6 +15,8 @@ import numpy as np
 
 BSP_F32 = 0
 BSP_BF16 = 1
+BSP_I8 = 2
+BSP_I32 = 3
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libbsp.so")
@@ -22,7 +24,7 @@ _lib = None
 
 EXPORTS = ("bsp_strerror", "bsp_version", "bsp_pack_count", "bsp_pack", "bsp_unpack",
            "bsp_validate", "bsp_plan_size", "bsp_plan_build", "bsp_fc", "bsp_conv2d",
-           "bsp_conv2d_general")
+           "bsp_conv2d_general", "bsp_quantize", "bsp_conv2d_i8", "bsp_fc_i8")
 
 
 class BspError(RuntimeError):
@@ -80,6 +82,12 @@ def load_library():
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [wp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]
+    lib.bsp_quantize.restype = ctypes.c_int
+    lib.bsp_quantize.argtypes = [vp, i64, i32, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.bsp_conv2d_i8.restype = ctypes.c_int
+    lib.bsp_conv2d_i8.argtypes = [wp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp]
+    lib.bsp_fc_i8.restype = ctypes.c_int
+    lib.bsp_fc_i8.argtypes = [wp, vp, vp, vp, i32, i32, i32, vp]
     _lib = lib
     return lib
 
@@ -98,6 +106,8 @@ def _np_dtype(code: int):
         return np.float32
     if code == BSP_BF16:
         return np.uint16
+    if code == BSP_I8:
+        return np.int8
     raise BspError(-5, "dtype")
 
 
@@ -124,7 +134,7 @@ def bsp_pack(W: np.ndarray, gamma: np.ndarray, bo: int, bi: int,
     """(row_ptr, col_idx, payload[nnzb][bo][H][K][bi]).  ``W`` is float32, or
     uint16 holding bf16 bit patterns."""
     if w_dtype is None:
-        w_dtype = BSP_BF16 if W.dtype == np.uint16 else BSP_F32
+        w_dtype = BSP_BF16 if W.dtype == np.uint16 else BSP_I8 if W.dtype == np.int8 else BSP_F32
     W = np.ascontiguousarray(W, dtype=_np_dtype(w_dtype))
     O, H, K, I = W.shape
     g = np.ascontiguousarray(gamma, dtype=np.uint8)
@@ -143,7 +153,7 @@ def bsp_pack(W: np.ndarray, gamma: np.ndarray, bo: int, bi: int,
 
 
 def bsp_unpack(row_ptr, col_idx, payload, O, H, K, I, bo, bi) -> np.ndarray:
-    code = BSP_BF16 if payload.dtype == np.uint16 else BSP_F32
+    code = _payload_code(payload)
     W = np.empty((O, H, K, I), dtype=payload.dtype)
     _check(load_library().bsp_unpack(_np_ptr(np.ascontiguousarray(row_ptr, dtype=np.int32)),
                                      _np_ptr(np.ascontiguousarray(col_idx, dtype=np.int32)),
@@ -160,7 +170,18 @@ def bsp_validate(row_ptr, col_idx, O, I, bo, bi) -> int:
 
 
 def _payload_code(payload: np.ndarray) -> int:
-    return BSP_BF16 if payload.dtype == np.uint16 else BSP_F32
+    return BSP_BF16 if payload.dtype == np.uint16 else BSP_I8 if payload.dtype == np.int8 \
+        else BSP_F32
+
+
+def bsp_quantize(W: np.ndarray, bits: int = 8) -> Tuple[np.ndarray, float]:
+    """(int8 codes of the same shape, Delta) by the round-to-nearest quantizer."""
+    Wf = np.ascontiguousarray(W, dtype=np.float32)
+    codes = np.zeros(Wf.shape, dtype=np.int8)
+    delta = ctypes.c_double(0.0)
+    _check(load_library().bsp_quantize(_np_ptr(Wf), Wf.size, bits, _np_ptr(codes),
+                                       ctypes.byref(delta)), "bsp_quantize")
+    return codes, delta.value
 
 
 def bsp_plan_size(row_ptr, col_idx, O, H, K, I, bo, bi, payload_dtype: int) -> int:
@@ -202,6 +223,19 @@ def bsp_conv2d_general(w: bsp_weights, X: int, bias: Optional[int], Y: int, B: i
     _check(load_library().bsp_conv2d_general(ctypes.byref(w), X, bias, Y, B, L, J, stride[0],
                                              stride[1], pad[0], pad[1], stream),
            "bsp_conv2d_general")
+
+
+def bsp_conv2d_i8(w: bsp_weights, X: int, bias: Optional[int], Y: int, y_dtype: int, shift: int,
+                  B: int, L: int, J: int, stride=(1, 1), pad=(0, 0), stream: int = 0) -> None:
+    _check(load_library().bsp_conv2d_i8(ctypes.byref(w), X, bias, Y, y_dtype, shift, B, L, J,
+                                        stride[0], stride[1], pad[0], pad[1], stream),
+           "bsp_conv2d_i8")
+
+
+def bsp_fc_i8(w: bsp_weights, X: int, bias: Optional[int], Y: int, y_dtype: int, shift: int,
+              B: int, stream: int = 0) -> None:
+    _check(load_library().bsp_fc_i8(ctypes.byref(w), X, bias, Y, y_dtype, shift, B, stream),
+           "bsp_fc_i8")
 
 
 class BspLayer:
@@ -273,4 +307,72 @@ class BspLayer:
         st = torch.cuda.current_stream(X.device).cuda_stream if stream is None else stream
         bsp_fc(self.struct, X.data_ptr(),
                None if self.d_bias is None else self.d_bias.data_ptr(), out.data_ptr(), B, st)
+        return out
+
+
+class BspLayerI8:
+    """An 8-bit integer layer resident on a GPU: int8 weight codes [O][H][K][I] (e.g. from
+    ``bsp_quantize``), block mask, optional int32 bias.  X is int8; Y is int8 after a rounding
+    right shift, or the exact int32 sums when ``shift`` is None."""
+
+    def __init__(self, Wq: np.ndarray, gamma: np.ndarray, bo: int, bi: int,
+                 bias: Optional[np.ndarray] = None, device: str = "cuda:0"):
+        import torch
+        load_library()
+        Wq = np.ascontiguousarray(Wq, dtype=np.int8)
+        O, H, K, I = Wq.shape
+        self.O, self.H, self.K, self.I, self.bo, self.bi = O, H, K, I, bo, bi
+        self.row_ptr, self.col_idx, self.payload = bsp_pack(Wq, gamma, bo, bi, BSP_I8)
+        self.plan = bsp_plan_build(self.row_ptr, self.col_idx, self.payload, O, H, K, I, bo, bi)
+        self.nnzb = int(self.col_idx.size)
+        self.device = torch.device(device)
+        self.d_payload = torch.zeros(max(self.payload.size, 16), dtype=torch.int8,
+                                     device=self.device)
+        if self.payload.size:
+            self.d_payload[:self.payload.size].copy_(torch.from_numpy(self.payload.reshape(-1)))
+        self.d_row_ptr = torch.from_numpy(self.row_ptr).to(self.device)
+        self.d_col_idx = torch.from_numpy(self.col_idx if self.nnzb
+                                          else np.zeros(1, np.int32)).to(self.device)
+        self.d_plan = torch.from_numpy(self.plan).to(self.device)
+        self.d_bias = None if bias is None else \
+            torch.from_numpy(np.ascontiguousarray(bias, dtype=np.int32)).to(self.device)
+        self.struct = bsp_weights(O, I, H, K, bo, bi, BSP_I8, 0, self.nnzb,
+                                  self.d_row_ptr.data_ptr(), self.d_col_idx.data_ptr(),
+                                  self.d_payload.data_ptr(), self.d_plan.data_ptr(),
+                                  self.plan.nbytes, self.plan.ctypes.data)
+
+    def out_shape(self, B, L, J, stride, pad):
+        M = (L + 2 * pad[0] - self.H) // stride[0] + 1
+        N = (J + 2 * pad[1] - self.K) // stride[1] + 1
+        return (B, M, N, self.O)
+
+    def conv2d(self, X, stride=(1, 1), pad=(0, 0), shift: Optional[int] = None, out=None,
+               stream=None):
+        """X: int8 torch tensor [B][L][J][I] on the layer's device, contiguous."""
+        import torch
+        assert X.is_contiguous() and X.dtype == torch.int8 and X.shape[-1] == self.I
+        B, L, J, _ = X.shape
+        ydt = torch.int32 if shift is None else torch.int8
+        if out is None:
+            out = torch.empty(self.out_shape(B, L, J, stride, pad), dtype=ydt, device=X.device)
+        assert out.dtype == ydt
+        st = torch.cuda.current_stream(X.device).cuda_stream if stream is None else stream
+        bsp_conv2d_i8(self.struct, X.data_ptr(),
+                      None if self.d_bias is None else self.d_bias.data_ptr(), out.data_ptr(),
+                      BSP_I32 if shift is None else BSP_I8, 0 if shift is None else shift,
+                      B, L, J, stride, pad, st)
+        return out
+
+    def fc(self, X, shift: Optional[int] = None, out=None, stream=None):
+        """X: int8 torch tensor [B][I]."""
+        import torch
+        assert X.is_contiguous() and X.dtype == torch.int8 and X.shape[-1] == self.I
+        B = X.shape[0]
+        ydt = torch.int32 if shift is None else torch.int8
+        if out is None:
+            out = torch.empty((B, self.O), dtype=ydt, device=X.device)
+        st = torch.cuda.current_stream(X.device).cuda_stream if stream is None else stream
+        bsp_fc_i8(self.struct, X.data_ptr(),
+                  None if self.d_bias is None else self.d_bias.data_ptr(), out.data_ptr(),
+                  BSP_I32 if shift is None else BSP_I8, 0 if shift is None else shift, B, st)
         return out

@@ -23,14 +23,15 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 int prepare(const bsp_weights* w, const void* X, const float* bias, void* Y, int32_t B,
             int32_t L, int32_t J, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
-            ConvParams* out) {
+            ConvParams* out, bool integer = false) {
   if (!w || (B != 0 && (!X || !Y))) return BSP_ERR_NULL;  // an empty batch needs no X or Y
   if (!w->plan) return BSP_ERR_NULL;
   if (w->nnzb > 0 && !w->payload) return BSP_ERR_NULL;
   if (w->O <= 0 || w->I <= 0 || w->H <= 0 || w->K <= 0 || w->nnzb < 0) return BSP_ERR_SHAPE;
   if (!((w->bo == 8 && w->bi == 8) || (w->bo == 4 && w->bi == 16) || (w->bo == 16 && w->bi == 4)))
     return BSP_ERR_UNSUPPORTED;
-  if (w->dtype != BSP_F32 && w->dtype != BSP_BF16) return BSP_ERR_DTYPE;
+  if (integer ? w->dtype != BSP_I8 : (w->dtype != BSP_F32 && w->dtype != BSP_BF16))
+    return BSP_ERR_DTYPE;
   if (B < 0 || L <= 0 || J <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return BSP_ERR_SHAPE;
   if (L + 2 * (int64_t)ph < w->H || J + 2 * (int64_t)pw < w->K) return BSP_ERR_SHAPE;
   const int64_t M = (L + 2 * (int64_t)ph - w->H) / sh + 1;
@@ -41,7 +42,8 @@ int prepare(const bsp_weights* w, const void* X, const float* bias, void* Y, int
       (int64_t)B * L * J * w->I > lim * 4)
     return BSP_ERR_SHAPE;
   if (w->plan_bytes < (int64_t)BSP_PLAN_HEADER_WORDS * 4) return BSP_ERR_CAPACITY;
-  if ((B != 0 && (!aligned16(X) || !aligned16(Y))) || !aligned16(w->payload) || !aligned16(w->plan) ||
+  if ((B != 0 && ((integer ? (reinterpret_cast<uintptr_t>(X) & 7u) != 0 : !aligned16(X)) ||
+                  !aligned16(Y))) || !aligned16(w->payload) || !aligned16(w->plan) ||
       (reinterpret_cast<uintptr_t>(bias) & 3u))
     return BSP_ERR_ALIGN;
   ConvParams p;
@@ -103,6 +105,28 @@ int bsp_fc(const bsp_weights* w, const void* X, const float* bias, void* Y, int3
   if (!w || (B != 0 && (!X || !Y))) return BSP_ERR_NULL;
   if (w->H != 1 || w->K != 1) return BSP_ERR_SHAPE;
   return bsp_conv2d(w, X, bias, Y, B, 1, 1, 1, 1, 0, 0, stream);
+}
+
+int bsp_conv2d_i8(const bsp_weights* w, const int8_t* X, const int32_t* bias, void* Y,
+                  int32_t y_dtype, int32_t shift, int32_t B, int32_t L, int32_t J,
+                  int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                  void* stream) {
+  ConvParams p;
+  if (int rc = prepare(w, X, (const float*)bias, Y, B, L, J, stride_h, stride_w, pad_h, pad_w, &p,
+                       true))
+    return rc;
+  if (y_dtype != BSP_I8 && y_dtype != BSP_I32) return BSP_ERR_DTYPE;
+  if (y_dtype == BSP_I8 && (shift < 0 || shift > 31)) return BSP_ERR_SHAPE;
+  if (p.P == 0) return BSP_OK;
+  return bsp_launch_i8(p, y_dtype == BSP_I8, y_dtype == BSP_I8 ? shift : 0, w->bo, w->bi,
+                       (hipStream_t)stream);
+}
+
+int bsp_fc_i8(const bsp_weights* w, const int8_t* X, const int32_t* bias, void* Y,
+              int32_t y_dtype, int32_t shift, int32_t B, void* stream) {
+  if (!w || (B != 0 && (!X || !Y))) return BSP_ERR_NULL;
+  if (w->H != 1 || w->K != 1) return BSP_ERR_SHAPE;
+  return bsp_conv2d_i8(w, X, bias, Y, y_dtype, shift, B, 1, 1, 1, 1, 0, 0, stream);
 }
 
 }  // extern "C"

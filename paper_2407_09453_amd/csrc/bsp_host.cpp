@@ -4,6 +4,7 @@
 #include "bsp.h"
 #include "bsp_plan.h"
 
+#include <cmath>
 #include <cstring>
 #include <limits>
 #include <vector>
@@ -42,6 +43,7 @@ template <> inline float convert<float, float>(float v) { return v; }
 template <> inline uint16_t convert<uint16_t, uint16_t>(uint16_t v) { return v; }
 template <> inline uint16_t convert<float, uint16_t>(float v) { return f32_to_bf16(v); }
 template <> inline float convert<uint16_t, float>(uint16_t v) { return bf16_to_f32(v); }
+template <> inline int8_t convert<int8_t, int8_t>(int8_t v) { return v; }
 
 // Copy the kept blocks of W, block row by block row, column ascending.
 template <typename Src, typename Dst>
@@ -139,15 +141,19 @@ int bsp_pack(const void* W, int32_t w_dtype, const uint8_t* gamma, int32_t O, in
   if (H <= 0 || K <= 0) return BSP_ERR_SHAPE;
   int64_t nnzb = 0;
   if (int rc = bsp_pack_count(gamma, O, I, bo, bi, &nnzb)) return rc;
-  if ((w_dtype != BSP_F32 && w_dtype != BSP_BF16) ||
-      (payload_dtype != BSP_F32 && payload_dtype != BSP_BF16))
+  const bool codes = w_dtype == BSP_I8 || payload_dtype == BSP_I8;
+  if (codes ? (w_dtype != payload_dtype)
+            : ((w_dtype != BSP_F32 && w_dtype != BSP_BF16) ||
+               (payload_dtype != BSP_F32 && payload_dtype != BSP_BF16)))
     return BSP_ERR_DTYPE;
   if (nnzb > 0 && (!col_idx || !payload)) return BSP_ERR_NULL;
   if (nnzb > std::numeric_limits<int32_t>::max()) return BSP_ERR_SHAPE;
-  const int64_t esz = payload_dtype == BSP_F32 ? 4 : 2;
+  const int64_t esz = payload_dtype == BSP_F32 ? 4 : payload_dtype == BSP_BF16 ? 2 : 1;
   if (col_capacity < nnzb) return BSP_ERR_CAPACITY;
   if (payload_capacity_bytes < nnzb * bo * bi * (int64_t)H * K * esz) return BSP_ERR_CAPACITY;
-  if (w_dtype == BSP_F32 && payload_dtype == BSP_F32)
+  if (codes)
+    compact((const int8_t*)W, gamma, O, H, K, I, bo, bi, row_ptr, col_idx, (int8_t*)payload);
+  else if (w_dtype == BSP_F32 && payload_dtype == BSP_F32)
     compact((const float*)W, gamma, O, H, K, I, bo, bi, row_ptr, col_idx, (float*)payload);
   else if (w_dtype == BSP_F32)
     compact((const float*)W, gamma, O, H, K, I, bo, bi, row_ptr, col_idx, (uint16_t*)payload);
@@ -183,13 +189,41 @@ int bsp_unpack(const int32_t* row_ptr, const int32_t* col_idx, const void* paylo
   if (!W) return BSP_ERR_NULL;
   if (H <= 0 || K <= 0) return BSP_ERR_SHAPE;
   if (int rc = bsp_validate(row_ptr, col_idx, O, I, bo, bi)) return rc;
-  if (payload_dtype != BSP_F32 && payload_dtype != BSP_BF16) return BSP_ERR_DTYPE;
+  if (payload_dtype != BSP_F32 && payload_dtype != BSP_BF16 && payload_dtype != BSP_I8)
+    return BSP_ERR_DTYPE;
   const int64_t nnzb = row_ptr[cdiv(O, bo)];
   if (nnzb > 0 && !payload) return BSP_ERR_NULL;
-  if (payload_dtype == BSP_F32)
+  if (payload_dtype == BSP_I8)
+    expand(row_ptr, col_idx, (const int8_t*)payload, O, H, K, I, bo, bi, (int8_t*)W);
+  else if (payload_dtype == BSP_F32)
     expand(row_ptr, col_idx, (const float*)payload, O, H, K, I, bo, bi, (float*)W);
   else
     expand(row_ptr, col_idx, (const uint16_t*)payload, O, H, K, I, bo, bi, (uint16_t*)W);
+  return BSP_OK;
+}
+
+int bsp_quantize(const float* W, int64_t n, int32_t bits, int8_t* codes, double* delta) {
+  if (!delta || (n > 0 && (!W || !codes))) return BSP_ERR_NULL;
+  if (n < 0 || bits < 2 || bits > 8) return BSP_ERR_SHAPE;
+  double top = 0.0;
+  for (int64_t i = 0; i < n; ++i) {
+    const double a = std::fabs((double)W[i]);
+    if (a > top) top = a;
+  }
+  if (top == 0.0) {
+    *delta = 0.0;
+    for (int64_t i = 0; i < n; ++i) codes[i] = 0;
+    return BSP_OK;
+  }
+  const double d = top / (double)(1 << (bits - 1));
+  const double lo = -(double)(1 << (bits - 1)), hi = (double)((1 << (bits - 1)) - 1);
+  for (int64_t i = 0; i < n; ++i) {
+    double q = std::nearbyint((double)W[i] / d);  // default rounding mode: ties to even
+    if (q < lo) q = lo;
+    if (q > hi) q = hi;
+    codes[i] = (int8_t)q;
+  }
+  *delta = d;
   return BSP_OK;
 }
 
@@ -199,7 +233,7 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, const void*
                      int32_t dtype, int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo,
                      int32_t bi, int32_t* out, int64_t capacity_words, int64_t* words_needed) {
   if (H <= 0 || K <= 0) return BSP_ERR_SHAPE;
-  if (dtype != BSP_F32 && dtype != BSP_BF16) return BSP_ERR_DTYPE;
+  if (dtype != BSP_F32 && dtype != BSP_BF16 && dtype != BSP_I8) return BSP_ERR_DTYPE;
   if (H > 255 || K > 255) return BSP_ERR_SHAPE;
   if (int rc = bsp_validate(row_ptr, col_idx, O, I, bo, bi)) return rc;
   const int64_t nbr = cdiv(O, bo);

@@ -21,4 +21,8 @@ int bsp_launch_fc_stream(const ConvParams& p, int dtype, int bo, int bi, hipStre
 // of the plan to size LDS.  BSP_ERR_UNSUPPORTED = not applicable, nothing launched.
 int bsp_launch_lds(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);
 
+// 8-bit integer layers: X and payload int8, bias int32 (passed through ConvParams::bias),
+// Y int8 after a rounding right shift (y_i8 = 1) or the int32 sums.
+int bsp_launch_i8(const ConvParams& p, int y_i8, int shift, int bo, int bi, hipStream_t st);
+
 #endif

@@ -1,0 +1,60 @@
+"""Host side of the 8-bit path: the C quantizer against the oracle's Eq. (8), the packer on
+int8 codes against the oracle's independent packer, error codes (no GPU needed)."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2407_09453_amd as bsp
+
+GRANS = [(8, 8), (4, 16), (16, 4)]
+
+
+@pytest.mark.parametrize("bits", [8, 4, 2])
+def test_quantizer_matches_oracle_bit_for_bit(bits):
+    rng = np.random.default_rng(bits)
+    W = (rng.standard_normal((64, 3, 3, 24)) * 0.05).astype(np.float32)
+    W.reshape(-1)[:6] = np.float32([0.0, W.max(), -np.abs(W).max(), 1e-9, -1e-9, np.abs(W).max()])
+    q, d = bsp.bsp_quantize(W, bits)
+    q0, d0 = oracle.quantize_eq8(W, bits)
+    assert d == d0 and q.dtype == np.int8 and (q == q0).all()
+
+
+def test_quantizer_hand_example_and_ties():
+    W = np.float32([0.5, -0.5, 0.009765625, 0.005859375, -0.005859375, 0.25])   # Delta = 2^-8
+    q, d = bsp.bsp_quantize(W)
+    assert d == 0.5 / 128
+    # 128 -> 127 (clamped); 2.5 -> 2 and 1.5 -> 2 (ties to even); -1.5 -> -2
+    assert q.tolist() == [127, -128, 2, 2, -2, 64]
+    z, dz = bsp.bsp_quantize(np.zeros(7, np.float32))
+    assert dz == 0.0 and not z.any()
+    with pytest.raises(bsp.BspError) as e:
+        bsp.bsp_quantize(W, 9)
+    assert e.value.code == -2
+
+
+@pytest.mark.parametrize("bo,bi", GRANS)
+@pytest.mark.parametrize("O,I,H,K", [(64, 64, 3, 3), (20, 12, 2, 3), (48, 80, 1, 7), (16, 3, 7, 7)])
+def test_pack_int8_codes_bit_exact_and_roundtrip(bo, bi, O, I, H, K):
+    rng = np.random.default_rng(O + I + H)
+    Wq = rng.integers(-128, 128, (O, H, K, I), dtype=np.int8)
+    gamma = (rng.random((-(-O // bo), -(-I // bi))) < 0.5).astype(np.uint8)
+    rp0, ci0, pl0 = oracle.pack_reference_i8(Wq, gamma, bo, bi)
+    rp, ci, pl = bsp.bsp_pack(Wq, gamma, bo, bi, bsp.BSP_I8)
+    assert pl.dtype == np.int8
+    assert (rp == rp0).all() and (ci == ci0).all() and pl.tobytes() == pl0.tobytes()
+    back = bsp.bsp_unpack(rp, ci, pl, O, H, K, I, bo, bi)
+    keep = oracle.expand_mask(gamma, O, I, bo, bi)[:, None, None, :]
+    assert back.dtype == np.int8 and (back == np.where(keep, Wq, 0)).all()
+    plan = bsp.bsp_plan_build(rp, ci, pl, O, H, K, I, bo, bi)
+    assert plan[15] == bsp.BSP_I8 and plan[18] == 0          # no bf16 step section
+
+
+def test_mixed_int8_and_float_types_are_refused():
+    Wq = np.zeros((8, 1, 1, 8), dtype=np.int8)
+    g = np.ones((1, 1), dtype=np.uint8)
+    with pytest.raises(bsp.BspError) as e:
+        bsp.bsp_pack(Wq, g, 8, 8, bsp.BSP_BF16)
+    assert e.value.code == -5
+    with pytest.raises(bsp.BspError) as e:
+        bsp.bsp_pack(Wq.astype(np.float32), g, 8, 8, bsp.BSP_I8)
+    assert e.value.code == -5
