@@ -57,6 +57,85 @@ def pick_case(name: str):
     raise SystemExit(f"unknown workload {name}")
 
 
+def bench_i8(args) -> int:
+    """Config 1's shape as an 8-bit integer layer: weights quantized by Eq. (8), int8
+    activations, int32 bias, int8 output after a power-of-two rescale."""
+    import torch
+    import paper_2407_09453_amd as bsp
+    from synthetic import config_cases
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    c = next(config_cases(1))
+    rng = np.random.default_rng(240709453 + 1001)
+    Wq, delta = bsp.bsp_quantize(c.W)
+    Xq = np.clip(np.rint(c.X * 32.0), -128, 127).astype(np.int8)      # N(0,1) at scale 2^-5
+    bias = rng.integers(-2 ** 12, 2 ** 12, c.O).astype(np.int32)
+    shift = 9
+    layer = bsp.BspLayerI8(Wq, c.gamma, c.bo, c.bi, bias=bias)
+    dense = bsp.BspLayerI8(Wq, np.ones_like(c.gamma), c.bo, c.bi, bias=bias)
+    nbr = -(-c.O // c.bo)
+    nbytes = (Xq.size + c.P * c.O + layer.nnzb * c.bo * c.bi * c.H * c.K
+              + 4 * (layer.nnzb + nbr + 1) + 4 * c.O)
+    nsets = args.sets or max(2, int(np.ceil(300e6 / nbytes)))
+    X0 = torch.from_numpy(Xq).to(dev)
+    Xs = [X0] + [X0.clone() for _ in range(nsets - 1)]
+    Ys = [torch.empty(layer.out_shape(c.B, c.L, c.J, c.stride, c.pad), dtype=torch.int8, device=dev)
+          for _ in range(nsets)]
+    stream = torch.cuda.current_stream(dev)
+
+    def timed(lay):
+        for i in range(args.warmup):
+            lay.conv2d(Xs[i % nsets], c.stride, c.pad, shift=shift, out=Ys[i % nsets])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t = time.perf_counter()
+        e0.record(stream)
+        for i in range(args.steps):
+            lay.conv2d(Xs[i % nsets], c.stride, c.pad, shift=shift, out=Ys[i % nsets])
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / args.steps, e0.elapsed_time(e1) / args.steps
+
+    ms_wall, ms_ev = timed(layer)
+    ms_wall_d, _ = timed(dense)
+    ops = 2 * c.P * layer.nnzb * c.bo * c.bi * c.H * c.K
+    achieved = nbytes / (ms_ev * 1e-3) / 1e9
+    out = {
+        "metric": "effective nonzero TOP/s (2*P*nnzb*bo*bi*H*K / t), 50% 8x8 block-sparse int8 conv",
+        "value": round(ops / (ms_wall * 1e-3) / 1e12, 4), "unit": "TOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_wall, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8",
+        "data": "synthetic",
+        "config": {"workload": "config1's shape as an int8 layer: conv3x3 s1 p1, X 32x56x56x64 "
+                               "int8, W 64x3x3x64 int8 codes (Eq. 8), int32 bias, int8 out >> 9",
+                   "block": "8x8", "nnzb": layer.nnzb, "buffer_sets": nsets,
+                   "kernel": "general int8", "delta": delta},
+        "speedup_vs_dense_mask": round(ms_wall_d / ms_wall, 4),
+        "dense_mask_ms_per_step": round(ms_wall_d, 6),
+        "event_ms_per_step": round(ms_ev, 6),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                     "algorithmic_bytes": int(nbytes)},
+        "int8_mfma_frac_of_peak": round(ops / (ms_ev * 1e-3) / 1e12 / 5000.0, 5),
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        reps, dt = 0, 0.0
+        while reps < 12 and dt * 16 < 12.0:
+            t = time.perf_counter()
+            oracle.conv2d_i8(Xq, Wq, bias, c.gamma, c.bo, c.bi, c.stride, c.pad, shift=shift)
+            dt += time.perf_counter() - t
+            reps += 1
+        out["cpu_baseline"] = {"value": round(ops * reps / dt / 1e12, 6), "unit": "TOP/s",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+                               "kind": "oracle",
+                               "sample": f"the full workload {reps} times ({dt:.2f} s wall); the integer "
+                                         "oracle takes the dense masked sum exactly and skips nothing"}
+    print(json.dumps(out))
+    return 0
+
+
 def bench_network(args, net: str) -> int:
     """Per-layer timing of a whole network-shaped stack: every layer on its own
     resident N(0,1) input (layers are independent: glue such as pooling is not
@@ -133,7 +212,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c1",
-                    help="c1 (default), c0, c2:<bo>x<bi>.d<density>, resnet50, vgg16, inception_v3")
+                    help="c1 (default), c0, c2:<bo>x<bi>.d<density>, c1_i8, resnet50, vgg16, inception_v3")
     ap.add_argument("--sets", type=int, default=0,
                     help="distinct X/Y buffer sets cycled through (0 = enough to exceed 256 MB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -148,6 +227,8 @@ def main() -> int:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); "
               "multi-GPU figures are not produced", file=sys.stderr)
         return 2
+    if args.workload == "c1_i8":
+        return bench_i8(args)
     if args.workload in ("resnet50", "vgg16", "inception_v3"):
         if args.steps == 400:
             args.steps, args.warmup = 30, 5

@@ -53,6 +53,14 @@ def load_library():
     if _lib is not None:
         return _lib
     path = os.environ.get("BSP_LIBRARY", _LIB_PATH)   # override: a differently built libbsp.so
+    # libbsp launches on streams and memory that torch owns, so both must talk to the same
+    # copy of the HIP runtime: torch ships its own, and whichever is loaded first serves the
+    # whole process.  Loading libbsp first would bring in the system copy and leave torch's
+    # handles meaningless to it (launches then fail).
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(path):
         raise RuntimeError(
             f"{path} is missing: build it with "
