@@ -89,12 +89,15 @@ int bsp_conv2d(const bsp_weights* w, const void* X, const float* bias, void* Y, 
   ConvParams p;
   if (int rc = prepare(w, X, bias, Y, B, L, J, stride_h, stride_w, pad_h, pad_w, &p)) return rc;
   if (p.P == 0) return BSP_OK;
-  if (bsp_tile_supported(p, w->dtype) && kernel_limit() >= 1) {
-    int rc = bsp_launch_fc_stream(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
+  if (w->dtype == BSP_BF16 && kernel_limit() >= 1) {
+    // each launcher declines (UNSUPPORTED, nothing launched) what lies outside its limits
+    const bool chunked = bsp_tile_supported(p, w->dtype);  // whole 8-channel chunks
+    int rc = BSP_ERR_UNSUPPORTED;
+    if (chunked) rc = bsp_launch_fc_stream(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
     if (kernel_limit() >= 2) rc = bsp_launch_lds(p, w->dtype, w->plan_host, (hipStream_t)stream);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
-    rc = bsp_launch_tile(p, w->dtype, (hipStream_t)stream);
+    if (chunked) rc = bsp_launch_tile(p, w->dtype, (hipStream_t)stream);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
   }
   return bsp_launch_general(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);

@@ -43,6 +43,7 @@ struct LdsCfg {
   int32_t maxsteps;       // most steps any (strip, slab) has
   int32_t nsteps;         // steps in the whole plan
   int32_t mover_first;    // raise the data movers' wave priority
+  int32_t narrow;         // fewer than 8 input channels: pieces are gathered element-wise
   int32_t groups;         // strip groups (of four)
   int32_t wg_per_group;   // workgroups sharing one strip group
   int32_t off_slab, off_xdesc, off_wfrag;  // plan sections, in words (read on the host)
@@ -156,8 +157,17 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
       xv[u] = u32x4_t{0u, 0u, 0u, 0u};
       const int q = xq[u];
       if (xg[u] >= 0 && (unsigned)(o.iy + ((q >> 10) & 1023)) < (unsigned)p.L &&
-          (unsigned)(o.ix + (q & 1023)) < (unsigned)p.J && o.ch0 + (q >> 20) * BSP_CHUNK < p.I)
-        xv[u] = *(const u32x4_t*)(o.org + xg[u]);
+          (unsigned)(o.ix + (q & 1023)) < (unsigned)p.J && o.ch0 + (q >> 20) * BSP_CHUNK < p.I) {
+        if (!c.narrow) {
+          xv[u] = *(const u32x4_t*)(o.org + xg[u]);
+        } else {  // the pixel's p.I < 8 channels, one by one; the rest of the chunk stays zero
+          const uint16_t* e = o.org + xg[u];
+          uint32_t h[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) h[k] = k < p.I ? e[k < p.I ? k : 0] : 0u;
+          xv[u] = u32x4_t{h[0] | h[1] << 16, h[2] | h[3] << 16, h[4] | h[5] << 16, h[6] | h[7] << 16};
+        }
+      }
     };
     // first unit: build the maps piece by piece, each piece's load leaving right away
     auto first_patch = [&](int tl) {
@@ -395,7 +405,9 @@ int launch(const ConvParams& p, const TileCfg& t, const LdsCfg& c, dim3 grid, si
 }  // namespace
 
 int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hipStream_t st) {
-  if (!plan_host || dtype != BSP_BF16 || (p_in.I % 8) != 0 || (p_in.O % 8) != 0)
+  // input channels: whole 8-channel chunks, or fewer than 8 in all (a first layer's RGB
+  // planes), which the data movers then gather element by element into one zero-padded chunk
+  if (!plan_host || dtype != BSP_BF16 || ((p_in.I % 8) != 0 && p_in.I > 8) || (p_in.O % 8) != 0)
     return BSP_ERR_UNSUPPORTED;
   const int32_t* hdr = (const int32_t*)plan_host;
   if (hdr[BSP_PLAN_MAGIC_W] != BSP_PLAN_MAGIC || hdr[BSP_PLAN_VERSION_W] != BSP_PLAN_VERSION ||
@@ -488,6 +500,7 @@ int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hip
   // long compute phases (windows over several slabs) hide the movers anyway, and their
   // instructions then only take issue slots from the matrix cores
   c.mover_first = !(p.H * p.K > 1 && nslabs > 1);
+  c.narrow = (p.I % 8) != 0;
   c.nsteps = hdr[BSP_PLAN_NSTEPS_W];
   c.off_slab = hdr[BSP_PLAN_OFF_SLAB_W];
   c.off_xdesc = hdr[BSP_PLAN_OFF_XDESC_W];
