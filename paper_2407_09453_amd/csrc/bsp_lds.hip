@@ -43,7 +43,6 @@ struct LdsCfg {
   int32_t maxsteps;       // most steps any (strip, slab) has
   int32_t nsteps;         // steps in the whole plan
   int32_t mover_first;    // raise the data movers' wave priority
-  int32_t narrow;         // fewer than 8 input channels: pieces are gathered element-wise
   int32_t groups;         // strip groups (of four)
   int32_t wg_per_group;   // workgroups sharing one strip group
   int32_t off_slab, off_xdesc, off_wfrag;  // plan sections, in words (read on the host)
@@ -87,7 +86,7 @@ __device__ __forceinline__ void tile_pos(const TileCfg& t, int gt, int j, int* t
 //   A  the unit's patch and weights are in LDS
 //   E  (single-slab layers only) the staging tile has been drained, results may go in
 //   B  the compute waves are done reading the patch and weights
-template <int NT>
+template <int NT, bool NARROW>
 __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileCfg t, LdsCfg c) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -158,14 +157,15 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
       const int q = xq[u];
       if (xg[u] >= 0 && (unsigned)(o.iy + ((q >> 10) & 1023)) < (unsigned)p.L &&
           (unsigned)(o.ix + (q & 1023)) < (unsigned)p.J && o.ch0 + (q >> 20) * BSP_CHUNK < p.I) {
-        if (!c.narrow) {
+        if constexpr (!NARROW) {
           xv[u] = *(const u32x4_t*)(o.org + xg[u]);
-        } else {  // the pixel's p.I < 8 channels, one by one; the rest of the chunk stays zero
+        } else {  // the pixel's p.I <= 4 channels, one by one (no branch between the loads);
+                  // the rest of the chunk stays zero
           const uint16_t* e = o.org + xg[u];
-          uint32_t h[8];
-#pragma unroll
-          for (int k = 0; k < 8; ++k) h[k] = k < p.I ? e[k < p.I ? k : 0] : 0u;
-          xv[u] = u32x4_t{h[0] | h[1] << 16, h[2] | h[3] << 16, h[4] | h[5] << 16, h[6] | h[7] << 16};
+          const uint32_t h0 = e[0], h1 = e[min(1, p.I - 1)], h2 = e[min(2, p.I - 1)],
+                         h3 = e[min(3, p.I - 1)];
+          xv[u] = u32x4_t{h0 | (p.I > 1 ? h1 << 16 : 0u), (p.I > 2 ? h2 : 0u) | (p.I > 3 ? h3 << 16 : 0u),
+                          0u, 0u};
         }
       }
     };
@@ -387,27 +387,27 @@ int device_cus() {
 
 constexpr int64_t kLdsPerCu = 160 * 1024;
 
-template <int NT>
+template <int NT, bool NARROW>
 int launch(const ConvParams& p, const TileCfg& t, const LdsCfg& c, dim3 grid, size_t ldsb,
            hipStream_t st) {
   static bool raised = false;  // dynamic LDS above 64 KB has to be allowed once per kernel
   if (!raised) {
-    if (hipFuncSetAttribute((const void*)conv_lds_bf16<NT>,
+    if (hipFuncSetAttribute((const void*)conv_lds_bf16<NT, NARROW>,
                             hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)kLdsPerCu) != hipSuccess)
       return BSP_ERR_HIP;
     raised = true;
   }
-  hipLaunchKernelGGL(conv_lds_bf16<NT>, grid, dim3(kThreads), ldsb, st, p, t, c);
+  hipLaunchKernelGGL((conv_lds_bf16<NT, NARROW>), grid, dim3(kThreads), ldsb, st, p, t, c);
   return hipGetLastError() == hipSuccess ? BSP_OK : BSP_ERR_HIP;
 }
 
 }  // namespace
 
 int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hipStream_t st) {
-  // input channels: whole 8-channel chunks, or fewer than 8 in all (a first layer's RGB
-  // planes), which the data movers then gather element by element into one zero-padded chunk
-  if (!plan_host || dtype != BSP_BF16 || ((p_in.I % 8) != 0 && p_in.I > 8) || (p_in.O % 8) != 0)
+  // input channels: whole 8-channel chunks, or at most 4 in all (a first layer's RGB planes),
+  // which the data movers then gather element by element into one zero-padded chunk
+  if (!plan_host || dtype != BSP_BF16 || ((p_in.I % 8) != 0 && p_in.I > 4) || (p_in.O % 8) != 0)
     return BSP_ERR_UNSUPPORTED;
   const int32_t* hdr = (const int32_t*)plan_host;
   if (hdr[BSP_PLAN_MAGIC_W] != BSP_PLAN_MAGIC || hdr[BSP_PLAN_VERSION_W] != BSP_PLAN_VERSION ||
@@ -444,7 +444,7 @@ int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hip
       t.nstrips = (p.O + BSP_STRIP - 1) / BSP_STRIP;
       // the LDS left after the weights holds the patch and the results staging tile
       if (!bsp_choose_tile(p, t.slab, kLdsPerCu - wbytes, kLoaderThreads * kXBatch, kPH, kOutRow,
-                           &NT, &t))
+                           2, &NT, &t))
         NT = 0;
       if (memo.size() > 4096) memo.clear();
       it = memo.emplace(key, std::make_pair(NT, t)).first;
@@ -500,16 +500,21 @@ int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hip
   // long compute phases (windows over several slabs) hide the movers anyway, and their
   // instructions then only take issue slots from the matrix cores
   c.mover_first = !(p.H * p.K > 1 && nslabs > 1);
-  c.narrow = (p.I % 8) != 0;
   c.nsteps = hdr[BSP_PLAN_NSTEPS_W];
   c.off_slab = hdr[BSP_PLAN_OFF_SLAB_W];
   c.off_xdesc = hdr[BSP_PLAN_OFF_XDESC_W];
   c.off_wfrag = hdr[BSP_PLAN_OFF_WFRAG_W];
   dim3 grid((unsigned)nwg);
+  if ((p.I % 8) != 0) {  // first layers are large: the two large tile shapes are enough
+    if (NT == 7) return launch<7, true>(p, t, c, grid, ldsb, st);
+    if (NT == 8) return launch<8, true>(p, t, c, grid, ldsb, st);
+    return BSP_ERR_UNSUPPORTED;
+  }
   switch (NT) {
-    case 4: return launch<4>(p, t, c, grid, ldsb, st);
-    case 7: return launch<7>(p, t, c, grid, ldsb, st);
-    case 8: return launch<8>(p, t, c, grid, ldsb, st);
+    case 2: return launch<2, false>(p, t, c, grid, ldsb, st);
+    case 4: return launch<4, false>(p, t, c, grid, ldsb, st);
+    case 7: return launch<7, false>(p, t, c, grid, ldsb, st);
+    case 8: return launch<8, false>(p, t, c, grid, ldsb, st);
     default: return BSP_ERR_UNSUPPORTED;
   }
 }

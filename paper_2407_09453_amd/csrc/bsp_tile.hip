@@ -268,14 +268,15 @@ int conflict_excess(const TileCfg& t, int NT) {
 }  // namespace
 
 bool bsp_choose_tile(const ConvParams& p, int slab, int64_t max_lds, int max_pieces, int nt_scale,
-                     int out_row_bytes, int* NT, TileCfg* out) {
+                     int out_row_bytes, int min_nt, int* NT, TileCfg* out) {
   const bool pointwise = p.H == 1 && p.K == 1;
-  static const int nts[] = {4, 7, 8};
+  static const int nts[] = {2, 4, 7, 8};
   static const int tws[] = {4, 7, 8, 14, 16, 24, 28, 32, 56, 64, 112, 128, 224, 256};
   double best = -1.0;
   for (int nt1 : nts)
     for (int tw : tws)
       for (int mode = 0; mode < 2; ++mode) {
+        if (nt1 < min_nt) continue;
         const int nt = nt1 * nt_scale;
         TileCfg t = *out;
         t.tile2x8 = mode;
@@ -358,7 +359,7 @@ int bsp_launch_tile(const ConvParams& p_in, int dtype, hipStream_t st) {
       t.slab = bsp_slab_channels(p.I, p.H, p.K);
       t.nslabs = ((p.I + 7) / 8 + t.slab / 8 - 1) / (t.slab / 8);
       t.nstrips = (p.O + BSP_STRIP - 1) / BSP_STRIP;
-      if (!bsp_choose_tile(p, t.slab, 64 * 1024, 0, 1, 0, &NT, &t)) NT = 0;
+      if (!bsp_choose_tile(p, t.slab, 64 * 1024, 0, 1, 0, 4, &NT, &t)) NT = 0;
       if (memo.size() > 4096) memo.clear();
       it = memo.emplace(key, std::make_pair(NT, t)).first;
     }
