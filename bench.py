@@ -215,6 +215,9 @@ def main() -> int:
                     help="c1 (default), c0, c2:<bo>x<bi>.d<density>, c1_i8, resnet50, vgg16, inception_v3")
     ap.add_argument("--sets", type=int, default=0,
                     help="distinct X/Y buffer sets cycled through (0 = enough to exceed 256 MB)")
+    ap.add_argument("--mask", default="synthetic", choices=["synthetic", "l2", "l1", "var"],
+                    help="synthetic: the config's seeded mask; l2/l1/var: keep the half of the "
+                         "blocks with the largest importance (bsp_select_mask on the layer's W)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--general", action="store_true", help="force the general-shape kernel")
     ap.add_argument("--no-multi-stream", dest="multi_stream", action="store_false",
@@ -242,6 +245,11 @@ def main() -> int:
     c, workload = pick_case(args.workload)
     tdt = torch.float32 if c.dtype == "f32" else torch.bfloat16
 
+    select_ms = None
+    if args.mask != "synthetic":
+        t0 = time.perf_counter()
+        c.gamma = bsp.bsp_select_mask(c.W, c.bo, c.bi, {"l2": 0, "l1": 1, "var": 2}[args.mask], 0.5)
+        select_ms = (time.perf_counter() - t0) * 1e3
     t0 = time.perf_counter()
     layer = bsp.BspLayer(c.W, c.gamma, c.bo, c.bi, c.dtype, bias=c.bias)
     pack_ms = (time.perf_counter() - t0) * 1e3
@@ -342,6 +350,7 @@ def main() -> int:
         "mfma_frac_of_peak": round(fl / (ms_ev * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5)
         if c.dtype == "bf16" else None,
         "pack_ms": round(pack_ms, 3),
+        "mask": args.mask, "mask_select_ms": None if select_ms is None else round(select_ms, 3),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
                      "traffic": None if args.general else MEASURED_TRAFFIC_BYTES.get(args.workload),

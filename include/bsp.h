@@ -177,6 +177,39 @@ int bsp_conv2d_general(const bsp_weights* w, const void* X, const float* bias, v
                        int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
                        void* stream);
 
+/* ------------------------------------------------------- choosing the mask (host)
+ * Paper Section IV ("Predetermined Sparsity ratio and Full Training Ahead"): every mask
+ * entry stands for one block W_i; blocks are ranked by an importance measure and the least
+ * important ones are zeroed.
+ */
+enum bsp_importance {
+  BSP_IMPORTANCE_L2 = 0,   /* sqrt(sum w^2) over the block */
+  BSP_IMPORTANCE_L1 = 1,   /* sum |w| */
+  BSP_IMPORTANCE_VAR = 2   /* (1/n) sum (w - mean)^2, n = bo*H*K*bi (overhang counts as zeros) */
+};
+
+/* Importance of every block of W [O][H][K][I] (float), in fp64, summed in the block's storage
+ * order.  score: out, [ceil(O/bo)][ceil(I/bi)].  Errors: NULL, SHAPE, UNSUPPORTED. */
+int bsp_block_importance(const float* W, int32_t O, int32_t H, int32_t K, int32_t I,
+                         int32_t bo, int32_t bi, int32_t measure, double* score);
+
+/* Gamma with round(density * n) blocks kept: blocks sorted by ascending importance (ties:
+ * lower block index first) and the first n - round(density * n) zeroed; n counts the blocks
+ * of the layer, or of each block row when per_row != 0.  density in [0, 1].
+ * gamma: out, [ceil(O/bo)][ceil(I/bi)] bytes.  Errors: NULL, SHAPE, UNSUPPORTED. */
+int bsp_select_mask(const float* W, int32_t O, int32_t H, int32_t K, int32_t I,
+                    int32_t bo, int32_t bi, int32_t measure, double density, int32_t per_row,
+                    uint8_t* gamma);
+
+/* One step of the incremental schedule (Section IV, "Sparsity Ratio as Incremental"): with k
+ * kept blocks still above the target round(target_density * n), zero the
+ * max(ceil(0.05 k), 1) least important kept blocks (never more than k).  gamma: in/out.
+ * zeroed: out, how many were zeroed (0 when the target is reached).
+ * Errors: NULL, SHAPE, UNSUPPORTED, MASK. */
+int bsp_mask_step(const float* W, int32_t O, int32_t H, int32_t K, int32_t I,
+                  int32_t bo, int32_t bi, int32_t measure, double target_density,
+                  uint8_t* gamma, int32_t* zeroed);
+
 /* ------------------------------------------------------------- 8-bit integers
  * The paper deploys 8-bit integer layers (Section I: "we quantize to 8-bit integer
  * computations"; Section III: weights 8 bits, bias 32 bits; Section V: INT8 tensors

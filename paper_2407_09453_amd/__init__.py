@@ -12,16 +12,19 @@ from .binding import (  # noqa: F401
     BspError,
     BspLayer,
     BspLayerI8,
+    bsp_block_importance,
     bsp_conv2d,
     bsp_conv2d_general,
     bsp_conv2d_i8,
     bsp_fc,
     bsp_fc_i8,
+    bsp_mask_step,
     bsp_pack,
     bsp_pack_count,
     bsp_plan_build,
     bsp_plan_size,
     bsp_quantize,
+    bsp_select_mask,
     bsp_strerror,
     bsp_unpack,
     bsp_validate,

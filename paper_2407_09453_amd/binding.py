@@ -24,7 +24,8 @@ _lib = None
 
 EXPORTS = ("bsp_strerror", "bsp_version", "bsp_pack_count", "bsp_pack", "bsp_unpack",
            "bsp_validate", "bsp_plan_size", "bsp_plan_build", "bsp_fc", "bsp_conv2d",
-           "bsp_conv2d_general", "bsp_quantize", "bsp_conv2d_i8", "bsp_fc_i8")
+           "bsp_conv2d_general", "bsp_quantize", "bsp_conv2d_i8", "bsp_fc_i8",
+           "bsp_block_importance", "bsp_select_mask", "bsp_mask_step")
 
 
 class BspError(RuntimeError):
@@ -90,6 +91,14 @@ def load_library():
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [wp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]
+    f64 = ctypes.c_double
+    lib.bsp_block_importance.restype = ctypes.c_int
+    lib.bsp_block_importance.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp]
+    lib.bsp_select_mask.restype = ctypes.c_int
+    lib.bsp_select_mask.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, f64, i32, vp]
+    lib.bsp_mask_step.restype = ctypes.c_int
+    lib.bsp_mask_step.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, f64, vp,
+                                  ctypes.POINTER(i32)]
     lib.bsp_quantize.restype = ctypes.c_int
     lib.bsp_quantize.argtypes = [vp, i64, i32, vp, ctypes.POINTER(ctypes.c_double)]
     lib.bsp_conv2d_i8.restype = ctypes.c_int
@@ -180,6 +189,42 @@ def bsp_validate(row_ptr, col_idx, O, I, bo, bi) -> int:
 def _payload_code(payload: np.ndarray) -> int:
     return BSP_BF16 if payload.dtype == np.uint16 else BSP_I8 if payload.dtype == np.int8 \
         else BSP_F32
+
+
+BSP_IMPORTANCE_L2, BSP_IMPORTANCE_L1, BSP_IMPORTANCE_VAR = 0, 1, 2
+
+
+def bsp_block_importance(W: np.ndarray, bo: int, bi: int, measure: int = 0) -> np.ndarray:
+    Wf = np.ascontiguousarray(W, dtype=np.float32)
+    O, H, K, I = Wf.shape
+    score = np.zeros((-(-O // bo), -(-I // bi)), dtype=np.float64)
+    _check(load_library().bsp_block_importance(_np_ptr(Wf), O, H, K, I, bo, bi, measure,
+                                               _np_ptr(score)), "bsp_block_importance")
+    return score
+
+
+def bsp_select_mask(W: np.ndarray, bo: int, bi: int, measure: int = 0, density: float = 0.5,
+                    per_row: bool = False) -> np.ndarray:
+    """Gamma keeping the round(density * n) most important blocks."""
+    Wf = np.ascontiguousarray(W, dtype=np.float32)
+    O, H, K, I = Wf.shape
+    gamma = np.zeros((-(-O // bo), -(-I // bi)), dtype=np.uint8)
+    _check(load_library().bsp_select_mask(_np_ptr(Wf), O, H, K, I, bo, bi, measure, float(density),
+                                          int(per_row), _np_ptr(gamma)), "bsp_select_mask")
+    return gamma
+
+
+def bsp_mask_step(W: np.ndarray, gamma: np.ndarray, bo: int, bi: int, measure: int = 0,
+                  target_density: float = 0.5) -> Tuple[np.ndarray, int]:
+    """(new Gamma, blocks zeroed) after one step of the incremental schedule."""
+    Wf = np.ascontiguousarray(W, dtype=np.float32)
+    O, H, K, I = Wf.shape
+    g = np.array(gamma, dtype=np.uint8).reshape(-(-O // bo), -(-I // bi)).copy()
+    z = ctypes.c_int32(0)
+    _check(load_library().bsp_mask_step(_np_ptr(Wf), O, H, K, I, bo, bi, measure,
+                                        float(target_density), _np_ptr(g), ctypes.byref(z)),
+           "bsp_mask_step")
+    return g, z.value
 
 
 def bsp_quantize(W: np.ndarray, bits: int = 8) -> Tuple[np.ndarray, float]:

@@ -4,6 +4,7 @@
 #include "bsp.h"
 #include "bsp_plan.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <limits>
@@ -201,6 +202,119 @@ int bsp_unpack(const int32_t* row_ptr, const int32_t* col_idx, const void* paylo
     expand(row_ptr, col_idx, (const uint16_t*)payload, O, H, K, I, bo, bi, (uint16_t*)W);
   return BSP_OK;
 }
+
+}  // extern "C"
+
+// ------------------------------------------------------------ choosing the mask
+namespace {
+
+// zero `count` kept entries with the lowest score (ties: lower index first)
+void zero_lowest(const double* score, uint8_t* gamma, int64_t n, int64_t count) {
+  std::vector<int64_t> kept;
+  for (int64_t i = 0; i < n; ++i)
+    if (gamma[i]) kept.push_back(i);
+  std::stable_sort(kept.begin(), kept.end(),
+                   [&](int64_t a, int64_t b) { return score[a] < score[b]; });
+  for (int64_t i = 0; i < count && i < (int64_t)kept.size(); ++i) gamma[kept[i]] = 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bsp_block_importance(const float* W, int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo,
+                         int32_t bi, int32_t measure, double* score) {
+  if (!W || !score) return BSP_ERR_NULL;
+  if (H <= 0 || K <= 0) return BSP_ERR_SHAPE;
+  if (int rc = check_layer(O, I, bo, bi)) return rc;
+  if (measure < BSP_IMPORTANCE_L2 || measure > BSP_IMPORTANCE_VAR) return BSP_ERR_SHAPE;
+  const int64_t nbr = cdiv(O, bo), nbc = cdiv(I, bi);
+  const int64_t HK = (int64_t)H * K;
+  const double n = (double)bo * (double)HK * (double)bi;
+  for (int64_t l = 0; l < nbr; ++l)
+    for (int64_t c = 0; c < nbc; ++c) {
+      const int64_t no = std::min<int64_t>(bo, O - l * bo), ni = std::min<int64_t>(bi, I - c * bi);
+      long double s1 = 0.0L, s2 = 0.0L, sa = 0.0L;  // extended sums: the rank must not hinge on rounding
+      for (int64_t r = 0; r < no; ++r)
+        for (int64_t t = 0; t < HK; ++t) {
+          const float* w = W + ((l * bo + r) * HK + t) * I + c * bi;
+          for (int64_t j = 0; j < ni; ++j) {
+            const long double v = (long double)w[j];
+            s1 += v;
+            s2 += v * v;
+            sa += v < 0 ? -v : v;
+          }
+        }
+      double out;
+      if (measure == BSP_IMPORTANCE_L2) {
+        out = std::sqrt((double)s2);
+      } else if (measure == BSP_IMPORTANCE_L1) {
+        out = (double)sa;
+      } else {
+        // sum (w - mu)^2 over the n stored entries, the overhang's zeros included
+        const long double mu = s1 / (long double)n;
+        long double acc = 0.0L;
+        for (int64_t r = 0; r < no; ++r)
+          for (int64_t t = 0; t < HK; ++t) {
+            const float* w = W + ((l * bo + r) * HK + t) * I + c * bi;
+            for (int64_t j = 0; j < ni; ++j) {
+              const long double d = (long double)w[j] - mu;
+              acc += d * d;
+            }
+          }
+        acc += ((long double)n - (long double)(no * HK * ni)) * mu * mu;
+        out = (double)(acc / (long double)n);
+      }
+      score[l * nbc + c] = out;
+    }
+  return BSP_OK;
+}
+
+int bsp_select_mask(const float* W, int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo,
+                    int32_t bi, int32_t measure, double density, int32_t per_row,
+                    uint8_t* gamma) {
+  if (!gamma) return BSP_ERR_NULL;
+  if (!(density >= 0.0 && density <= 1.0)) return BSP_ERR_SHAPE;
+  const int64_t nbr = cdiv(O, bo), nbc = cdiv(I, bi);
+  if (O <= 0 || I <= 0) return BSP_ERR_SHAPE;
+  std::vector<double> score((size_t)(nbr * nbc));
+  if (int rc = bsp_block_importance(W, O, H, K, I, bo, bi, measure, score.data())) return rc;
+  std::memset(gamma, 1, (size_t)(nbr * nbc));
+  if (per_row) {
+    const int64_t keep = (int64_t)std::nearbyint(density * (double)nbc);
+    for (int64_t l = 0; l < nbr; ++l)
+      zero_lowest(score.data() + l * nbc, gamma + l * nbc, nbc, nbc - keep);
+  } else {
+    const int64_t keep = (int64_t)std::nearbyint(density * (double)(nbr * nbc));
+    zero_lowest(score.data(), gamma, nbr * nbc, nbr * nbc - keep);
+  }
+  return BSP_OK;
+}
+
+int bsp_mask_step(const float* W, int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo,
+                  int32_t bi, int32_t measure, double target_density, uint8_t* gamma,
+                  int32_t* zeroed) {
+  if (!gamma || !zeroed) return BSP_ERR_NULL;
+  if (!(target_density >= 0.0 && target_density <= 1.0)) return BSP_ERR_SHAPE;
+  int64_t kept = 0;
+  if (int rc = bsp_pack_count(gamma, O, I, bo, bi, &kept)) return rc;
+  const int64_t n = cdiv(O, bo) * cdiv(I, bi);
+  std::vector<double> score((size_t)n);
+  if (int rc = bsp_block_importance(W, O, H, K, I, bo, bi, measure, score.data())) return rc;
+  const int64_t k = kept - (int64_t)std::nearbyint(target_density * (double)n);
+  *zeroed = 0;
+  if (k <= 0) return BSP_OK;
+  int64_t step = (int64_t)std::ceil(0.05 * (double)k);
+  if (step < 1) step = 1;
+  if (step > k) step = k;
+  zero_lowest(score.data(), gamma, n, step);
+  *zeroed = (int32_t)step;
+  return BSP_OK;
+}
+
+}  // extern "C"
+
+extern "C" {
 
 int bsp_quantize(const float* W, int64_t n, int32_t bits, int8_t* codes, double* delta) {
   if (!delta || (n > 0 && (!W || !codes))) return BSP_ERR_NULL;
