@@ -82,10 +82,14 @@ __device__ __forceinline__ void tile_pos(const TileCfg& t, int gt, int j, int* t
 // weight fragments in flight into spare registers.  Waves 8-11 move data: while a unit is
 // computed they have the next unit's patch in flight into their registers, after the
 // barrier they write it into LDS, and they carry finished results from the LDS staging
-// tile to global memory.  Barriers per unit, taken by all twelve waves:
-//   A  the unit's patch and weights are in LDS
-//   E  (single-slab layers only) the staging tile has been drained, results may go in
-//   B  the compute waves are done reading the patch and weights
+// tile to global memory.  Two barriers per unit, taken by all twelve waves.  Single-slab
+// layers (weights stay in LDS):
+//   E  compute is done with the patch (the movers may overwrite it) and the staging tile
+//      has been drained (results may go in)
+//   A  the next patch is in LDS and the results are staged
+// otherwise:
+//   B  compute is done with the patch and the weights; results, if any, are staged
+//   A  the next unit's patch and weights are in LDS
 template <int NT, bool NARROW>
 __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileCfg t, LdsCfg c) {
   extern __shared__ __align__(16) unsigned char lds[];
@@ -248,11 +252,13 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
       const bool more = advance(tile, sl, &ntile, &nsl);
       if (more) issue_patch(ntile, nsl);  // lands in registers during the compute phase
       flush_tile = sl == t.nslabs - 1 ? tile : -1;
-      if (!reload_w) __syncthreads();  // E
-      __syncthreads();                 // B: compute waves are done with the LDS patch
+      // E (single-slab layers): the compute waves are done with the patch and go on to stage
+      // their results, so the next patch can go in at once and B is not needed;
+      // B (otherwise): the compute waves are done with the patch and the weights
+      __syncthreads();
+      if (more) commit_patch();
+      __syncthreads();  // A: next unit is in LDS (single-slab: and the results are staged)
       if (!more) break;
-      commit_patch();
-      __syncthreads();  // A: next unit is in LDS
       tile = ntile;
       sl = nsl;
     }
@@ -351,7 +357,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
         }
       }
     }
-    if (!reload_w) __syncthreads();  // E
+    if (!reload_w) __syncthreads();  // E (the staging tile has been drained by now)
     if (sl == t.nslabs - 1 && valid) {
       // + bias, one rounding; lane holds channels 4g..4g+3 of pixel jn of every pixel tile
 #pragma unroll
@@ -363,10 +369,12 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
         *(u32x2_t*)(lds + orow + nt * 16 * kOutRow) = v;
       }
     }
-    __syncthreads();  // B
-    if (!more) break;
-    if (reload_w) commit_weights();
+    if (reload_w) {
+      __syncthreads();  // B
+      if (more) commit_weights();
+    }
     __syncthreads();  // A
+    if (!more) break;
     tile = ntile;
     sl = nsl;
   }
