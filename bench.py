@@ -218,6 +218,9 @@ def main() -> int:
     ap.add_argument("--mask", default="synthetic", choices=["synthetic", "l2", "l1", "var"],
                     help="synthetic: the config's seeded mask; l2/l1/var: keep the half of the "
                          "blocks with the largest importance (bsp_select_mask on the layer's W)")
+    ap.add_argument("--fused", action="store_true",
+                    help="time the layer with the fused residual-add + ReLU epilogue (and, for "
+                         "comparison, the plain layer followed by torch's add and relu)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--general", action="store_true", help="force the general-shape kernel")
     ap.add_argument("--no-multi-stream", dest="multi_stream", action="store_false",
@@ -263,8 +266,15 @@ def main() -> int:
           for _ in range(nsets)]
     stream = torch.cuda.current_stream(dev)
 
+    Rs = [torch.randn_like(Ys[0]) for _ in range(nsets)] if args.fused else None
+
     def step(lay, i, st=None):
-        lay.conv2d(Xs[i % nsets], c.stride, c.pad, out=Ys[i % nsets], general=args.general, stream=st)
+        if args.fused:
+            lay.conv2d(Xs[i % nsets], c.stride, c.pad, out=Ys[i % nsets], stream=st,
+                       residual=Rs[i % nsets], relu=True)
+        else:
+            lay.conv2d(Xs[i % nsets], c.stride, c.pad, out=Ys[i % nsets], general=args.general,
+                       stream=st)
 
     def timed_streams(lay, steps, nstreams):
         """Same steps, issued round-robin on several default-priority streams so that
@@ -314,6 +324,20 @@ def main() -> int:
     kd_avg, kd_med, kd_min = per_launch_us(dense, args.steps)
 
     ms_multi = timed_streams(layer, args.steps, 4) if args.multi_stream else None
+    ms_unfused = None
+    if args.fused:   # the same work as separate passes: conv, then add and relu by torch
+        def unfused(i):
+            y = Ys[i % nsets]
+            layer.conv2d(Xs[i % nsets], c.stride, c.pad, out=y)
+            y.add_(Rs[i % nsets]).relu_()
+        for i in range(args.warmup):
+            unfused(i)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(args.steps):
+            unfused(i)
+        torch.cuda.synchronize()
+        ms_unfused = (time.perf_counter() - t) * 1e3 / args.steps
 
     fl = flops_nonzero(c, layer.nnzb)
     value = fl / (ms_wall * 1e-3) / 1e12
@@ -350,6 +374,8 @@ def main() -> int:
         "mfma_frac_of_peak": round(fl / (ms_ev * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5)
         if c.dtype == "bf16" else None,
         "pack_ms": round(pack_ms, 3),
+        "fused_epilogue": bool(args.fused),
+        "unfused_ms_per_step": None if ms_unfused is None else round(ms_unfused, 6),
         "mask": args.mask, "mask_select_ms": None if select_ms is None else round(select_ms, 3),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),

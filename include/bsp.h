@@ -170,6 +170,24 @@ int bsp_conv2d(const bsp_weights* w, const void* X, const float* bias, void* Y,
                int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
                void* stream);
 
+/* The same layers with a fused epilogue (a step towards the fusion the paper's Section VI
+ * explores for its sub-graph tiling: the element-wise work after a convolution shares its
+ * pass over Y):
+ *   Y = act( round(conv + bias) + residual ), rounded again to w->dtype
+ *   residual   device, same shape and element type as Y (16-byte aligned), or null
+ *   relu       nonzero: act = max(., 0); zero: identity
+ * The sum of convolution and bias is rounded to w->dtype before the residual is added, i.e.
+ * the result equals bsp_conv2d followed by an element-wise add and activation in w->dtype's
+ * precision (fp32 arithmetic), without the extra pass over Y.  With residual null and relu 0
+ * this is bsp_conv2d.  Errors as bsp_conv2d, plus ALIGN for the residual. */
+int bsp_conv2d_fused(const bsp_weights* w, const void* X, const float* bias,
+                     const void* residual, int32_t relu, void* Y,
+                     int32_t B, int32_t L, int32_t J,
+                     int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                     void* stream);
+int bsp_fc_fused(const bsp_weights* w, const void* X, const float* bias, const void* residual,
+                 int32_t relu, void* Y, int32_t B, void* stream);
+
 /* Same layer, but always through the general-shape kernel (no shape-specialised
  * fast path).  For testing and for timing the dispatcher's choice. */
 int bsp_conv2d_general(const bsp_weights* w, const void* X, const float* bias, void* Y,

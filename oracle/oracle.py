@@ -131,6 +131,23 @@ def conv2d(X: np.ndarray, W: np.ndarray, bias: Optional[np.ndarray],
     return (Y, used) if return_threads else Y
 
 
+def conv2d_fused(X, W, bias, gamma, bo, bi, stride=(1, 1), pad=(0, 0), residual=None,
+                 relu: bool = False, dtype: str = "bf16") -> np.ndarray:
+    """The layer followed by an element-wise residual add and activation in the storage
+    type: act(round(conv + bias) + residual) in fp64, the caller's comparison supplying the
+    last rounding.  (Paper Section VI fuses a layer with what follows it; the arithmetic is
+    that of the separate operations: the convolution's result is first stored in `dtype`.)"""
+    y = conv2d(X, W, bias, gamma, bo, bi, stride, pad)
+    if residual is None and not relu:
+        return y
+    y = round_to_storage(y, dtype).astype(np.float64)
+    if residual is not None:
+        y = y + np.asarray(residual, dtype=np.float64)
+    if relu:
+        y = np.maximum(y, 0.0)
+    return y
+
+
 def conv2d_at(X, W, bias, gamma, bo, bi, positions: np.ndarray,
               stride=(1, 1), pad=(0, 0)) -> np.ndarray:
     """The outputs Y[n,m,q,o] at the listed (n,m,q,o) rows only (fp64)."""

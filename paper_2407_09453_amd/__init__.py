@@ -14,9 +14,11 @@ from .binding import (  # noqa: F401
     BspLayerI8,
     bsp_block_importance,
     bsp_conv2d,
+    bsp_conv2d_fused,
     bsp_conv2d_general,
     bsp_conv2d_i8,
     bsp_fc,
+    bsp_fc_fused,
     bsp_fc_i8,
     bsp_mask_step,
     bsp_pack,

@@ -25,7 +25,8 @@ _lib = None
 EXPORTS = ("bsp_strerror", "bsp_version", "bsp_pack_count", "bsp_pack", "bsp_unpack",
            "bsp_validate", "bsp_plan_size", "bsp_plan_build", "bsp_fc", "bsp_conv2d",
            "bsp_conv2d_general", "bsp_quantize", "bsp_conv2d_i8", "bsp_fc_i8",
-           "bsp_block_importance", "bsp_select_mask", "bsp_mask_step")
+           "bsp_block_importance", "bsp_select_mask", "bsp_mask_step", "bsp_conv2d_fused",
+           "bsp_fc_fused")
 
 
 class BspError(RuntimeError):
@@ -92,6 +93,10 @@ def load_library():
         fn.restype = ctypes.c_int
         fn.argtypes = [wp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]
     f64 = ctypes.c_double
+    lib.bsp_conv2d_fused.restype = ctypes.c_int
+    lib.bsp_conv2d_fused.argtypes = [wp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, i32, vp]
+    lib.bsp_fc_fused.restype = ctypes.c_int
+    lib.bsp_fc_fused.argtypes = [wp, vp, vp, vp, i32, vp, i32, vp]
     lib.bsp_block_importance.restype = ctypes.c_int
     lib.bsp_block_importance.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp]
     lib.bsp_select_mask.restype = ctypes.c_int
@@ -271,6 +276,20 @@ def bsp_conv2d(w: bsp_weights, X: int, bias: Optional[int], Y: int, B: int, L: i
                                      pad[0], pad[1], stream), "bsp_conv2d")
 
 
+def bsp_conv2d_fused(w: bsp_weights, X: int, bias: Optional[int], residual: Optional[int],
+                     relu: bool, Y: int, B: int, L: int, J: int, stride=(1, 1), pad=(0, 0),
+                     stream: int = 0) -> None:
+    _check(load_library().bsp_conv2d_fused(ctypes.byref(w), X, bias, residual, int(relu), Y, B, L,
+                                           J, stride[0], stride[1], pad[0], pad[1], stream),
+           "bsp_conv2d_fused")
+
+
+def bsp_fc_fused(w: bsp_weights, X: int, bias: Optional[int], residual: Optional[int],
+                 relu: bool, Y: int, B: int, stream: int = 0) -> None:
+    _check(load_library().bsp_fc_fused(ctypes.byref(w), X, bias, residual, int(relu), Y, B,
+                                       stream), "bsp_fc_fused")
+
+
 def bsp_conv2d_general(w: bsp_weights, X: int, bias: Optional[int], Y: int, B: int, L: int,
                        J: int, stride=(1, 1), pad=(0, 0), stream: int = 0) -> None:
     _check(load_library().bsp_conv2d_general(ctypes.byref(w), X, bias, Y, B, L, J, stride[0],
@@ -336,8 +355,10 @@ class BspLayer:
         N = (J + 2 * pad[1] - self.K) // stride[1] + 1
         return (B, M, N, self.O)
 
-    def conv2d(self, X, stride=(1, 1), pad=(0, 0), out=None, general=False, stream=None):
-        """X: torch tensor [B][L][J][I] on the layer's device, contiguous."""
+    def conv2d(self, X, stride=(1, 1), pad=(0, 0), out=None, general=False, stream=None,
+               residual=None, relu=False):
+        """X: torch tensor [B][L][J][I] on the layer's device, contiguous.  ``residual`` (a
+        tensor shaped like the output) and ``relu`` select the fused epilogue."""
         import torch
         assert X.is_contiguous() and X.dtype == self.torch_dtype and X.shape[-1] == self.I
         B, L, J, _ = X.shape
@@ -345,12 +366,21 @@ class BspLayer:
             out = torch.empty(self.out_shape(B, L, J, stride, pad), dtype=self.torch_dtype,
                               device=X.device)
         st = torch.cuda.current_stream(X.device).cuda_stream if stream is None else stream
+        bias = None if self.d_bias is None else self.d_bias.data_ptr()
+        if residual is not None or relu:
+            assert not general
+            if residual is not None:
+                assert residual.is_contiguous() and residual.dtype == self.torch_dtype \
+                    and residual.shape == out.shape
+            bsp_conv2d_fused(self.struct, X.data_ptr(), bias,
+                             None if residual is None else residual.data_ptr(), relu,
+                             out.data_ptr(), B, L, J, stride, pad, st)
+            return out
         fn = bsp_conv2d_general if general else bsp_conv2d
-        fn(self.struct, X.data_ptr(), None if self.d_bias is None else self.d_bias.data_ptr(),
-           out.data_ptr(), B, L, J, stride, pad, st)
+        fn(self.struct, X.data_ptr(), bias, out.data_ptr(), B, L, J, stride, pad, st)
         return out
 
-    def fc(self, X, out=None, stream=None):
+    def fc(self, X, out=None, stream=None, residual=None, relu=False):
         """X: torch tensor [B][I]."""
         import torch
         assert X.is_contiguous() and X.dtype == self.torch_dtype and X.shape[-1] == self.I
@@ -358,8 +388,13 @@ class BspLayer:
         if out is None:
             out = torch.empty((B, self.O), dtype=self.torch_dtype, device=X.device)
         st = torch.cuda.current_stream(X.device).cuda_stream if stream is None else stream
-        bsp_fc(self.struct, X.data_ptr(),
-               None if self.d_bias is None else self.d_bias.data_ptr(), out.data_ptr(), B, st)
+        bias = None if self.d_bias is None else self.d_bias.data_ptr()
+        if residual is not None or relu:
+            bsp_fc_fused(self.struct, X.data_ptr(), bias,
+                         None if residual is None else residual.data_ptr(), relu, out.data_ptr(),
+                         B, st)
+        else:
+            bsp_fc(self.struct, X.data_ptr(), bias, out.data_ptr(), B, st)
         return out
 
 

@@ -66,8 +66,30 @@ int prepare(const bsp_weights* w, const void* X, const float* bias, void* Y, int
   p.ph = ph;
   p.pw = pw;
   p.P = (int32_t)((int64_t)B * M * N);
+  p.residual = nullptr;
+  p.relu = 0;
   *out = p;
   return BSP_OK;
+}
+
+}  // namespace
+
+namespace {
+
+int dispatch(const bsp_weights* w, const ConvParams& p, void* stream) {
+  if (p.P == 0) return BSP_OK;
+  if (w->dtype == BSP_BF16 && kernel_limit() >= 1) {
+    // each launcher declines (UNSUPPORTED, nothing launched) what lies outside its limits
+    const bool chunked = bsp_tile_supported(p, w->dtype);  // whole 8-channel chunks
+    int rc = BSP_ERR_UNSUPPORTED;
+    if (chunked) rc = bsp_launch_fc_stream(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
+    if (rc != BSP_ERR_UNSUPPORTED) return rc;
+    if (kernel_limit() >= 2) rc = bsp_launch_lds(p, w->dtype, w->plan_host, (hipStream_t)stream);
+    if (rc != BSP_ERR_UNSUPPORTED) return rc;
+    if (chunked) rc = bsp_launch_tile(p, w->dtype, (hipStream_t)stream);
+    if (rc != BSP_ERR_UNSUPPORTED) return rc;
+  }
+  return bsp_launch_general(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
 }
 
 }  // namespace
@@ -86,21 +108,27 @@ int bsp_conv2d_general(const bsp_weights* w, const void* X, const float* bias, v
 int bsp_conv2d(const bsp_weights* w, const void* X, const float* bias, void* Y, int32_t B,
                int32_t L, int32_t J, int32_t stride_h, int32_t stride_w, int32_t pad_h,
                int32_t pad_w, void* stream) {
+  return bsp_conv2d_fused(w, X, bias, nullptr, 0, Y, B, L, J, stride_h, stride_w, pad_h, pad_w,
+                          stream);
+}
+
+int bsp_conv2d_fused(const bsp_weights* w, const void* X, const float* bias,
+                     const void* residual, int32_t relu, void* Y, int32_t B, int32_t L,
+                     int32_t J, int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                     void* stream) {
   ConvParams p;
   if (int rc = prepare(w, X, bias, Y, B, L, J, stride_h, stride_w, pad_h, pad_w, &p)) return rc;
-  if (p.P == 0) return BSP_OK;
-  if (w->dtype == BSP_BF16 && kernel_limit() >= 1) {
-    // each launcher declines (UNSUPPORTED, nothing launched) what lies outside its limits
-    const bool chunked = bsp_tile_supported(p, w->dtype);  // whole 8-channel chunks
-    int rc = BSP_ERR_UNSUPPORTED;
-    if (chunked) rc = bsp_launch_fc_stream(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
-    if (rc != BSP_ERR_UNSUPPORTED) return rc;
-    if (kernel_limit() >= 2) rc = bsp_launch_lds(p, w->dtype, w->plan_host, (hipStream_t)stream);
-    if (rc != BSP_ERR_UNSUPPORTED) return rc;
-    if (chunked) rc = bsp_launch_tile(p, w->dtype, (hipStream_t)stream);
-    if (rc != BSP_ERR_UNSUPPORTED) return rc;
-  }
-  return bsp_launch_general(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
+  if (residual && !aligned16(residual)) return BSP_ERR_ALIGN;
+  p.residual = residual;
+  p.relu = relu != 0;
+  return dispatch(w, p, stream);
+}
+
+int bsp_fc_fused(const bsp_weights* w, const void* X, const float* bias, const void* residual,
+                 int32_t relu, void* Y, int32_t B, void* stream) {
+  if (!w || (B != 0 && (!X || !Y))) return BSP_ERR_NULL;
+  if (w->H != 1 || w->K != 1) return BSP_ERR_SHAPE;
+  return bsp_conv2d_fused(w, X, bias, residual, relu, Y, B, 1, 1, 1, 1, 0, 0, stream);
 }
 
 int bsp_fc(const bsp_weights* w, const void* X, const float* bias, void* Y, int32_t B,

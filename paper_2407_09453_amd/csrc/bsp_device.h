@@ -26,6 +26,9 @@ struct ConvParams {
   int32_t B, L, J, I, O, H, K, M, N;
   int32_t sh, sw, ph, pw;
   int32_t P;  // B*M*N output pixels
+  // fused epilogue: Y = act(round(conv + bias) + residual), then rounded to the element type
+  const void* residual;  // same shape and element type as Y, or null
+  int32_t relu;          // act = max(., 0) when nonzero, identity otherwise
 };
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
@@ -61,6 +64,36 @@ __device__ __forceinline__ PlanView plan_view(const int32_t* plan) {
   v.chunk_xc = plan + plan[BSP_PLAN_OFF_XC_W];
   v.chunk_src = plan + plan[BSP_PLAN_OFF_SRC_W];
   return v;
+}
+
+// Fused epilogue on four bf16 results packed in v (channels c..c+3 of one pixel): adds the
+// residual's channels (r4 points at channel c; `n` of the four exist), applies the
+// activation, rounds again.  Without a residual the second rounding changes nothing.
+__device__ __forceinline__ u32x2_t post_bf16x4(u32x2_t v, const uint16_t* r4, int n, bool vec,
+                                               int relu) {
+  float f[4] = {bf16_bits_to_f32((uint16_t)(v.x & 0xFFFF)), bf16_bits_to_f32((uint16_t)(v.x >> 16)),
+                bf16_bits_to_f32((uint16_t)(v.y & 0xFFFF)), bf16_bits_to_f32((uint16_t)(v.y >> 16))};
+  if (r4) {
+    if (vec) {
+      const u32x2_t r = *(const u32x2_t*)r4;
+      f[0] += bf16_bits_to_f32((uint16_t)(r.x & 0xFFFF));
+      f[1] += bf16_bits_to_f32((uint16_t)(r.x >> 16));
+      f[2] += bf16_bits_to_f32((uint16_t)(r.y & 0xFFFF));
+      f[3] += bf16_bits_to_f32((uint16_t)(r.y >> 16));
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (k < n) f[k] += bf16_bits_to_f32(r4[k]);
+    }
+  }
+  if (relu) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) f[k] = fmaxf(f[k], 0.f);
+  }
+  u32x2_t o;
+  o.x = (uint32_t)f32_to_bf16_rne(f[0]) | ((uint32_t)f32_to_bf16_rne(f[1]) << 16);
+  o.y = (uint32_t)f32_to_bf16_rne(f[2]) | ((uint32_t)f32_to_bf16_rne(f[3]) << 16);
+  return o;
 }
 
 #endif

@@ -139,6 +139,9 @@ __global__ __launch_bounds__(kFcWaves * 64) void fc_stream_bf16(ConvParams p) {
     o.x = pack_bf16x2(v[0] + bv[0], v[1] + bv[1]);
     o.y = pack_bf16x2(v[2] + bv[2], v[3] + bv[3]);
     uint16_t* yp = Y + (int64_t)pix * p.O + ch;
+    if (p.residual || p.relu)
+      o = post_bf16x4(o, p.residual ? (const uint16_t*)p.residual + (int64_t)pix * p.O + ch : nullptr,
+                      p.O - ch, (p.O % 4) == 0 && ch + 3 < p.O, p.relu);
     if ((p.O % 4) == 0 && ch + 3 < p.O) {
       *(u32x2_t*)yp = o;
     } else {

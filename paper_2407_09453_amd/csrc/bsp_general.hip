@@ -130,7 +130,19 @@ __global__ __launch_bounds__(256) void conv_general_bf16(ConvParams p) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) h[r] = f32_to_bf16_rne(acc[mt][r] + bv[r]);
     uint16_t* yp = Y + (int64_t)pid * p.O + ch;
-    if ((p.O % 4) == 0 && ch + 3 < p.O) {
+    const bool vec = (p.O % 4) == 0 && ch + 3 < p.O;
+    if (p.residual || p.relu) {
+      u32x2_t v;
+      v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+      v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+      const uint16_t* rp = p.residual ? (const uint16_t*)p.residual + (int64_t)pid * p.O + ch : nullptr;
+      v = post_bf16x4(v, rp, p.O - ch, vec, p.relu);
+      h[0] = (uint16_t)(v.x & 0xFFFF);
+      h[1] = (uint16_t)(v.x >> 16);
+      h[2] = (uint16_t)(v.y & 0xFFFF);
+      h[3] = (uint16_t)(v.y >> 16);
+    }
+    if (vec) {
       u32x2_t v;
       v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
       v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
@@ -231,13 +243,19 @@ __global__ __launch_bounds__(256) void conv_general_f32(ConvParams p) {
     const int pid = pix_base + mt * 16 + jn;
     if (!vp[mt]) continue;
     float* yp = Y + (int64_t)pid * p.O + ch;
+    float y[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      y[r] = acc[mt][r] + bv[r];
+      if (p.residual && ch + r < p.O) y[r] += ((const float*)p.residual)[(int64_t)pid * p.O + ch + r];
+      if (p.relu) y[r] = fmaxf(y[r], 0.f);
+    }
     if ((p.O % 4) == 0 && ch + 3 < p.O) {
-      *(float4*)yp = make_float4(acc[mt][0] + bv[0], acc[mt][1] + bv[1], acc[mt][2] + bv[2],
-                                 acc[mt][3] + bv[3]);
+      *(float4*)yp = make_float4(y[0], y[1], y[2], y[3]);
     } else {
 #pragma unroll
       for (int r = 0; r < 4; ++r)
-        if (ch + r < p.O) yp[r] = acc[mt][r] + bv[r];
+        if (ch + r < p.O) yp[r] = y[r];
     }
   }
 }

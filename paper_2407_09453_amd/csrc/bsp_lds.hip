@@ -21,6 +21,7 @@
 #include "bsp_tile.h"
 
 #include <array>
+#include <type_traits>
 #include <map>
 #include <mutex>
 
@@ -214,23 +215,62 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
       const int tyi = (int)fdiv((uint32_t)trem, t.d_tiles_x);
       const int oy0 = tyi * t.TH, ox0 = (trem - tyi * t.tiles_x) * t.TW;
       uint16_t* yorg = Y + (((int64_t)n * p.M + oy0) * p.N + ox0) * p.O + sg * 64;
+      const uint16_t* rorg = (const uint16_t*)p.residual + (yorg - Y);
       const int my = p.M - oy0, mx = p.N - ox0;  // rows / columns of the tile inside the image
-      // four pieces at a time: reads first, then the stores, so that neither waits on the other
+      // a few pieces at a time: all reads first, then the stores, so that neither waits on
+      // the other.  Plain: four staged pieces.  Fused: two staged pieces and their two
+      // residual pieces (the same registers in all).
+      auto batch = [&](auto bs_tag, auto fused_tag) {
+        constexpr int BS = decltype(bs_tag)::value;
+        constexpr bool FUSED = decltype(fused_tag)::value;
 #pragma unroll
-      for (int k0 = 0; k0 < NT; k0 += 4) {
-        u32x4_t ov[4];
+        for (int k0 = 0; k0 < NT; k0 += BS) {
+          u32x4_t ov[BS], rv[FUSED ? BS : 1];
+          bool ok[BS];
 #pragma unroll
-        for (int k = k0; k < k0 + 4 && k < NT; ++k)
-          ov[k - k0] = *(const u32x4_t*)(lds + c.obuf_off + ((ltid >> 3) + 32 * k) * kOutRow + (ltid & 7) * 16);
+          for (int k = k0; k < k0 + BS && k < NT; ++k) {
+            const int f = fpos[k];
+            ok[k - k0] = f >= 0 && (f >> 16) < my && (f & 0xFFFF) < mx;
+            if constexpr (FUSED) {
+              rv[k - k0] = u32x4_t{0u, 0u, 0u, 0u};
+              if (p.residual && ok[k - k0]) rv[k - k0] = *(const u32x4_t*)(rorg + foff[k]);
+            }
+          }
 #pragma unroll
-        for (int k = k0; k < k0 + 4 && k < NT; ++k) {
-          const int f = fpos[k];
-          // streaming store: results are not read again here, and lines left dirty in L2
-          // would all be written back in one burst when the kernel ends
-          if (f >= 0 && (f >> 16) < my && (f & 0xFFFF) < mx)
-            __builtin_nontemporal_store(ov[k - k0], (u32x4_t*)(yorg + foff[k]));
+          for (int k = k0; k < k0 + BS && k < NT; ++k)
+            ov[k - k0] = *(const u32x4_t*)(lds + c.obuf_off + ((ltid >> 3) + 32 * k) * kOutRow + (ltid & 7) * 16);
+#pragma unroll
+          for (int k = k0; k < k0 + BS && k < NT; ++k) {
+            if (!ok[k - k0]) continue;
+            u32x4_t o = ov[k - k0];
+            if constexpr (FUSED) {  // eight channels: + residual, activation, second rounding
+              const u32x4_t r = rv[k - k0];
+              const uint32_t in[4] = {o.x, o.y, o.z, o.w}, rr[4] = {r.x, r.y, r.z, r.w};
+              uint32_t out[4];
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                float lo = bf16_bits_to_f32((uint16_t)(in[q] & 0xFFFF)) +
+                           bf16_bits_to_f32((uint16_t)(rr[q] & 0xFFFF));
+                float hi = bf16_bits_to_f32((uint16_t)(in[q] >> 16)) +
+                           bf16_bits_to_f32((uint16_t)(rr[q] >> 16));
+                if (p.relu) {
+                  lo = fmaxf(lo, 0.f);
+                  hi = fmaxf(hi, 0.f);
+                }
+                out[q] = pack_bf16x2(lo, hi);
+              }
+              o = u32x4_t{out[0], out[1], out[2], out[3]};
+            }
+            // streaming store: results are not read again here, and lines left dirty in L2
+            // would all be written back in one burst when the kernel ends
+            __builtin_nontemporal_store(o, (u32x4_t*)(yorg + foff[k]));
+          }
         }
-      }
+      };
+      if (p.residual || p.relu)
+        batch(std::integral_constant<int, 2>{}, std::true_type{});
+      else
+        batch(std::integral_constant<int, 4>{}, std::false_type{});
     };
 
     int sl = 0;

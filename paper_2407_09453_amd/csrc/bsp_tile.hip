@@ -218,6 +218,9 @@ __global__ __launch_bounds__(256, BSP_TILE_OCC) void conv_tile_bf16(ConvParams p
         if (pyx[nt] < 0 || oy >= p.M || ox >= p.N) continue;
         const int64_t pid = ((int64_t)n * p.M + oy) * p.N + ox;
         uint16_t* yp = Y + pid * p.O + ch;
+        if (p.residual || p.relu)
+          v = post_bf16x4(v, p.residual ? (const uint16_t*)p.residual + pid * p.O + ch : nullptr,
+                          p.O - ch, (p.O % 4) == 0 && ch + 3 < p.O, p.relu);
         if ((p.O % 4) == 0 && ch + 3 < p.O) {
           *(u32x2_t*)yp = v;
         } else {

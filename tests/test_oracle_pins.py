@@ -358,3 +358,29 @@ def test_bf16_rounding_matches_library():
     x = (rng.standard_normal(200000) * np.exp(rng.uniform(-20, 20, 200000))).astype(np.float32)
     lib = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert (oracle.bf16_bits_rne(x) == lib).all()
+
+
+def test_fused_epilogue_against_library_ops():
+    """conv -> store in bf16 -> + residual -> relu, each step by torch (fp64 conv, bf16 cast)."""
+    import torch
+    rng = np.random.default_rng(21)
+    B, L, J, I, O = 2, 6, 7, 16, 24
+    X = oracle.round_to_storage(rng.standard_normal((B, L, J, I)), "bf16")
+    W = oracle.round_to_storage(rng.standard_normal((O, 3, 3, I)) * 0.1, "bf16")
+    bias = rng.standard_normal(O).astype(np.float32)
+    gamma = (rng.random((O // 8, I // 8)) < 0.6).astype(np.uint8)
+    R = oracle.round_to_storage(rng.standard_normal((B, L, J, O)), "bf16")
+    Wm = oracle.apply_mask(W, gamma, 8, 8)
+    y = torch.nn.functional.conv2d(torch.from_numpy(X.astype(np.float64)).permute(0, 3, 1, 2),
+                                   torch.from_numpy(Wm.astype(np.float64)).permute(0, 3, 1, 2),
+                                   torch.from_numpy(bias.astype(np.float64)), padding=1)
+    y = y.permute(0, 2, 3, 1).to(torch.float32).to(torch.bfloat16).to(torch.float64)
+    want = torch.relu(y + torch.from_numpy(R.astype(np.float64))).numpy()
+    got = oracle.conv2d_fused(X, W, bias, gamma, 8, 8, (1, 1), (1, 1), residual=R, relu=True)
+    # the fp32 hop of the torch cast can move a value sitting on a bf16 tie: allow one bf16 ulp there
+    assert np.abs(got - want).max() <= 2.0 ** -7 * np.abs(want).max()
+    assert (np.abs(got - want) > 0).mean() < 0.01
+    plain = oracle.conv2d_fused(X, W, bias, gamma, 8, 8, (1, 1), (1, 1))
+    assert (plain == oracle.conv2d(X, W, bias, gamma, 8, 8, (1, 1), (1, 1))).all()
+    only_relu = oracle.conv2d_fused(X, W, bias, gamma, 8, 8, (1, 1), (1, 1), relu=True)
+    assert (only_relu >= 0).all() and (only_relu[plain > 0.01] > 0).all()
