@@ -358,14 +358,18 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, const void*
   const int32_t nstrips = (int32_t)cdiv(O, BSP_STRIP);
   const int32_t nxc = (int32_t)cdiv(I, BSP_CHUNK);
   const int32_t rows_per_strip = BSP_STRIP / bo;  // 2, 4 or 1
-  const bool steps_wanted = dtype == BSP_BF16;
-  const int32_t slab = bsp_slab_channels(I, H, K);
-  const int32_t slab_chunks = slab / BSP_CHUNK;
-  const int32_t nslabs = (int32_t)cdiv(nxc, slab_chunks);
+  const bool steps_wanted = dtype == BSP_BF16 || dtype == BSP_I8;
+  // the step section's chunks are 16 bytes of input channels per pixel: 8 bf16 or 16 int8
+  const int32_t scw = dtype == BSP_I8 ? 2 : 1;  // 8-channel chunks per step-section chunk
+  const int32_t nsc = (int32_t)cdiv(nxc, scw);
+  const int32_t slab_chunks = bsp_slab_channels(nsc * BSP_CHUNK, H, K) / BSP_CHUNK;
+  const int32_t slab = slab_chunks * BSP_CHUNK * scw;  // channels
+  const int32_t nslabs = (int32_t)cdiv(nsc, slab_chunks);
 
   std::vector<int32_t> src((size_t)nxc * BSP_MAXSUB);
   std::vector<int32_t> strip_ptr((size_t)nstrips + 1, 0);
   std::vector<int32_t> xc_list, src_list;
+  std::vector<int32_t> sc_list, sc_ptr((size_t)nstrips + 1, 0);  // step-section chunks per strip
   std::vector<int32_t> slab_ptr;  // [nstrips][nslabs+1]
   int32_t max_chunks = 0, max_steps = 0, max_slab_steps = 0;
   int64_t nsteps = 0;
@@ -403,16 +407,23 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, const void*
         ++next_slab;
       }
     };
+    int32_t last_sc = -1;
     for (int32_t xc = 0; xc < nxc; ++xc) {
       const int32_t* e = &src[(size_t)xc * BSP_MAXSUB];
       if (e[0] < 0 && e[1] < 0 && e[2] < 0 && e[3] < 0) continue;
-      close_slabs_upto(xc / slab_chunks);
       xc_list.push_back(xc);
       src_list.insert(src_list.end(), e, e + BSP_MAXSUB);
       ++count;
-      ++in_slab;
+      const int32_t sc = xc / scw;
+      if (sc != last_sc) {
+        close_slabs_upto(sc / slab_chunks);
+        sc_list.push_back(sc);
+        ++in_slab;
+        last_sc = sc;
+      }
     }
     close_slabs_upto(nslabs);
+    sc_ptr[(size_t)t + 1] = (int32_t)sc_list.size();
     strip_ptr[(size_t)t + 1] = strip_ptr[t] + count;
     if (count > max_chunks) max_chunks = count;
     if (nsteps - strip_first_step > max_steps) max_steps = (int32_t)(nsteps - strip_first_step);
@@ -426,7 +437,7 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, const void*
   const int64_t off_slab = off_src + nchunks * BSP_MAXSUB;
   const int64_t off_xdesc = off_slab + (steps_wanted ? pad4((int64_t)nstrips * (nslabs + 1)) : 0);
   const int64_t off_wfrag = off_xdesc + nsteps * 4;
-  const int64_t total = off_wfrag + nsteps * 64 * 8 / 2;  // bf16: two elements per word
+  const int64_t total = off_wfrag + nsteps * 64 * 4;  // 16 bytes (four words) per lane and step
   if (total > std::numeric_limits<int32_t>::max()) return BSP_ERR_SHAPE;
   if (words_needed) *words_needed = total;
   if (!out) return BSP_OK;
@@ -464,8 +475,47 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, const void*
   }
   if (!steps_wanted) return BSP_OK;
 
-  // Step section: re-order the kept bf16 weights into MFMA operand order.
+  // Step section: re-order the kept weights into MFMA operand order.
   std::memcpy(out + off_slab, slab_ptr.data(), sizeof(int32_t) * slab_ptr.size());
+  if (dtype == BSP_I8) {
+    // int8 codes, 16-channel chunks: lane 16g + j of a step holds the sixteen codes
+    // W[16*strip + j][tap][16*chunk .. 16*chunk + 15] of the step's pair g (or zeros).
+    const int8_t* pl8 = (const int8_t*)payload;
+    int32_t* xdesc = out + off_xdesc;
+    int8_t* wfrag = (int8_t*)(out + off_wfrag);
+    const int64_t Ipad = (int64_t)nsc * 16;
+    std::vector<int8_t> dense((size_t)(BSP_STRIP * HK * Ipad));  // the strip's masked rows
+    for (int32_t t = 0; t < nstrips; ++t) {
+      std::fill(dense.begin(), dense.end(), (int8_t)0);
+      for (int32_t s = 0; s < rows_per_strip; ++s) {
+        const int64_t l = (int64_t)t * rows_per_strip + s;
+        if (l >= nbr) break;
+        for (int64_t n = row_ptr[l]; n < row_ptr[l + 1]; ++n)
+          for (int64_t r = 0; r < bo; ++r)
+            for (int64_t tp = 0; tp < HK; ++tp)
+              std::memcpy(&dense[(size_t)(((s * bo + r) * HK + tp) * Ipad + (int64_t)col_idx[n] * bi)],
+                          pl8 + n * blk_elems + (r * HK + tp) * bi, (size_t)bi);
+      }
+      int32_t e = sc_ptr[t];
+      for (int32_t sl = 0; sl < nslabs; ++sl) {
+        const int32_t e0 = e;
+        while (e < sc_ptr[(size_t)t + 1] && sc_list[e] / slab_chunks == sl) ++e;
+        const int64_t pairs = (int64_t)(e - e0) * HK;
+        const int64_t s0 = slab_ptr[(size_t)t * (nslabs + 1) + sl];
+        for (int64_t q = 0; q < pairs; ++q) {
+          const int64_t step = s0 + q / 4;
+          const int32_t g = (int32_t)(q % 4);
+          const int32_t sc = sc_list[e0 + (int32_t)(q / HK)];
+          const int32_t tap = (int32_t)(q % HK);
+          xdesc[step * 4 + g] = (sc - sl * slab_chunks) | ((tap / K) << 16) | ((tap % K) << 24);
+          for (int32_t j = 0; j < BSP_STRIP; ++j)
+            std::memcpy(wfrag + ((step * 64) + g * 16 + j) * 16,
+                        &dense[(size_t)((j * HK + tap) * Ipad + (int64_t)sc * 16)], 16);
+        }
+      }
+    }
+    return BSP_OK;
+  }
   const uint16_t* pl = (const uint16_t*)payload;
   int32_t* xdesc = out + off_xdesc;
   uint16_t* wfrag = (uint16_t*)(out + off_wfrag);

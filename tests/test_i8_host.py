@@ -46,7 +46,39 @@ def test_pack_int8_codes_bit_exact_and_roundtrip(bo, bi, O, I, H, K):
     keep = oracle.expand_mask(gamma, O, I, bo, bi)[:, None, None, :]
     assert back.dtype == np.int8 and (back == np.where(keep, Wq, 0)).all()
     plan = bsp.bsp_plan_build(rp, ci, pl, O, H, K, I, bo, bi)
-    assert plan[15] == bsp.BSP_I8 and plan[18] == 0          # no bf16 step section
+    assert plan[15] == bsp.BSP_I8
+    _check_i8_steps(plan, np.where(keep, Wq, 0), O, H, K, I)
+
+
+def _check_i8_steps(plan, Wm, O, H, K, I):
+    """Decode the int8 step section (16-channel chunks, four (chunk, tap) pairs a step, sixteen
+    codes per lane) and rebuild the masked weights from it: every nonzero code must appear
+    exactly where the descriptors say, and nothing else."""
+    nstrips, slab, nslabs, nsteps = plan[8], plan[16], plan[17], plan[18]
+    off_slab, off_xdesc, off_wfrag = plan[19], plan[20], plan[21]
+    slab_chunks = slab // 16
+    assert nslabs == -(-(-(-I // 16)) // slab_chunks) and (nsteps > 0 or not Wm.any())
+    sp = plan[off_slab:off_slab + nstrips * (nslabs + 1)].reshape(nstrips, nslabs + 1)
+    xd = plan[off_xdesc:off_xdesc + nsteps * 4].reshape(nsteps, 4)
+    wf = plan[off_wfrag:off_wfrag + nsteps * 64 * 4].view(np.int8).reshape(nsteps, 4, 16, 16)
+    Ip = -(-I // 16) * 16
+    got = np.zeros((nstrips * 16, H, K, Ip), dtype=np.int64)
+    seen = np.zeros((nstrips * 16, H, K, Ip), dtype=np.int64)
+    for t in range(nstrips):
+        for sl in range(nslabs):
+            for st in range(sp[t, sl], sp[t, sl + 1]):
+                for g in range(4):
+                    d = int(xd[st, g])
+                    c, r, k = (d & 0xFFFF) + sl * slab_chunks, (d >> 16) & 0xFF, (d >> 24) & 0xFF
+                    frag = wf[st, g].astype(np.int64)               # [row j][16 codes]
+                    if not frag.any():
+                        continue                                     # padding pair or all-zero
+                    got[t * 16:(t + 1) * 16, r, k, c * 16:(c + 1) * 16] += frag
+                    seen[t * 16:(t + 1) * 16, r, k, c * 16:(c + 1) * 16] += 1
+    assert seen.max() <= 1                                           # no pair listed twice
+    want = np.zeros_like(got)
+    want[:O, :, :, :I] = Wm
+    assert (got == want).all()
 
 
 def test_mixed_int8_and_float_types_are_refused():
