@@ -110,7 +110,7 @@ def bench_i8(args) -> int:
         "config": {"workload": "config1's shape as an int8 layer: conv3x3 s1 p1, X 32x56x56x64 "
                                "int8, W 64x3x3x64 int8 codes (Eq. 8), int32 bias, int8 out >> 9",
                    "block": "8x8", "nnzb": layer.nnzb, "buffer_sets": nsets,
-                   "kernel": "general int8", "delta": delta},
+                   "kernel": "dispatch", "delta": delta},
         "speedup_vs_dense_mask": round(ms_wall_d / ms_wall, 4),
         "dense_mask_ms_per_step": round(ms_wall_d, 6),
         "event_ms_per_step": round(ms_ev, 6),

@@ -149,6 +149,10 @@ int bsp_conv2d_i8(const bsp_weights* w, const int8_t* X, const int32_t* bias, vo
   if (y_dtype != BSP_I8 && y_dtype != BSP_I32) return BSP_ERR_DTYPE;
   if (y_dtype == BSP_I8 && (shift < 0 || shift > 31)) return BSP_ERR_SHAPE;
   if (p.P == 0) return BSP_OK;
+  if (y_dtype == BSP_I8 && kernel_limit() >= 2 && aligned16(X)) {
+    const int rc = bsp_launch_lds_i8(p, w->plan_host, shift, (hipStream_t)stream);
+    if (rc != BSP_ERR_UNSUPPORTED) return rc;
+  }
   return bsp_launch_i8(p, y_dtype == BSP_I8, y_dtype == BSP_I8 ? shift : 0, w->bo, w->bi,
                        (hipStream_t)stream);
 }

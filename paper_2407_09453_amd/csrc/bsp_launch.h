@@ -20,6 +20,8 @@ int bsp_launch_fc_stream(const ConvParams& p, int dtype, int bo, int bi, hipStre
 // LDS-resident kernel (weights and activations of a slab both in LDS); needs the host copy
 // of the plan to size LDS.  BSP_ERR_UNSUPPORTED = not applicable, nothing launched.
 int bsp_launch_lds(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);
+// the same for int8 codes with int8 results (sum + bias, rounding right shift, saturation)
+int bsp_launch_lds_i8(const ConvParams& p, const void* plan_host, int shift, hipStream_t st);
 
 // 8-bit integer layers: X and payload int8, bias int32 (passed through ConvParams::bias),
 // Y int8 after a rounding right shift (y_i8 = 1) or the int32 sums.

@@ -27,6 +27,8 @@
 
 namespace {
 
+typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+
 constexpr int kPH = 2;              // compute waves per strip, each taking a share of the pixel tiles
 constexpr int kComputeThreads = 256 * kPH;
 constexpr int kLoaderWaves = 4;     // one per strip of the group
@@ -36,6 +38,7 @@ constexpr int kXBatch = 11;         // 16-byte patch pieces a loader thread keep
 constexpr int kWHalf = 10;         // weight fragments a loader lane keeps in flight (one slab of a strip)
 constexpr int kMaxSlabs = 32;
 constexpr int kOutRow = 4 * BSP_STRIP * 2 + 16;  // bytes per pixel in the results staging tile
+constexpr int kOutRowI8 = 4 * BSP_STRIP + 16;     // the same for int8 results
 
 struct LdsCfg {
   int32_t wbuf_off;       // LDS offset of the weight regions (after the patch)
@@ -44,6 +47,7 @@ struct LdsCfg {
   int32_t maxsteps;       // most steps any (strip, slab) has
   int32_t nsteps;         // steps in the whole plan
   int32_t mover_first;    // raise the data movers' wave priority
+  int32_t shift;          // int8 results: rounding right shift of the 32-bit sums
   int32_t groups;         // strip groups (of four)
   int32_t wg_per_group;   // workgroups sharing one strip group
   int32_t off_slab, off_xdesc, off_wfrag;  // plan sections, in words (read on the host)
@@ -91,8 +95,18 @@ __device__ __forceinline__ void tile_pos(const TileCfg& t, int gt, int j, int* t
 // otherwise:
 //   B  compute is done with the patch and the weights; results, if any, are staged
 //   A  the next unit's patch and weights are in LDS
-template <int NT, bool NARROW>
+// KIND: what a 16-byte chunk of a pixel holds.
+enum { kBf16 = 0, kBf16Narrow = 1, kInt8 = 2 };
+
+template <int NT, int KIND>
 __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileCfg t, LdsCfg c) {
+  constexpr bool NARROW = KIND == kBf16Narrow;
+  // int8 codes: a chunk is sixteen channels, the MFMA is i32 16x16x64, sums are exact 32-bit
+  // integers, the results are int8 after a rounding shift (c.shift).  The data movers see
+  // pairs of codes as one 2-byte element (p.I counts such pairs), so the patch path is the
+  // same; the staging tile holds 64 bytes per pixel and leaves as 16-byte pieces of 16 channels.
+  constexpr bool I8 = KIND == kInt8;
+  constexpr int OUT_ROW = I8 ? kOutRowI8 : kOutRow;
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -138,7 +152,11 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
     int xg[kXBatch], xl[kXBatch], xq[kXBatch];
     // the results staging tile: piece q = ltid + 256 k is channels 8 (q & 7).. of pixel q >> 3
     // (filled in once the first unit's loads are on their way)
-    int fpos[NT], foff[NT];
+    constexpr int PPP = I8 ? 4 : 8;          // 16-byte pieces per staged pixel
+    constexpr int PXK = kLoaderThreads / PPP;  // pixels per round of the 256 threads
+    constexpr int NF = (NT * kPH * 16 + PXK - 1) / PXK;
+    const int fpart = ltid % PPP, fpix = ltid / PPP;
+    int fpos[NF], foff[NF];
 
     u32x4_t xv[kXBatch];
     // X + origin of the patch may point before the image (padding); only in-image pieces are read
@@ -208,14 +226,15 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
     };
     // results of tile tl: LDS staging tile -> Y as whole 16-byte pieces, eight consecutive
     // lanes covering the 64 output channels (128 bytes) of one pixel
-    uint16_t* Y = (uint16_t*)p.Y;
     auto flush = [&](int tl) {
       const int n = (int)fdiv((uint32_t)tl, t.d_tpi);
       const int trem = tl - n * tpi;
       const int tyi = (int)fdiv((uint32_t)trem, t.d_tiles_x);
       const int oy0 = tyi * t.TH, ox0 = (trem - tyi * t.tiles_x) * t.TW;
-      uint16_t* yorg = Y + (((int64_t)n * p.M + oy0) * p.N + ox0) * p.O + sg * 64;
-      const uint16_t* rorg = (const uint16_t*)p.residual + (yorg - Y);
+      // element offsets; an element of Y is 2 bytes (bf16) or 1 byte (int8)
+      constexpr int YES = I8 ? 1 : 2;
+      unsigned char* yorg = (unsigned char*)p.Y + ((((int64_t)n * p.M + oy0) * p.N + ox0) * p.O + sg * 64) * YES;
+      const unsigned char* rorg = (const unsigned char*)p.residual + (yorg - (unsigned char*)p.Y);
       const int my = p.M - oy0, mx = p.N - ox0;  // rows / columns of the tile inside the image
       // a few pieces at a time: all reads first, then the stores, so that neither waits on
       // the other.  Plain: four staged pieces.  Fused: two staged pieces and their two
@@ -224,23 +243,23 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
         constexpr int BS = decltype(bs_tag)::value;
         constexpr bool FUSED = decltype(fused_tag)::value;
 #pragma unroll
-        for (int k0 = 0; k0 < NT; k0 += BS) {
+        for (int k0 = 0; k0 < NF; k0 += BS) {
           u32x4_t ov[BS], rv[FUSED ? BS : 1];
           bool ok[BS];
 #pragma unroll
-          for (int k = k0; k < k0 + BS && k < NT; ++k) {
+          for (int k = k0; k < k0 + BS && k < NF; ++k) {
             const int f = fpos[k];
             ok[k - k0] = f >= 0 && (f >> 16) < my && (f & 0xFFFF) < mx;
             if constexpr (FUSED) {
               rv[k - k0] = u32x4_t{0u, 0u, 0u, 0u};
-              if (p.residual && ok[k - k0]) rv[k - k0] = *(const u32x4_t*)(rorg + foff[k]);
+              if (p.residual && ok[k - k0]) rv[k - k0] = *(const u32x4_t*)(rorg + foff[k] * YES);
             }
           }
 #pragma unroll
-          for (int k = k0; k < k0 + BS && k < NT; ++k)
-            ov[k - k0] = *(const u32x4_t*)(lds + c.obuf_off + ((ltid >> 3) + 32 * k) * kOutRow + (ltid & 7) * 16);
+          for (int k = k0; k < k0 + BS && k < NF; ++k)
+            ov[k - k0] = *(const u32x4_t*)(lds + c.obuf_off + (fpix + PXK * k) * OUT_ROW + fpart * 16);
 #pragma unroll
-          for (int k = k0; k < k0 + BS && k < NT; ++k) {
+          for (int k = k0; k < k0 + BS && k < NF; ++k) {
             if (!ok[k - k0]) continue;
             u32x4_t o = ov[k - k0];
             if constexpr (FUSED) {  // eight channels: + residual, activation, second rounding
@@ -263,11 +282,11 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
             }
             // streaming store: results are not read again here, and lines left dirty in L2
             // would all be written back in one burst when the kernel ends
-            __builtin_nontemporal_store(o, (u32x4_t*)(yorg + foff[k]));
+            __builtin_nontemporal_store(o, (u32x4_t*)(yorg + foff[k] * YES));
           }
         }
       };
-      if (p.residual || p.relu)
+      if (!I8 && (p.residual || p.relu))
         batch(std::integral_constant<int, 2>{}, std::true_type{});
       else
         batch(std::integral_constant<int, 4>{}, std::false_type{});
@@ -276,12 +295,14 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
     int sl = 0;
     first_patch(tile);
 #pragma unroll
-    for (int k = 0; k < NT; ++k) {
-      const int pi = (ltid >> 3) + 32 * k;
+    for (int k = 0; k < NF; ++k) {
+      const int pi = fpix + PXK * k;
       int ty, tx;
       tile_pos(t, pi >> 4, pi & 15, &ty, &tx);
-      fpos[k] = (ty < t.TH && tx < t.TW && sg * 64 + (ltid & 7) * 8 < p.O) ? (ty << 16 | tx) : -1;
-      foff[k] = (ty * p.N + tx) * p.O + (ltid & 7) * 8;
+      fpos[k] = (pi < NT * kPH * 16 && ty < t.TH && tx < t.TW && sg * 64 + fpart * (64 / PPP) < p.O)
+                    ? (ty << 16 | tx)
+                    : -1;
+      foff[k] = (ty * p.N + tx) * p.O + fpart * (64 / PPP);  // in elements of Y
     }
     commit_patch();
     __syncthreads();  // A: first unit is in LDS
@@ -345,11 +366,14 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
   int s_lo = valid ? slab_ptr[0] : 0, s_hi = valid ? slab_ptr[1] : 0;  // steps of the current slab
   issue_weights(s_lo, s_hi);
 
-  float bv[4] = {0.f, 0.f, 0.f, 0.f};
+  using acc_t = typename std::conditional<I8, i32x4_t, f32x4_t>::type;
+  using bias_t = typename std::conditional<I8, int32_t, float>::type;
+  bias_t bv[4] = {0, 0, 0, 0};
   const int ch = strip * BSP_STRIP + 4 * g;
   if (valid) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) bv[r] = (p.bias && ch + r < p.O) ? p.bias[ch + r] : 0.f;
+    for (int r = 0; r < 4; ++r)
+      bv[r] = (p.bias && ch + r < p.O) ? ((const bias_t*)p.bias)[ch + r] : (bias_t)0;
   }
   int base[NT];  // LDS base of this lane's pixel in each of the wave's pixel tiles
 #pragma unroll
@@ -359,11 +383,22 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
     base[nt] = (ty < t.TH && tx < t.TW) ? (ty * t.lsh) * t.pitch + (tx * t.lsw) * t.row_bytes : 0;
   }
   // where this lane's four channels of pixel jn of pixel tile nt go in the staging tile
-  const int orow = c.obuf_off + (half * NT * 16 + jn) * kOutRow + wave * (BSP_STRIP * 2) + g * 8;
+  const int orow = c.obuf_off + (half * NT * 16 + jn) * OUT_ROW +
+                   (I8 ? wave * BSP_STRIP + g * 4 : wave * (BSP_STRIP * 2) + g * 8);
 
-  f32x4_t acc[NT];
+  acc_t acc[NT];
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int nt = 0; nt < NT; ++nt) acc[nt] = acc_t{0, 0, 0, 0};
+  auto mma = [&](const u32x4_t& a, const u32x4_t (&b)[NT]) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      if constexpr (I8)
+        acc[nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4_t, a),
+                                                        __builtin_bit_cast(i32x4_t, b[nt]), acc[nt], 0, 0, 0);
+      else
+        acc[nt] = mfma_bf16_16x16x32(a, b[nt], acc[nt]);
+    }
+  };
 
   int sl = 0;
   commit_weights();
@@ -388,12 +423,12 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
         const int x2 = xo[min(s + 2, lastq) * 4 + g];
         a[1] = wl[min(s + 1, lastq) * 64 + lane];
         load_b_at<NT>(b[1], x1, lds, base);
-        do_mma<NT>(acc, a[0], b[0]);
+        mma(a[0], b[0]);
         if (s + 1 < nst) {
           x1 = xo[min(s + 3, lastq) * 4 + g];
           a[0] = wl[min(s + 2, lastq) * 64 + lane];
           load_b_at<NT>(b[0], x2, lds, base);
-          do_mma<NT>(acc, a[1], b[1]);
+          mma(a[1], b[1]);
         }
       }
     }
@@ -402,11 +437,23 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileC
       // + bias, one rounding; lane holds channels 4g..4g+3 of pixel jn of every pixel tile
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
-        u32x2_t v;
-        v.x = pack_bf16x2(acc[nt][0] + bv[0], acc[nt][1] + bv[1]);
-        v.y = pack_bf16x2(acc[nt][2] + bv[2], acc[nt][3] + bv[3]);
-        acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        *(u32x2_t*)(lds + orow + nt * 16 * kOutRow) = v;
+        if constexpr (I8) {
+          // exact sum + 32-bit bias, rounding right shift (ties upward), saturation to int8
+          uint32_t packed = 0;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const long long sft = ((long long)acc[nt][r] + bv[r] + (c.shift > 0 ? 1ll << (c.shift - 1) : 0)) >> c.shift;
+            const int q = sft < -128 ? -128 : (sft > 127 ? 127 : (int)sft);
+            packed |= (uint32_t)(q & 0xFF) << (8 * r);
+          }
+          *(uint32_t*)(lds + orow + nt * 16 * OUT_ROW) = packed;
+        } else {
+          u32x2_t v;
+          v.x = pack_bf16x2(acc[nt][0] + bv[0], acc[nt][1] + bv[1]);
+          v.y = pack_bf16x2(acc[nt][2] + bv[2], acc[nt][3] + bv[3]);
+          *(u32x2_t*)(lds + orow + nt * 16 * OUT_ROW) = v;
+        }
+        acc[nt] = acc_t{0, 0, 0, 0};
       }
     }
     if (reload_w) {
@@ -435,34 +482,44 @@ int device_cus() {
 
 constexpr int64_t kLdsPerCu = 160 * 1024;
 
-template <int NT, bool NARROW>
+template <int NT, int KIND>
 int launch(const ConvParams& p, const TileCfg& t, const LdsCfg& c, dim3 grid, size_t ldsb,
            hipStream_t st) {
   static bool raised = false;  // dynamic LDS above 64 KB has to be allowed once per kernel
   if (!raised) {
-    if (hipFuncSetAttribute((const void*)conv_lds_bf16<NT, NARROW>,
+    if (hipFuncSetAttribute((const void*)conv_lds_bf16<NT, KIND>,
                             hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)kLdsPerCu) != hipSuccess)
       return BSP_ERR_HIP;
     raised = true;
   }
-  hipLaunchKernelGGL((conv_lds_bf16<NT, NARROW>), grid, dim3(kThreads), ldsb, st, p, t, c);
+  hipLaunchKernelGGL((conv_lds_bf16<NT, KIND>), grid, dim3(kThreads), ldsb, st, p, t, c);
   return hipGetLastError() == hipSuccess ? BSP_OK : BSP_ERR_HIP;
 }
 
 }  // namespace
 
-int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hipStream_t st) {
-  // input channels: whole 8-channel chunks, or at most 4 in all (a first layer's RGB planes),
-  // which the data movers then gather element by element into one zero-padded chunk
-  if (!plan_host || dtype != BSP_BF16 || ((p_in.I % 8) != 0 && p_in.I > 4) || (p_in.O % 8) != 0)
+namespace {
+
+// dtype BSP_BF16: bf16 layers.  dtype BSP_I8: int8 codes in, int8 results after `shift`.
+int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shift, hipStream_t st) {
+  const bool i8 = dtype == BSP_I8;
+  // input channels: whole 16-byte chunks (8 bf16 or 16 int8), or, for bf16, at most 4 in all
+  // (a first layer's RGB planes), which the data movers then gather element by element into
+  // one zero-padded chunk.  int8 results leave as pieces of 16 channels.
+  if (!plan_host || (dtype != BSP_BF16 && !i8)) return BSP_ERR_UNSUPPORTED;
+  if (i8 ? ((p_in.I % 16) != 0 || (p_in.O % 16) != 0)
+         : (((p_in.I % 8) != 0 && p_in.I > 4) || (p_in.O % 8) != 0))
     return BSP_ERR_UNSUPPORTED;
   const int32_t* hdr = (const int32_t*)plan_host;
   if (hdr[BSP_PLAN_MAGIC_W] != BSP_PLAN_MAGIC || hdr[BSP_PLAN_VERSION_W] != BSP_PLAN_VERSION ||
       hdr[BSP_PLAN_O_W] != p_in.O || hdr[BSP_PLAN_I_W] != p_in.I || hdr[BSP_PLAN_H_W] != p_in.H ||
-      hdr[BSP_PLAN_K_W] != p_in.K || hdr[BSP_PLAN_DTYPE_W] != BSP_BF16)
+      hdr[BSP_PLAN_K_W] != p_in.K || hdr[BSP_PLAN_DTYPE_W] != dtype)
     return BSP_ERR_UNSUPPORTED;
   ConvParams p = p_in;
+  const int plan_slab = i8 ? hdr[BSP_PLAN_SLAB_W] / 2 : hdr[BSP_PLAN_SLAB_W];
+  if (i8) p.I /= 2;  // from here on an input element is a pair of codes (2 bytes, like a bf16)
+  const int out_row = i8 ? kOutRowI8 : kOutRow;
   if (p.H == 1 && p.K == 1 && p.sh == 1 && p.sw == 1 && p.ph == 0 && p.pw == 0) {
     p.J = p.N = p.P;
     p.L = p.M = 1;
@@ -481,9 +538,9 @@ int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hip
   int NT = 0;
   {
     static std::mutex mu;
-    static std::map<std::array<int32_t, 11>, std::pair<int, TileCfg>> memo;
-    const std::array<int32_t, 11> key = {p.M, p.N, p.I, p.O, p.H, p.K, p.sh, p.sw, p.ph, p.pw,
-                                         c.maxsteps};
+    static std::map<std::array<int32_t, 12>, std::pair<int, TileCfg>> memo;
+    const std::array<int32_t, 12> key = {p.M, p.N, p.I, p.O, p.H, p.K, p.sh, p.sw, p.ph, p.pw,
+                                         c.maxsteps, dtype};
     std::lock_guard<std::mutex> lock(mu);
     auto it = memo.find(key);
     if (it == memo.end()) {
@@ -491,7 +548,7 @@ int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hip
       t.nslabs = ((p.I + 7) / 8 + t.slab / 8 - 1) / (t.slab / 8);
       t.nstrips = (p.O + BSP_STRIP - 1) / BSP_STRIP;
       // the LDS left after the weights holds the patch and the results staging tile
-      if (!bsp_choose_tile(p, t.slab, kLdsPerCu - wbytes, kLoaderThreads * kXBatch, kPH, kOutRow,
+      if (!bsp_choose_tile(p, t.slab, kLdsPerCu - wbytes, kLoaderThreads * kXBatch, kPH, out_row,
                            2, &NT, &t))
         NT = 0;
       if (memo.size() > 4096) memo.clear();
@@ -501,13 +558,13 @@ int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hip
     t = it->second.second;
     if (NT == 0) return BSP_ERR_UNSUPPORTED;
   }
-  if (t.nslabs != nslabs || t.slab != hdr[BSP_PLAN_SLAB_W]) return BSP_ERR_UNSUPPORTED;
+  if (t.nslabs != nslabs || t.slab != plan_slab) return BSP_ERR_UNSUPPORTED;
   if (t.TPH * t.gsh >= 1024 || t.TPW * t.gsw >= 1024 || t.slab / BSP_CHUNK > 32)
     return BSP_ERR_UNSUPPORTED;
   const int64_t ntiles = (int64_t)p.B * t.tiles_y * t.tiles_x;
   c.wbuf_off = (t.TPH * t.pitch + 15) & ~15;
   c.obuf_off = c.wbuf_off + (int32_t)wbytes;
-  const size_t ldsb = (size_t)c.obuf_off + (size_t)NT * kPH * 16 * kOutRow;
+  const size_t ldsb = (size_t)c.obuf_off + (size_t)NT * kPH * 16 * out_row;
   if ((int64_t)ldsb > kLdsPerCu) return BSP_ERR_UNSUPPORTED;
   c.groups = (t.nstrips + 3) / 4;
   // persistent grid: one workgroup per CU, shared out among the strip groups
@@ -548,21 +605,43 @@ int bsp_launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, hip
   // long compute phases (windows over several slabs) hide the movers anyway, and their
   // instructions then only take issue slots from the matrix cores
   c.mover_first = !(p.H * p.K > 1 && nslabs > 1);
+  c.shift = shift;
   c.nsteps = hdr[BSP_PLAN_NSTEPS_W];
   c.off_slab = hdr[BSP_PLAN_OFF_SLAB_W];
   c.off_xdesc = hdr[BSP_PLAN_OFF_XDESC_W];
   c.off_wfrag = hdr[BSP_PLAN_OFF_WFRAG_W];
   dim3 grid((unsigned)nwg);
+  if (i8) {
+    switch (NT) {
+      case 2: return launch<2, kInt8>(p, t, c, grid, ldsb, st);
+      case 4: return launch<4, kInt8>(p, t, c, grid, ldsb, st);
+      case 7: return launch<7, kInt8>(p, t, c, grid, ldsb, st);
+      case 8: return launch<8, kInt8>(p, t, c, grid, ldsb, st);
+      default: return BSP_ERR_UNSUPPORTED;
+    }
+  }
   if ((p.I % 8) != 0) {  // first layers are large: the two large tile shapes are enough
-    if (NT == 7) return launch<7, true>(p, t, c, grid, ldsb, st);
-    if (NT == 8) return launch<8, true>(p, t, c, grid, ldsb, st);
+    if (NT == 7) return launch<7, kBf16Narrow>(p, t, c, grid, ldsb, st);
+    if (NT == 8) return launch<8, kBf16Narrow>(p, t, c, grid, ldsb, st);
     return BSP_ERR_UNSUPPORTED;
   }
   switch (NT) {
-    case 2: return launch<2, false>(p, t, c, grid, ldsb, st);
-    case 4: return launch<4, false>(p, t, c, grid, ldsb, st);
-    case 7: return launch<7, false>(p, t, c, grid, ldsb, st);
-    case 8: return launch<8, false>(p, t, c, grid, ldsb, st);
+    case 2: return launch<2, kBf16>(p, t, c, grid, ldsb, st);
+    case 4: return launch<4, kBf16>(p, t, c, grid, ldsb, st);
+    case 7: return launch<7, kBf16>(p, t, c, grid, ldsb, st);
+    case 8: return launch<8, kBf16>(p, t, c, grid, ldsb, st);
     default: return BSP_ERR_UNSUPPORTED;
   }
+}
+
+}  // namespace
+
+int bsp_launch_lds(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st) {
+  if (dtype != BSP_BF16) return BSP_ERR_UNSUPPORTED;
+  return launch_lds(p, dtype, plan_host, 0, st);
+}
+
+int bsp_launch_lds_i8(const ConvParams& p, const void* plan_host, int shift, hipStream_t st) {
+  if (p.residual || p.relu) return BSP_ERR_UNSUPPORTED;
+  return launch_lds(p, BSP_I8, plan_host, shift, st);
 }

@@ -68,6 +68,53 @@ def test_shifted_int8_output_bit_exact(shift):
         assert Y.dtype == torch.int8 and (Y.cpu().numpy() == want).all(), (shape, shift)
 
 
+LDS_SHAPES = [
+    # channel counts in whole 16-code chunks: these take the LDS-resident int8 kernel
+    (2, 20, 20, 64, 64, 3, 3, (1, 1), (1, 1)),       # one slab
+    (1, 14, 14, 192, 128, 3, 3, (1, 1), (1, 1)),     # two slabs, two strip groups
+    (3, 13, 13, 128, 96, 1, 1, (1, 1), (0, 0)),      # pointwise, ragged strip group
+    (2, 15, 15, 144, 32, 3, 3, (2, 2), (1, 1)),      # two slabs, strided
+    (1, 9, 9, 512, 48, 1, 1, (2, 2), (0, 0)),        # strided pointwise
+    (1, 20, 33, 64, 64, 3, 3, (1, 1), (1, 1)),       # tiles hang over both image edges
+    (2, 6, 11, 16, 48, 1, 7, (1, 1), (0, 3)),
+    (2, 11, 6, 48, 16, 7, 1, (1, 1), (3, 0)),
+    (2, 40, 40, 32, 16, 3, 3, (1, 1), (1, 1)),       # several tiles per workgroup
+]
+
+
+@pytest.mark.parametrize("bo,bi", GRANS)
+def test_lds_int8_kernel_bit_exact(bo, bi):
+    import torch
+    for n, shape in enumerate(LDS_SHAPES):
+        X, W, bias, gamma, s, p = _draw(shape, 300 + n, bo, bi, extreme=(n % 4 == 0))
+        print("case", n, shape, bo, bi, flush=True)
+        layer = bsp.BspLayerI8(W, gamma, bo, bi, bias=bias)
+        Xd = torch.from_numpy(X).cuda()
+        for shift in (0, 6, 11):
+            Y = layer.conv2d(Xd, s, p, shift=shift)
+            torch.cuda.synchronize()
+            want = oracle.conv2d_i8(X, W, bias, gamma, bo, bi, s, p, shift=shift)
+            assert (Y.cpu().numpy() == want).all(), (shape, bo, bi, shift)
+        # the int32 sums (general kernel) shifted on the host give the same bytes
+        Y32 = layer.conv2d(Xd, s, p).cpu().numpy().astype(np.int64)
+        assert (oracle.requant_shift(Y32, 6) == oracle.conv2d_i8(X, W, bias, gamma, bo, bi, s, p, shift=6)).all()
+
+
+def test_int8_config1_full_size():
+    import torch
+    from synthetic import config_cases
+    c = next(config_cases(1))
+    Wq, _ = bsp.bsp_quantize(c.W)
+    Xq = np.clip(np.rint(c.X * 32.0), -128, 127).astype(np.int8)
+    bias = np.arange(c.O, dtype=np.int32) * 37 - 1000
+    layer = bsp.BspLayerI8(Wq, c.gamma, c.bo, c.bi, bias=bias)
+    Y = layer.conv2d(torch.from_numpy(Xq).cuda(), c.stride, c.pad, shift=9)
+    torch.cuda.synchronize()
+    want = oracle.conv2d_i8(Xq, Wq, bias, c.gamma, c.bo, c.bi, c.stride, c.pad, shift=9)
+    assert (Y.cpu().numpy() == want).all()
+    assert np.abs(want).max() > 20 and (want == 127).sum() < want.size // 100   # a live, unsaturated layer
+
+
 def test_rounding_ties_and_saturation_on_gpu():
     """One kept block of ones against chosen inputs puts exact ties and both saturation ends
     into the sums."""
