@@ -99,7 +99,7 @@ __device__ __forceinline__ void tile_pos(const TileCfg& t, int gt, int j, int* t
 enum { kBf16 = 0, kBf16Narrow = 1, kInt8 = 2 };
 
 template <int NT, int KIND>
-__global__ __launch_bounds__(kThreads, 1) void conv_lds_bf16(ConvParams p, TileCfg t, LdsCfg c) {
+__global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t, LdsCfg c) {
   constexpr bool NARROW = KIND == kBf16Narrow;
   // int8 codes: a chunk is sixteen channels, the MFMA is i32 16x16x64, sums are exact 32-bit
   // integers, the results are int8 after a rounding shift (c.shift).  The data movers see
@@ -487,13 +487,13 @@ int launch(const ConvParams& p, const TileCfg& t, const LdsCfg& c, dim3 grid, si
            hipStream_t st) {
   static bool raised = false;  // dynamic LDS above 64 KB has to be allowed once per kernel
   if (!raised) {
-    if (hipFuncSetAttribute((const void*)conv_lds_bf16<NT, KIND>,
+    if (hipFuncSetAttribute((const void*)conv_lds<NT, KIND>,
                             hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)kLdsPerCu) != hipSuccess)
       return BSP_ERR_HIP;
     raised = true;
   }
-  hipLaunchKernelGGL((conv_lds_bf16<NT, KIND>), grid, dim3(kThreads), ldsb, st, p, t, c);
+  hipLaunchKernelGGL((conv_lds<NT, KIND>), grid, dim3(kThreads), ldsb, st, p, t, c);
   return hipGetLastError() == hipSuccess ? BSP_OK : BSP_ERR_HIP;
 }
 
