@@ -5,3 +5,4 @@ from .quant import (conv2d_i8, fc_i8, pack_reference_i8, quantize_eq8,  # noqa: 
                     requant_shift)
 from .select import block_importance, incremental_step, select_mask  # noqa: F401
 from . import select as select  # noqa: F401
+from .spgemm import mask_blocks, matching_block_products, spgemm_nt  # noqa: F401
