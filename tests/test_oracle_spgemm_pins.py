@@ -23,8 +23,8 @@ def _merge_product(A, gamma, B, omega, k):
                     y += 1
                 else:
                     c = la[x]
-                    C[i * k:(i + 1) * k, j * k:(j + 1) * k] += \\
-                        A[i * k:(i + 1) * k, c * k:(c + 1) * k] @ B[j * k:(j + 1) * k, c * k:(c + 1) * k].T
+                    C[i * k:(i + 1) * k, j * k:(j + 1) * k] += (
+                        A[i * k:(i + 1) * k, c * k:(c + 1) * k] @ B[j * k:(j + 1) * k, c * k:(c + 1) * k].T)
                     count += 1
                     x += 1
                     y += 1
