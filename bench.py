@@ -136,6 +136,77 @@ def bench_i8(args) -> int:
     return 0
 
 
+def bench_spgemm(args) -> int:
+    """Block-sparse x block-sparse product (Section III-A): square operands of 4096 x 4096 bf16
+    in 8x8 blocks, each with a Bernoulli(0.5) block mask; C = (Gamma A)(Omega B)^t in fp32."""
+    import torch
+    import paper_2407_09453_amd as bsp
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    n = 512                                    # block rows = block columns
+    rng = np.random.default_rng(240709453 + 9000)
+    A = rng.standard_normal((n * 8, n * 8)).astype(np.float32).view(np.uint32)
+    B = rng.standard_normal((n * 8, n * 8)).astype(np.float32).view(np.uint32)
+    A = (A & np.uint32(0xFFFF0000)).view(np.float32)      # onto the bf16 grid
+    B = (B & np.uint32(0xFFFF0000)).view(np.float32)
+    gamma = (rng.random((n, n)) < 0.5).astype(np.uint8)
+    omega = (rng.random((n, n)) < 0.5).astype(np.uint8)
+    Am, Bm = bsp.BspMatrix(A, gamma), bsp.BspMatrix(B, omega)
+    ones = np.ones((n, n), dtype=np.uint8)
+    Ad, Bd = bsp.BspMatrix(A, ones), bsp.BspMatrix(B, ones)
+    C = torch.empty((n * 8, n * 8), dtype=torch.float32, device="cuda:0")
+    stream = torch.cuda.current_stream()
+
+    def timed(x, y):
+        for _ in range(args.warmup):
+            x.matmul_nt(y, out=C)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t = time.perf_counter()
+        e0.record(stream)
+        for _ in range(args.steps):
+            x.matmul_nt(y, out=C)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / args.steps, e0.elapsed_time(e1) / args.steps
+
+    ms, ms_ev = timed(Am, Bm)
+    ms_d, _ = timed(Ad, Bd)
+    pairs = int((gamma.astype(np.int64) @ omega.astype(np.int64).T).sum())
+    flops = 2 * 512 * pairs                                   # 8x8x8 multiply-adds per block pair
+    nbytes = (Am.nnzb + Bm.nnzb) * 128 + 2 * n * n * 4 + C.numel() * 4
+    out = {
+        "metric": "effective TFLOP/s of the block-sparse x block-sparse product (2*8^3 per matching block pair)",
+        "value": round(flops / (ms * 1e-3) / 1e12, 4), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "C = (Gamma A)(Omega B)^t, A and B 4096x4096 bf16 in 8x8 blocks, "
+                               "Bernoulli(0.5) masks, C fp32", "matching_block_pairs": pairs,
+                   "nnzb_a": Am.nnzb, "nnzb_b": Bm.nnzb},
+        "speedup_vs_dense_mask": round(ms_d / ms, 4), "dense_mask_ms_per_step": round(ms_d, 6),
+        "event_ms_per_step": round(ms_ev, 6),
+        "roofline": {"bound": "mfma", "achieved": round(flops / (ms_ev * 1e-3) / 1e12, 3),
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(flops / (ms_ev * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5),
+                     "traffic": None, "algorithmic_bytes": int(nbytes)},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        m = n                                     # the whole problem: a masked fp64 matmul
+        t = time.perf_counter()
+        oracle.spgemm_nt(A[:m * 8], gamma[:m], B[:m * 8], omega[:m], 8)
+        dt = time.perf_counter() - t
+        sub = int((gamma[:m].astype(np.int64) @ omega[:m].astype(np.int64).T).sum())
+        out["cpu_baseline"] = {"value": round(2 * 512 * sub / dt / 1e12, 6), "unit": "TFLOP/s",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+                               "kind": "oracle",
+                               "sample": f"the first {m} block rows of A against the first {m} of B "
+                                         f"({dt:.2f} s; masked dense fp64 matmul, nothing skipped)"}
+    print(json.dumps(out))
+    return 0
+
+
 def bench_network(args, net: str) -> int:
     """Per-layer timing of a whole network-shaped stack: every layer on its own
     resident N(0,1) input (layers are independent: glue such as pooling is not
@@ -212,7 +283,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c1",
-                    help="c1 (default), c0, c2:<bo>x<bi>.d<density>, c1_i8, resnet50, vgg16, inception_v3")
+                    help="c1 (default), c0, c2:<bo>x<bi>.d<density>, c1_i8, spgemm, resnet50, vgg16, inception_v3")
     ap.add_argument("--sets", type=int, default=0,
                     help="distinct X/Y buffer sets cycled through (0 = enough to exceed 256 MB)")
     ap.add_argument("--mask", default="synthetic", choices=["synthetic", "l2", "l1", "var"],
@@ -235,6 +306,10 @@ def main() -> int:
         return 2
     if args.workload == "c1_i8":
         return bench_i8(args)
+    if args.workload == "spgemm":
+        if args.steps == 400:
+            args.steps, args.warmup = 50, 5
+        return bench_spgemm(args)
     if args.workload in ("resnet50", "vgg16", "inception_v3"):
         if args.steps == 400:
             args.steps, args.warmup = 30, 5

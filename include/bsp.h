@@ -195,6 +195,35 @@ int bsp_conv2d_general(const bsp_weights* w, const void* X, const float* bias, v
                        int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
                        void* stream);
 
+/* ------------------------------------------- block-sparse x block-sparse product
+ * Paper Section III-A: C = (Gamma A) (Omega B)^t with k x k blocks; a block product is done
+ * if and only if both blocks are kept (the paper merges the two sorted lists of kept block
+ * columns; here the same matches are found from a dense position table per operand).
+ * An operand is what bsp_pack makes of a matrix [rows*8][1][1][cols*8] with 8x8 blocks:
+ * row_ptr / col_idx / payload [nnzb][8][8], plus the position table from bsp_bcsr_index.
+ */
+typedef struct {
+  int32_t rows, cols;      /* block rows and block columns */
+  int32_t k;               /* block edge; 8 */
+  int32_t dtype;           /* BSP_BF16 */
+  int64_t nnzb;
+  const int32_t* row_ptr;  /* device, rows + 1 */
+  const int32_t* col_idx;  /* device, nnzb */
+  const void* payload;     /* device, [nnzb][k][k], 16-byte aligned */
+  const int32_t* index;    /* device, [rows][cols]: position of block (r, c) in payload, or -1 */
+} bsp_bcsr;
+
+/* Host: fill index[rows][cols] from row_ptr / col_idx (validated first).
+ * Errors: NULL, SHAPE, INDEX. */
+int bsp_bcsr_index(const int32_t* row_ptr, const int32_t* col_idx, int32_t rows, int32_t cols,
+                   int32_t* index);
+
+/* Device: C [A.rows*k][B.rows*k] float, row-major, = A . B^t, every element written (zero
+ * where no block pair matches); fp32 accumulation of bf16 products.  A.cols must equal
+ * B.cols.  Asynchronous on `stream`.  Errors: NULL, SHAPE, DTYPE, UNSUPPORTED (k != 8),
+ * ALIGN, HIP. */
+int bsp_spgemm_nt(const bsp_bcsr* A, const bsp_bcsr* B, float* C, void* stream);
+
 /* ------------------------------------------------------- choosing the mask (host)
  * Paper Section IV ("Predetermined Sparsity ratio and Full Training Ahead"): every mask
  * entry stands for one block W_i; blocks are ranked by an importance measure and the least

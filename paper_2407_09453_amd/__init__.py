@@ -12,6 +12,9 @@ from .binding import (  # noqa: F401
     BspError,
     BspLayer,
     BspLayerI8,
+    BspMatrix,
+    bsp_bcsr,
+    bsp_bcsr_index,
     bsp_block_importance,
     bsp_conv2d,
     bsp_conv2d_fused,
@@ -27,6 +30,7 @@ from .binding import (  # noqa: F401
     bsp_plan_size,
     bsp_quantize,
     bsp_select_mask,
+    bsp_spgemm_nt,
     bsp_strerror,
     bsp_unpack,
     bsp_validate,
