@@ -1,22 +1,23 @@
-// LDS-resident variant of the tiled bf16 kernel: weights AND activations of the
-// current slab of input channels live in LDS, the hot loop touches nothing else.
+// LDS-resident tiled kernel: weights AND activations of the current slab of input channels
+// live in LDS, the hot loop touches nothing else.  bf16 layers (fp32 accumulation), first
+// layers with at most four input channels, and int8 layers (exact int32 sums).
 //
-// A persistent workgroup of eight waves owns a group of four strips (wave w:
-// strip w & 3, pixel-tile share w >> 2) and walks units = (pixel tile of an
-// image, slab of input channels).  For each unit the input patch of the slab
-// and the four strips' weight fragments of the slab are copied into LDS, the
-// step descriptors are turned into ready LDS offsets, and the waves run the
-// slab's steps reading only LDS (weights, offsets and activations each one
-// step ahead of the MFMAs).  While a unit is computed, the global loads of the
-// NEXT unit are already in flight into registers, so their latency is hidden
-// and, since the loop issues no other vector memory operation, nothing queues
-// up behind them.  When all of a layer's input channels fit one slab the
-// weights are copied once and stay for every tile the workgroup visits.  After
-// the last slab of a tile the results (+ bias, rounded once to bf16) go through
-// an LDS staging tile and leave as whole 16-byte pieces, eight lanes per pixel.
+// A persistent workgroup of twelve waves owns a group of four strips (64 output channels)
+// and walks units = (pixel tile of an image, slab of input channels).  Eight waves compute
+// (wave w: strip w & 3, pixel-tile share w >> 2), four move data.  For each unit the input
+// patch of the slab and the four strips' weight fragments of the slab are copied into LDS,
+// the step descriptors are turned into ready LDS offsets, and the compute waves run the
+// slab's steps reading only LDS (weights, offsets and activations each one step ahead of
+// the MFMAs).  While a unit is computed, the global loads of the NEXT unit are already in
+// flight into registers (the patch in the mover waves, the weight fragments in spare
+// registers of the compute waves), so their latency is hidden.  When all of a layer's input
+// channels fit one slab the weights are copied once and stay for every tile the workgroup
+// visits.  After the last slab of a tile the results (+ bias, rounded once) go through an
+// LDS staging tile and leave as whole 16-byte pieces; a residual add and a ReLU can be
+// applied on the way out.
 //
-// Only kept blocks have steps (paper Section I, advantages 3-4): work and
-// weight traffic shrink with the mask, the patch traffic does not.
+// Only kept blocks have steps (paper Section I, advantages 3-4): work and weight traffic
+// shrink with the mask, the patch traffic does not.
 #include "bsp_launch.h"
 #include "bsp_tile.h"
 
