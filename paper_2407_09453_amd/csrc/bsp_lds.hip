@@ -22,6 +22,7 @@
 #include "bsp_tile.h"
 
 #include <array>
+#include <cstdlib>
 #include <type_traits>
 #include <map>
 #include <mutex>
@@ -49,6 +50,9 @@ struct LdsCfg {
   int32_t nsteps;         // steps in the whole plan
   int32_t mover_first;    // raise the data movers' wave priority
   int32_t shift;          // int8 results: rounding right shift of the 32-bit sums
+  int32_t part_bytes;     // LDS bytes between a pixel's consecutive 16-byte chunks: 16 when a
+                          // pixel's chunks lie side by side, the plane size when every chunk
+                          // index has a plane of its own (then t.row_bytes is 16)
   int32_t groups;         // strip groups (of four)
   int32_t wg_per_group;   // workgroups sharing one strip group
   int32_t off_slab, off_xdesc, off_wfrag;  // plan sections, in words (read on the host)
@@ -99,7 +103,7 @@ __device__ __forceinline__ void tile_pos(const TileCfg& t, int gt, int j, int* t
 // KIND: what a 16-byte chunk of a pixel holds.
 enum { kBf16 = 0, kBf16Narrow = 1, kInt8 = 2 };
 
-template <int NT, int KIND>
+template <int NT, int KIND, bool RELOAD>
 __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t, LdsCfg c) {
   constexpr bool NARROW = KIND == kBf16Narrow;
   // int8 codes: a chunk is sixteen channels, the MFMA is i32 16x16x64, sums are exact 32-bit
@@ -121,7 +125,9 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
 
   const int tpi = t.tiles_y * t.tiles_x;
   const int nsl1 = t.nslabs + 1;
-  const bool reload_w = t.nslabs > 1;
+  // RELOAD: the layer has several slabs, so the weights of the next one are staged while
+  // this one is computed (registers for that; the step loop then prefetches less deeply)
+  constexpr bool reload_w = RELOAD;
   const int32_t* plan = p.plan;
 
   // which tile / slab follows (tile, sl), and whether there is one
@@ -200,7 +206,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
       int part = ltid - pix * PP;
       const int py0 = (int)fdiv((uint32_t)pix, t.d_tpw);
       int px = pix - py0 * t.TPW;
-      int l = py0 * t.pitch + px * t.row_bytes + part * 16;
+      int l = py0 * t.pitch + px * t.row_bytes + part * c.part_bytes;
       uint32_t g = (uint32_t)((py0 * t.gsh * p.J + px * t.gsw) * p.I + part * BSP_CHUNK);
       int iy = py0 * t.gsh, ix = px * t.gsw;
 #pragma unroll
@@ -343,7 +349,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
   // The strip's weight fragments of a slab go global -> registers -> LDS, this wave moving
   // steps [half * kWHalf, half * kWHalf + kWHalf) of them, and with them the LDS offsets
   // the steps' activation fragments are read at.
-  u32x4_t wv[kWHalf];
+  u32x4_t wv[kWHalf];  // live across the step loop only when RELOAD
   int dsc = 0, w_n = 0;
   // All kWHalf loads are always issued, in one straight line so that they are in flight
   // together; those past the wave's share repeat its last fragment and are dropped.
@@ -361,7 +367,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
       if (u < w_n) wl[(half * kWHalf + u) * 64 + lane] = wv[u];
     if (lane < w_n * 4)
       xo[half * kWHalf * 4 + lane] = ((dsc >> 16) & 0xFF) * t.pitch +
-                                     ((dsc >> 24) & 0xFF) * t.row_bytes + (dsc & 0xFFFF) * 16;
+                                     ((dsc >> 24) & 0xFF) * t.row_bytes + (dsc & 0xFFFF) * c.part_bytes;
   };
 
   int s_lo = valid ? slab_ptr[0] : 0, s_hi = valid ? slab_ptr[1] : 0;  // steps of the current slab
@@ -413,23 +419,32 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
       s_hi = valid ? slab_ptr[nsl + 1] : 0;
       issue_weights(s_lo, s_hi);
     }
-    // this slab's steps, everything from LDS and one step ahead (offsets two)
+    // this slab's steps, everything from LDS and D - 1 steps ahead of the MFMAs (offsets one
+    // more): the fragments of step s + D - 1 are requested before the MFMAs of step s go out.
+    // Two steps ahead where the registers allow it: one step does not cover the LDS latency.
     if (nst > 0) {
-      u32x4_t a[2], b[2][NT];
+      constexpr int D = (NT >= 8 || (RELOAD && NT > 4)) ? 2 : 3;
+      u32x4_t a[D], b[D][NT];
+      int x[D];
       const int lastq = nst - 1;
-      int x1 = xo[min(1, lastq) * 4 + g];
-      a[0] = wl[lane];
-      load_b_at<NT>(b[0], xo[g], lds, base);
-      for (int s = 0; s < nst; s += 2) {
-        const int x2 = xo[min(s + 2, lastq) * 4 + g];
-        a[1] = wl[min(s + 1, lastq) * 64 + lane];
-        load_b_at<NT>(b[1], x1, lds, base);
-        mma(a[0], b[0]);
-        if (s + 1 < nst) {
-          x1 = xo[min(s + 3, lastq) * 4 + g];
-          a[0] = wl[min(s + 2, lastq) * 64 + lane];
-          load_b_at<NT>(b[0], x2, lds, base);
-          mma(a[1], b[1]);
+#pragma unroll
+      for (int u = 0; u < D; ++u) x[u] = xo[min(u, lastq) * 4 + g];
+#pragma unroll
+      for (int u = 0; u < D - 1; ++u) {
+        a[u] = wl[min(u, lastq) * 64 + lane];
+        load_b_at<NT>(b[u], x[u], lds, base);
+      }
+      for (int s = 0; s < nst; s += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+          if (s + u < nst) {
+            const int nx = (u + D - 1) % D;  // buffer of step s + u + D - 1
+            const int xn = xo[min(s + u + D, lastq) * 4 + g];
+            a[nx] = wl[min(s + u + D - 1, lastq) * 64 + lane];
+            load_b_at<NT>(b[nx], x[nx], lds, base);
+            x[u] = xn;  // the offset of step s + u + D takes the place of step s + u's
+            mma(a[u], b[u]);
+          }
         }
       }
     }
@@ -483,19 +498,30 @@ int device_cus() {
 
 constexpr int64_t kLdsPerCu = 160 * 1024;
 
-template <int NT, int KIND>
-int launch(const ConvParams& p, const TileCfg& t, const LdsCfg& c, dim3 grid, size_t ldsb,
-           hipStream_t st) {
+template <int NT, int KIND, bool RELOAD>
+int launch_one(const ConvParams& p, const TileCfg& t, const LdsCfg& c, dim3 grid, size_t ldsb,
+               hipStream_t st) {
   static bool raised = false;  // dynamic LDS above 64 KB has to be allowed once per kernel
   if (!raised) {
-    if (hipFuncSetAttribute((const void*)conv_lds<NT, KIND>,
+    if (hipFuncSetAttribute((const void*)conv_lds<NT, KIND, RELOAD>,
                             hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)kLdsPerCu) != hipSuccess)
       return BSP_ERR_HIP;
     raised = true;
   }
-  hipLaunchKernelGGL((conv_lds<NT, KIND>), grid, dim3(kThreads), ldsb, st, p, t, c);
+  hipLaunchKernelGGL((conv_lds<NT, KIND, RELOAD>), grid, dim3(kThreads), ldsb, st, p, t, c);
   return hipGetLastError() == hipSuccess ? BSP_OK : BSP_ERR_HIP;
+}
+
+template <int NT, int KIND>
+int launch(const ConvParams& p, const TileCfg& t, const LdsCfg& c, dim3 grid, size_t ldsb,
+           hipStream_t st) {
+  if constexpr (KIND == kBf16Narrow) {  // first layers have one slab
+    return launch_one<NT, KIND, false>(p, t, c, grid, ldsb, st);
+  } else {
+    return t.nslabs > 1 ? launch_one<NT, KIND, true>(p, t, c, grid, ldsb, st)
+                        : launch_one<NT, KIND, false>(p, t, c, grid, ldsb, st);
+  }
 }
 
 }  // namespace
@@ -563,7 +589,16 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
   if (t.TPH * t.gsh >= 1024 || t.TPW * t.gsw >= 1024 || t.slab / BSP_CHUNK > 32)
     return BSP_ERR_UNSUPPORTED;
   const int64_t ntiles = (int64_t)p.B * t.tiles_y * t.tiles_x;
-  c.wbuf_off = (t.TPH * t.pitch + 15) & ~15;
+  c.part_bytes = 16;
+  int64_t patch_bytes = (int64_t)t.TPH * t.pitch;
+  if (const char* e = getenv("BSP_PLANAR")) {  // experiment: one plane per chunk index
+    const int pad = atoi(e);
+    t.row_bytes = 16;
+    t.pitch = t.TPW * 16 + pad;
+    c.part_bytes = ((t.TPH * t.pitch + 255) & ~255) + (getenv("BSP_SKEW") ? atoi(getenv("BSP_SKEW")) : 0);
+    patch_bytes = (int64_t)(t.slab / BSP_CHUNK) * c.part_bytes;
+  }
+  c.wbuf_off = (int32_t)((patch_bytes + 15) & ~15);
   c.obuf_off = c.wbuf_off + (int32_t)wbytes;
   const size_t ldsb = (size_t)c.obuf_off + (size_t)NT * kPH * 16 * out_row;
   if ((int64_t)ldsb > kLdsPerCu) return BSP_ERR_UNSUPPORTED;
@@ -593,11 +628,11 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
     c.s_part = kLoaderThreads % PP;
     const int s_py = spix / t.TPW;
     c.s_px = spix % t.TPW;
-    c.s_l = s_py * t.pitch + c.s_px * t.row_bytes + c.s_part * 16;
+    c.s_l = s_py * t.pitch + c.s_px * t.row_bytes + c.s_part * c.part_bytes;
     c.s_g = (s_py * t.gsh * p.J + c.s_px * t.gsw) * p.I + c.s_part * BSP_CHUNK;
     c.s_iy = s_py * t.gsh;
     c.s_ix = c.s_px * t.gsw;
-    c.cp_l = t.row_bytes - PP * 16;
+    c.cp_l = t.row_bytes - PP * c.part_bytes;
     c.cp_g = t.gsw * p.I - PP * BSP_CHUNK;
     c.cx_l = t.pitch - t.TPW * t.row_bytes;
     c.cx_g = (t.gsh * p.J - t.TPW * t.gsw) * p.I;
