@@ -589,15 +589,9 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
   if (t.TPH * t.gsh >= 1024 || t.TPW * t.gsw >= 1024 || t.slab / BSP_CHUNK > 32)
     return BSP_ERR_UNSUPPORTED;
   const int64_t ntiles = (int64_t)p.B * t.tiles_y * t.tiles_x;
+  const int movers = kLoaderThreads;  // threads that move the patch
   c.part_bytes = 16;
   int64_t patch_bytes = (int64_t)t.TPH * t.pitch;
-  if (const char* e = getenv("BSP_PLANAR")) {  // experiment: one plane per chunk index
-    const int pad = atoi(e);
-    t.row_bytes = 16;
-    t.pitch = t.TPW * 16 + pad;
-    c.part_bytes = ((t.TPH * t.pitch + 255) & ~255) + (getenv("BSP_SKEW") ? atoi(getenv("BSP_SKEW")) : 0);
-    patch_bytes = (int64_t)(t.slab / BSP_CHUNK) * c.part_bytes;
-  }
   c.wbuf_off = (int32_t)((patch_bytes + 15) & ~15);
   c.obuf_off = c.wbuf_off + (int32_t)wbytes;
   const size_t ldsb = (size_t)c.obuf_off + (size_t)NT * kPH * 16 * out_row;
@@ -609,7 +603,8 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
   c.wg_per_group = (int32_t)(ntiles < slots ? ntiles : slots);
   const int64_t nwg = (int64_t)c.wg_per_group * c.groups;
   const int64_t npieces = (int64_t)t.TPH * t.TPW * (t.slab / BSP_CHUNK);
-  if (nwg >= (1 << 24) || ntiles >= (1 << 24) || npieces > kLoaderThreads * kXBatch ||
+  if (nwg >= (1 << 24) || ntiles >= (1 << 24) ||
+      npieces > kLoaderThreads * kXBatch ||
       (npieces + kXBatch * kLoaderThreads) * t.TPW >= (1ll << 32) || (int64_t)p.L * p.J * p.I >= (1ll << 31))
     return BSP_ERR_UNSUPPORTED;
   t.spc = 4;
@@ -624,8 +619,8 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
   c.d_groups = make_fastdiv(c.groups);
   {
     const int PP = t.slab / BSP_CHUNK;
-    const int spix = kLoaderThreads / PP;  // pixels per step, then its rows and columns
-    c.s_part = kLoaderThreads % PP;
+    const int spix = movers / PP;  // pixels per step, then its rows and columns
+    c.s_part = movers % PP;
     const int s_py = spix / t.TPW;
     c.s_px = spix % t.TPW;
     c.s_l = s_py * t.pitch + c.s_px * t.row_bytes + c.s_part * c.part_bytes;
