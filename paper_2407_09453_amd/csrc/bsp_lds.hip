@@ -575,8 +575,9 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
       t.nslabs = ((p.I + 7) / 8 + t.slab / 8 - 1) / (t.slab / 8);
       t.nstrips = (p.O + BSP_STRIP - 1) / BSP_STRIP;
       // the LDS left after the weights holds the patch and the results staging tile
+      const int groups = (t.nstrips + 3) / 4;
       if (!bsp_choose_tile(p, t.slab, kLdsPerCu - wbytes, kLoaderThreads * kXBatch, kPH, out_row,
-                           2, &NT, &t))
+                           2, std::max(1, device_cus() / groups), &NT, &t))
         NT = 0;
       if (memo.size() > 4096) memo.clear();
       it = memo.emplace(key, std::make_pair(NT, t)).first;

@@ -73,6 +73,6 @@ __device__ __forceinline__ void do_mma(f32x4_t (&acc)[NT], const u32x4_t a,
 // The tile holds nt_scale * NT pixel tiles (nt_scale waves share a strip) and the LDS
 // budget also has to cover out_row_bytes per output pixel (results staging), if any.
 bool bsp_choose_tile(const ConvParams& p, int slab, int64_t max_lds, int max_pieces, int nt_scale,
-                     int out_row_bytes, int min_nt, int* NT, TileCfg* out);
+                     int out_row_bytes, int min_nt, int slots, int* NT, TileCfg* out);
 
 #endif

@@ -20,6 +20,8 @@
 #include "bsp_launch.h"
 #include "bsp_tile.h"
 
+#include <algorithm>
+
 #include <array>
 #include <map>
 #include <mutex>
@@ -271,7 +273,7 @@ int conflict_excess(const TileCfg& t, int NT) {
 }  // namespace
 
 bool bsp_choose_tile(const ConvParams& p, int slab, int64_t max_lds, int max_pieces, int nt_scale,
-                     int out_row_bytes, int min_nt, int* NT, TileCfg* out) {
+                     int out_row_bytes, int min_nt, int slots, int* NT, TileCfg* out) {
   const bool pointwise = p.H == 1 && p.K == 1;
   static const int nts[] = {2, 4, 7, 8};
   static const int tws[] = {4, 7, 8, 14, 16, 24, 28, 32, 56, 64, 112, 128, 224, 256};
@@ -323,7 +325,19 @@ bool bsp_choose_tile(const ConvParams& p, int slab, int64_t max_lds, int max_pie
         if (best_ex == (1 << 30)) continue;
         t.row_bytes = slab * 2 + brp;
         t.pitch = t.TPW * t.row_bytes + bpp;
-        const double util = (double)p.M * p.N / ((double)t.tiles_y * t.tiles_x * nt * 16);
+        double util = (double)p.M * p.N / ((double)t.tiles_y * t.tiles_x * nt * 16);
+        if (slots > 0) {
+          // persistent grid of `slots` workgroups per strip group: what counts is how many
+          // rounds of units the busiest workgroup runs and what a unit costs, a fixed part
+          // (barriers, writing the next unit into LDS; `fixed` 16-pixel tiles' worth of
+          // compute) plus its pixel tiles.  Small layers then get smaller tiles on more CUs.
+          const double steps = std::max(1.0, 0.75 * (slab / BSP_CHUNK) * (pointwise ? 1 : p.H * p.K) / 4.0);
+          const double fixed = 64.0 / steps;
+          const int64_t ntiles = (int64_t)p.B * t.tiles_y * t.tiles_x;
+          const int64_t rounds = (ntiles + slots - 1) / slots;
+          // (blended with the plain slot utilisation: the total work still costs bandwidth)
+          util = 0.7 * ((double)p.B * p.M * p.N / 16.0 / slots) / ((double)rounds * (fixed + nt)) + 0.3 * util;
+        }
         const double halo = (double)t.TPH * t.TPW / ((double)t.TH * t.TW * t.lsh * t.lsw);
         const double score = util - 0.02 * halo - 0.05 * best_ex / nt + 0.001 * nt;
         if (score > best) {
@@ -362,7 +376,7 @@ int bsp_launch_tile(const ConvParams& p_in, int dtype, hipStream_t st) {
       t.slab = bsp_slab_channels(p.I, p.H, p.K);
       t.nslabs = ((p.I + 7) / 8 + t.slab / 8 - 1) / (t.slab / 8);
       t.nstrips = (p.O + BSP_STRIP - 1) / BSP_STRIP;
-      if (!bsp_choose_tile(p, t.slab, 64 * 1024, 0, 1, 0, 4, &NT, &t)) NT = 0;
+      if (!bsp_choose_tile(p, t.slab, 64 * 1024, 0, 1, 0, 4, 0, &NT, &t)) NT = 0;
       if (memo.size() > 4096) memo.clear();
       it = memo.emplace(key, std::make_pair(NT, t)).first;
     }
