@@ -46,6 +46,7 @@ struct LdsCfg {
   int32_t wbuf_off;       // LDS offset of the weight regions (after the patch)
   int32_t region_bytes;   // per strip: maxsteps fragments + maxsteps offset quads
   int32_t obuf_off;       // LDS offset of the results staging tile
+  int32_t sp_off;         // LDS offset of the step-range table [4][nslabs + 1]
   int32_t maxsteps;       // most steps any (strip, slab) has
   int32_t nsteps;         // steps in the whole plan
   int32_t mover_first;    // raise the data movers' wave priority
@@ -370,6 +371,11 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
                                      ((dsc >> 24) & 0xFF) * t.row_bytes + (dsc & 0xFFFF) * c.part_bytes;
   };
 
+  // the strip's step ranges go to LDS once: later slabs then cost an LDS read, not a trip
+  // to global memory in front of the step loop
+  int* sp = (int*)(lds + c.sp_off) + wave * nsl1;
+  if (RELOAD && half == 0)
+    for (int k = lane; k < nsl1; k += 64) sp[k] = valid ? slab_ptr[k] : 0;
   int s_lo = valid ? slab_ptr[0] : 0, s_hi = valid ? slab_ptr[1] : 0;  // steps of the current slab
   issue_weights(s_lo, s_hi);
 
@@ -415,8 +421,8 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
     const bool more = advance(tile, sl, &ntile, &nsl);
     const int nst = s_hi - s_lo;
     if (reload_w && more) {  // next slab's fragments: in flight while this one is computed
-      s_lo = valid ? slab_ptr[nsl] : 0;
-      s_hi = valid ? slab_ptr[nsl + 1] : 0;
+      s_lo = sp[nsl];
+      s_hi = sp[nsl + 1];
       issue_weights(s_lo, s_hi);
     }
     // this slab's steps, everything from LDS and D - 1 steps ahead of the MFMAs (offsets one
@@ -576,7 +582,7 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
       t.nstrips = (p.O + BSP_STRIP - 1) / BSP_STRIP;
       // the LDS left after the weights holds the patch and the results staging tile
       const int groups = (t.nstrips + 3) / 4;
-      if (!bsp_choose_tile(p, t.slab, kLdsPerCu - wbytes, kLoaderThreads * kXBatch, kPH, out_row,
+      if (!bsp_choose_tile(p, t.slab, kLdsPerCu - wbytes - 4 * (kMaxSlabs + 1) * 4, kLoaderThreads * kXBatch, kPH, out_row,
                            2, std::max(1, device_cus() / groups), &NT, &t))
         NT = 0;
       if (memo.size() > 4096) memo.clear();
@@ -595,7 +601,8 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
   int64_t patch_bytes = (int64_t)t.TPH * t.pitch;
   c.wbuf_off = (int32_t)((patch_bytes + 15) & ~15);
   c.obuf_off = c.wbuf_off + (int32_t)wbytes;
-  const size_t ldsb = (size_t)c.obuf_off + (size_t)NT * kPH * 16 * out_row;
+  c.sp_off = c.obuf_off + NT * kPH * 16 * out_row;
+  const size_t ldsb = (size_t)c.sp_off + 4 * (kMaxSlabs + 1) * 4;
   if ((int64_t)ldsb > kLdsPerCu) return BSP_ERR_UNSUPPORTED;
   c.groups = (t.nstrips + 3) / 4;
   // persistent grid: one workgroup per CU, shared out among the strip groups
