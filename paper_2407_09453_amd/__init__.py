@@ -8,6 +8,9 @@ from .binding import (  # noqa: F401
     BSP_BF16,
     BSP_F32,
     BSP_I8,
+    BSP_IMPORTANCE_L1,
+    BSP_IMPORTANCE_L2,
+    BSP_IMPORTANCE_VAR,
     BSP_I32,
     BspError,
     BspLayer,
