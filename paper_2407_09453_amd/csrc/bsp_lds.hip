@@ -297,7 +297,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
       if (!I8 && (p.residual || p.relu))
         batch(std::integral_constant<int, 2>{}, std::true_type{});
       else
-        batch(std::integral_constant<int, 4>{}, std::false_type{});
+        batch(std::integral_constant<int, (NT >= 8 ? 4 : NF)>{}, std::false_type{});
     };
 
     int sl = 0;
@@ -316,10 +316,13 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
     __syncthreads();  // A: first unit is in LDS
     int flush_tile = -1;
     while (true) {
-      if (flush_tile >= 0) flush(flush_tile);  // while the compute waves work on (tile, sl)
       int ntile, nsl;
       const bool more = advance(tile, sl, &ntile, &nsl);
       if (more) issue_patch(ntile, nsl);  // lands in registers during the compute phase
+      // the previous tile's results, while the compute waves work on (tile, sl).  After the
+      // loads: a store's data registers may not be touched until the store has completed,
+      // so anything issued behind the stores would first wait for them.
+      if (flush_tile >= 0) flush(flush_tile);
       flush_tile = sl == t.nslabs - 1 ? tile : -1;
       // E (single-slab layers): the compute waves are done with the patch and go on to stage
       // their results, so the next patch can go in at once and B is not needed;
