@@ -48,6 +48,7 @@ struct LdsCfg {
   int32_t obuf_off;       // LDS offset of the results staging tile
   int32_t sp_off;         // LDS offset of the step-range table [4][nslabs + 1]
   int32_t maxsteps;       // most steps any (strip, slab) has
+  int32_t wload;          // steps of a slab each of a strip's waves stages: ceil(maxsteps / kPH)
   int32_t nsteps;         // steps in the whole plan
   int32_t mover_first;    // raise the data movers' wave priority
   int32_t shift;          // int8 results: rounding right shift of the 32-bit sums
@@ -358,19 +359,25 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
   // All kWHalf loads are always issued, in one straight line so that they are in flight
   // together; those past the wave's share repeat its last fragment and are dropped.
   auto issue_weights = [&](int s0, int s1) {
-    w_n = max(0, min(s1 - s0 - half * kWHalf, kWHalf));
-    const int f = s0 + half * kWHalf;
+    w_n = max(0, min(s1 - s0 - half * c.wload, c.wload));
+    const int f = s0 + half * c.wload;
     const int last = min(max(f + w_n, s0 + 1), c.nsteps) - 1;  // a fragment that exists
+    // (no more loads than any strip of the layer can need: c.wload, the same for every wave
+    // and unit, so the loads still leave in one straight line)
 #pragma unroll
-    for (int u = 0; u < kWHalf; ++u) wv[u] = wfrag[(int64_t)min(f + u, last) * 64 + lane];
+    for (int u = 0; u < kWHalf; ++u) {
+      u32x4_t v = u32x4_t{0u, 0u, 0u, 0u};
+      if (u < c.wload) v = wfrag[(int64_t)min(f + u, last) * 64 + lane];
+      wv[u] = v;
+    }
     if (lane < w_n * 4) dsc = xdesc[f * 4 + lane];
   };
   auto commit_weights = [&]() {
 #pragma unroll
     for (int u = 0; u < kWHalf; ++u)
-      if (u < w_n) wl[(half * kWHalf + u) * 64 + lane] = wv[u];
+      if (u < w_n) wl[(half * c.wload + u) * 64 + lane] = wv[u];
     if (lane < w_n * 4)
-      xo[half * kWHalf * 4 + lane] = ((dsc >> 16) & 0xFF) * t.pitch +
+      xo[half * c.wload * 4 + lane] = ((dsc >> 16) & 0xFF) * t.pitch +
                                      ((dsc >> 24) & 0xFF) * t.row_bytes + (dsc & 0xFFFF) * c.part_bytes;
   };
 
@@ -567,6 +574,7 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
   // a compute wave stages half the steps of a slab of its strip, one descriptor per lane
   if (c.maxsteps < 1 || c.maxsteps > kWHalf * kPH || c.maxsteps > 32 || nslabs > kMaxSlabs)
     return BSP_ERR_UNSUPPORTED;
+  c.wload = (c.maxsteps + kPH - 1) / kPH;  // each of a strip's waves stages this many steps
   c.region_bytes = c.maxsteps * (1024 + 16);
   const int64_t wbytes = 4ll * c.region_bytes;
 
