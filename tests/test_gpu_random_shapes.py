@@ -64,3 +64,42 @@ def test_random_shapes_int8():
         want = oracle.conv2d_i8(X, W, bias, gamma, bo, bi, s, p)
         assert (Y32.cpu().numpy().astype(np.int64) == want).all(), n
         assert (Y8.cpu().numpy() == oracle.requant_shift(want, shift)).all(), (n, shift)
+
+
+def _tiled_shapes(seed, count):
+    """Shapes with whole 16-channel chunks and more pixels: these land in the LDS-resident
+    kernels (bf16 and int8), with several tiles, slabs and strip groups."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        H, K = [(1, 1), (3, 3), (3, 3), (1, 7), (7, 1), (3, 1)][int(rng.integers(0, 6))]
+        s = int(rng.integers(1, 3))
+        p = (H // 2, K // 2) if rng.random() < 0.7 else (0, 0)
+        L, J = int(rng.integers(max(8, H), 44)), int(rng.integers(max(8, K), 44))
+        B = int(rng.integers(1, 4))
+        I = int(rng.choice([16, 32, 64, 128, 192, 256]))
+        O = int(rng.choice([16, 32, 64, 128, 192]))
+        if B * L * J * I * H * K * O > 1.5e9 or I * H * K > 4608:
+            continue
+        bo, bi = GRANS[int(rng.integers(0, 3))]
+        out.append((B, L, J, I, O, H, K, (s, s), p, bo, bi))
+    return out
+
+
+def test_random_tiled_shapes_bf16_and_int8():
+    import torch
+    rng = np.random.default_rng(6)
+    for n, (B, L, J, I, O, H, K, s, p, bo, bi) in enumerate(_tiled_shapes(79, 24)):
+        print("case", n, (B, L, J, I, O, H, K, s, p, bo, bi), flush=True)
+        c = draw_layer("t", B=B, L=L, J=J, I=I, O=O, H=H, K=K, stride=s, pad=p, bo=bo, bi=bi,
+                       dtype="bf16", mask_kind="exact", density=0.5, seed=7000 + n, b_std=0.5)
+        assert_close(gpu_conv(c), oracle_conv(c), "bf16", f"tiled shape {n}")
+        X = rng.integers(-128, 128, (B, L, J, I), dtype=np.int8)
+        W = rng.integers(-128, 128, (O, H, K, I), dtype=np.int8)
+        bias = rng.integers(-2 ** 16, 2 ** 16, O).astype(np.int32)
+        layer = bsp.BspLayerI8(W, c.gamma, bo, bi, bias=bias)
+        shift = int(rng.integers(4, 14))
+        Y8 = layer.conv2d(torch.from_numpy(X).cuda(), s, p, shift=shift)
+        torch.cuda.synchronize()
+        want = oracle.conv2d_i8(X, W, bias, c.gamma, bo, bi, s, p, shift=shift)
+        assert (Y8.cpu().numpy() == want).all(), (n, shift)
