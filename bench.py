@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
 # HBM bytes per launch of the dispatcher's kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this script, each scaled by the same counter's reading for a device copy of known
 # size (summary: profiles/conv_lds_bf16_c1_counters.md)
-MEASURED_TRAFFIC_BYTES = {"c1": 29_666_005}
+MEASURED_TRAFFIC_BYTES = {"c1": 29_681_518}
 
 
 def algorithmic_bytes(c, nnzb: int) -> int:
