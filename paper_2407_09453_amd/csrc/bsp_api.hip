@@ -52,6 +52,8 @@ int prepare(const bsp_weights* w, const void* X, const float* bias, void* Y, int
   p.bias = bias;
   p.payload = w->payload;
   p.plan = (const int32_t*)w->plan;
+  p.row_ptr = w->row_ptr;
+  p.col_idx = w->col_idx;
   p.B = B;
   p.L = L;
   p.J = J;
@@ -82,6 +84,8 @@ int dispatch(const bsp_weights* w, const ConvParams& p, void* stream) {
     // each launcher declines (UNSUPPORTED, nothing launched) what lies outside its limits
     const bool chunked = bsp_tile_supported(p, w->dtype);  // whole 8-channel chunks
     int rc = BSP_ERR_UNSUPPORTED;
+    if (chunked) rc = bsp_launch_fc_rows(p, w->dtype, w->bo, w->bi, w->nnzb, (hipStream_t)stream);
+    if (rc != BSP_ERR_UNSUPPORTED) return rc;
     if (chunked) rc = bsp_launch_fc_stream(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
     if (kernel_limit() >= 2) rc = bsp_launch_lds(p, w->dtype, w->plan_host, (hipStream_t)stream);

@@ -23,6 +23,8 @@ struct ConvParams {
   const float* bias;
   const void* payload;
   const int32_t* plan;
+  const int32_t* row_ptr;  // the compressed block rows themselves (for kernels that stream them)
+  const int32_t* col_idx;
   int32_t B, L, J, I, O, H, K, M, N;
   int32_t sh, sw, ph, pw;
   int32_t P;  // B*M*N output pixels

@@ -207,3 +207,25 @@ def test_empty_batch_is_a_no_op():
     Y = layer.conv2d(X, c.stride, c.pad, out=Yb[:0])
     torch.cuda.synchronize()
     assert Y.shape[0] == 0 and bool((Yb == -7.0).all())
+
+
+@pytest.mark.parametrize("B,I,O,d", [(16, 512, 1024, 0.5), (33, 264, 1032, 0.3), (64, 128, 2048, 0.55),
+                                     (5, 1024, 1030, 0.1), (1, 64, 1024, 0.5)])
+def test_fc_block_row_streaming_kernel(B, I, O, d):
+    """Sparse FC layers with many block rows take the kernel that streams the compressed
+    block rows; fused epilogue included."""
+    import torch
+    c = draw_layer("fcrows", B=B, L=1, J=1, I=I, O=O, H=1, K=1, stride=1, pad=0, bo=8, bi=8,
+                   dtype="bf16", mask_kind="exact", density=d, seed=B * 7 + O, b_std=0.5)
+    c.gamma = c.gamma.copy()
+    c.gamma[3, :] = 0                                   # an empty block row: bias only
+    layer = make_layer(c)
+    X = to_device(c).reshape(B, I)
+    Y = layer.fc(X)
+    torch.cuda.synchronize()
+    ref = oracle.fc(c.X.reshape(B, I), c.W.reshape(O, I), c.bias, c.gamma, 8, 8)
+    assert_close(to_host(Y), ref, "bf16", f"fc rows {B}x{I}->{O}")
+    R = torch.randn(B, O, device="cuda").to(torch.bfloat16)
+    Yf = layer.fc(X, residual=R, relu=True)
+    torch.cuda.synchronize()
+    assert torch.equal(Yf, torch.relu(Y.float() + R.float()).to(torch.bfloat16))
