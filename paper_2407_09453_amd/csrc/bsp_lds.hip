@@ -37,6 +37,7 @@ constexpr int kLoaderWaves = 4;     // one per strip of the group
 constexpr int kLoaderThreads = 64 * kLoaderWaves;
 constexpr int kThreads = kComputeThreads + kLoaderThreads;
 constexpr int kXBatch = 11;         // 16-byte patch pieces a loader thread keeps in flight
+constexpr int kXBatchFlat = 14;     // the same for flattened pointwise layers (no address maps to keep)
 constexpr int kWHalf = 10;         // weight fragments a loader lane keeps in flight (one slab of a strip)
 constexpr int kMaxSlabs = 32;
 constexpr int kOutRow = 4 * BSP_STRIP * 2 + 16;  // bytes per pixel in the results staging tile
@@ -48,6 +49,7 @@ struct LdsCfg {
   int32_t obuf_off;       // LDS offset of the results staging tile
   int32_t sp_off;         // LDS offset of the step-range table [4][nslabs + 1]
   int32_t maxsteps;       // most steps any (strip, slab) has
+  int32_t lgpp;           // flattened pointwise layers: log2 of the 16-byte pieces per pixel
   int32_t wload;          // steps of a slab each of a strip's waves stages: ceil(maxsteps / kPH)
   int32_t nsteps;         // steps in the whole plan
   int32_t mover_first;    // raise the data movers' wave priority
@@ -105,7 +107,7 @@ __device__ __forceinline__ void tile_pos(const TileCfg& t, int gt, int j, int* t
 // KIND: what a 16-byte chunk of a pixel holds.
 enum { kBf16 = 0, kBf16Narrow = 1, kInt8 = 2 };
 
-template <int NT, int KIND, bool RELOAD>
+template <int NT, int KIND, bool RELOAD, bool FLAT>
 __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t, LdsCfg c) {
   constexpr bool NARROW = KIND == kBf16Narrow;
   // int8 codes: a chunk is sixteen channels, the MFMA is i32 16x16x64, sums are exact 32-bit
@@ -158,7 +160,11 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
     // piece and advanced by the uniform step with two carries for the others.
     const int PP = t.slab / BSP_CHUNK;
     const int npieces = t.TPH * t.TPW * PP;
-    int xg[kXBatch], xl[kXBatch], xq[kXBatch];
+    // FLAT: a pointwise layer whose pixels were flattened into one row with a power-of-two
+    // number of pieces per pixel; piece -> (pixel, part) is then a shift and a mask, no maps
+    // are kept and the registers go to a longer batch (larger tiles)
+    constexpr int XB = FLAT ? kXBatchFlat : kXBatch;
+    int xg[FLAT ? 1 : kXBatch], xl[FLAT ? 1 : kXBatch], xq[FLAT ? 1 : kXBatch];
     // the results staging tile: piece q = ltid + 256 k is channels 8 (q & 7).. of pixel q >> 3
     // (filled in once the first unit's loads are on their way)
     constexpr int PPP = I8 ? 4 : 8;          // 16-byte pieces per staged pixel
@@ -167,7 +173,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
     const int fpart = ltid % PPP, fpix = ltid / PPP;
     int fpos[NF], foff[NF];
 
-    u32x4_t xv[kXBatch];
+    u32x4_t xv[XB];
     // X + origin of the patch may point before the image (padding); only in-image pieces are read
     struct Origin {
       const uint16_t* org;
@@ -186,6 +192,13 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
     };
     auto load_piece = [&](int u, const Origin& o) {
       xv[u] = u32x4_t{0u, 0u, 0u, 0u};
+      if constexpr (FLAT) {
+        const int i = ltid + u * kLoaderThreads;
+        const int pix = i >> c.lgpp, part = i & (PP - 1);
+        if (i < npieces && o.ix + pix < p.J && o.ch0 + part * BSP_CHUNK < p.I)
+          xv[u] = *(const u32x4_t*)(o.org + (int64_t)pix * p.I + part * BSP_CHUNK);
+        return;
+      }
       const int q = xq[u];
       if (xg[u] >= 0 && (unsigned)(o.iy + ((q >> 10) & 1023)) < (unsigned)p.L &&
           (unsigned)(o.ix + (q & 1023)) < (unsigned)p.J && o.ch0 + (q >> 20) * BSP_CHUNK < p.I) {
@@ -204,6 +217,11 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
     // first unit: build the maps piece by piece, each piece's load leaving right away
     auto first_patch = [&](int tl) {
       const Origin o = origin(tl, 0);
+      if constexpr (FLAT) {
+#pragma unroll
+        for (int u = 0; u < XB; ++u) load_piece(u, o);
+        return;
+      }
       const int pix = (int)fdiv((uint32_t)ltid, t.d_pp);
       int part = ltid - pix * PP;
       const int py0 = (int)fdiv((uint32_t)pix, t.d_tpw);
@@ -226,9 +244,18 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
     auto issue_patch = [&](int tl, int sl) {
       const Origin o = origin(tl, sl);
 #pragma unroll
-      for (int u = 0; u < kXBatch; ++u) load_piece(u, o);
+      for (int u = 0; u < XB; ++u) load_piece(u, o);
     };
     auto commit_patch = [&]() {
+      if constexpr (FLAT) {
+#pragma unroll
+        for (int u = 0; u < XB; ++u) {
+          const int i = ltid + u * kLoaderThreads;
+          if (i < npieces)
+            *(u32x4_t*)(lds + (i >> c.lgpp) * t.row_bytes + (i & (PP - 1)) * c.part_bytes) = xv[u];
+        }
+        return;
+      }
 #pragma unroll
       for (int u = 0; u < kXBatch; ++u)
         if (xg[u] >= 0) *(u32x4_t*)(lds + xl[u]) = xv[u];
@@ -514,18 +541,18 @@ int device_cus() {
 
 constexpr int64_t kLdsPerCu = 160 * 1024;
 
-template <int NT, int KIND, bool RELOAD>
+template <int NT, int KIND, bool RELOAD, bool FLAT>
 int launch_one(const ConvParams& p, const TileCfg& t, const LdsCfg& c, dim3 grid, size_t ldsb,
                hipStream_t st) {
   static bool raised = false;  // dynamic LDS above 64 KB has to be allowed once per kernel
   if (!raised) {
-    if (hipFuncSetAttribute((const void*)conv_lds<NT, KIND, RELOAD>,
+    if (hipFuncSetAttribute((const void*)conv_lds<NT, KIND, RELOAD, FLAT>,
                             hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)kLdsPerCu) != hipSuccess)
       return BSP_ERR_HIP;
     raised = true;
   }
-  hipLaunchKernelGGL((conv_lds<NT, KIND, RELOAD>), grid, dim3(kThreads), ldsb, st, p, t, c);
+  hipLaunchKernelGGL((conv_lds<NT, KIND, RELOAD, FLAT>), grid, dim3(kThreads), ldsb, st, p, t, c);
   return hipGetLastError() == hipSuccess ? BSP_OK : BSP_ERR_HIP;
 }
 
@@ -533,10 +560,15 @@ template <int NT, int KIND>
 int launch(const ConvParams& p, const TileCfg& t, const LdsCfg& c, dim3 grid, size_t ldsb,
            hipStream_t st) {
   if constexpr (KIND == kBf16Narrow) {  // first layers have one slab
-    return launch_one<NT, KIND, false>(p, t, c, grid, ldsb, st);
+    return launch_one<NT, KIND, false, false>(p, t, c, grid, ldsb, st);
   } else {
-    return t.nslabs > 1 ? launch_one<NT, KIND, true>(p, t, c, grid, ldsb, st)
-                        : launch_one<NT, KIND, false>(p, t, c, grid, ldsb, st);
+    if constexpr (NT <= 4) {  // flattened pointwise layers take the small tile counts
+      if (c.lgpp >= 0)
+        return t.nslabs > 1 ? launch_one<NT, KIND, true, true>(p, t, c, grid, ldsb, st)
+                            : launch_one<NT, KIND, false, true>(p, t, c, grid, ldsb, st);
+    }
+    return t.nslabs > 1 ? launch_one<NT, KIND, true, false>(p, t, c, grid, ldsb, st)
+                        : launch_one<NT, KIND, false, false>(p, t, c, grid, ldsb, st);
   }
 }
 
@@ -560,6 +592,7 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
       hdr[BSP_PLAN_K_W] != p_in.K || hdr[BSP_PLAN_DTYPE_W] != dtype)
     return BSP_ERR_UNSUPPORTED;
   ConvParams p = p_in;
+  bool flattened = false;
   const int plan_slab = i8 ? hdr[BSP_PLAN_SLAB_W] / 2 : hdr[BSP_PLAN_SLAB_W];
   if (i8) p.I /= 2;  // from here on an input element is a pair of codes (2 bytes, like a bf16)
   const int out_row = i8 ? kOutRowI8 : kOutRow;
@@ -567,6 +600,7 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
     p.J = p.N = p.P;
     p.L = p.M = 1;
     p.B = 1;
+    flattened = true;
   }
   LdsCfg c;
   c.maxsteps = hdr[BSP_PLAN_MAXSLABSTEPS_W];
@@ -578,6 +612,15 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
   c.region_bytes = c.maxsteps * (1024 + 16);
   const int64_t wbytes = 4ll * c.region_bytes;
 
+  // flattened pointwise layers with a power-of-two number of pieces per pixel: the movers keep
+  // no maps and move longer batches, so the tiles can be larger
+  int lgpp = -1;
+  if (flattened) {
+    const int pp = bsp_slab_channels(p.I, p.H, p.K) / BSP_CHUNK;
+    if ((pp & (pp - 1)) == 0)
+      for (lgpp = 0; (1 << lgpp) < pp; ++lgpp) {}
+  }
+  const int max_pieces = kLoaderThreads * (lgpp >= 0 ? kXBatchFlat : kXBatch);
   TileCfg t;
   int NT = 0;
   {
@@ -593,8 +636,12 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
       t.nstrips = (p.O + BSP_STRIP - 1) / BSP_STRIP;
       // the LDS left after the weights holds the patch and the results staging tile
       const int groups = (t.nstrips + 3) / 4;
-      if (!bsp_choose_tile(p, t.slab, kLdsPerCu - wbytes - 4 * (kMaxSlabs + 1) * 4, kLoaderThreads * kXBatch, kPH, out_row,
-                           2, std::max(1, device_cus() / groups), &NT, &t))
+      const int64_t room = kLdsPerCu - wbytes - 4 * (kMaxSlabs + 1) * 4;
+      const int slots = std::max(1, device_cus() / groups);
+      if (!bsp_choose_tile(p, t.slab, room, max_pieces, kPH, out_row, 2, slots, &NT, &t)) NT = 0;
+      // the long batches exist for the small tile counts only
+      if (NT > 4 && (int64_t)t.TPH * t.TPW * (t.slab / BSP_CHUNK) > kLoaderThreads * kXBatch &&
+          !bsp_choose_tile(p, t.slab, room, kLoaderThreads * kXBatch, kPH, out_row, 2, slots, &NT, &t))
         NT = 0;
       if (memo.size() > 4096) memo.clear();
       it = memo.emplace(key, std::make_pair(NT, t)).first;
@@ -623,8 +670,8 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
   const int64_t nwg = (int64_t)c.wg_per_group * c.groups;
   const int64_t npieces = (int64_t)t.TPH * t.TPW * (t.slab / BSP_CHUNK);
   if (nwg >= (1 << 24) || ntiles >= (1 << 24) ||
-      npieces > kLoaderThreads * kXBatch ||
-      (npieces + kXBatch * kLoaderThreads) * t.TPW >= (1ll << 32) || (int64_t)p.L * p.J * p.I >= (1ll << 31))
+      npieces > max_pieces ||
+      (npieces + kXBatchFlat * kLoaderThreads) * t.TPW >= (1ll << 32) || (int64_t)p.L * p.J * p.I >= (1ll << 31))
     return BSP_ERR_UNSUPPORTED;
   t.spc = 4;
   t.ntiles = (int32_t)ntiles;
@@ -656,6 +703,7 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
   // instructions then only take issue slots from the matrix cores
   c.mover_first = !(p.H * p.K > 1 && nslabs > 1);
   c.shift = shift;
+  c.lgpp = (lgpp >= 0 && NT <= 4) ? lgpp : -1;
   c.nsteps = hdr[BSP_PLAN_NSTEPS_W];
   c.off_slab = hdr[BSP_PLAN_OFF_SLAB_W];
   c.off_xdesc = hdr[BSP_PLAN_OFF_XDESC_W];
