@@ -49,7 +49,7 @@ struct LdsCfg {
   int32_t obuf_off;       // LDS offset of the results staging tile
   int32_t sp_off;         // LDS offset of the step-range table [4][nslabs + 1]
   int32_t maxsteps;       // most steps any (strip, slab) has
-  int32_t lgpp;           // flattened pointwise layers: log2 of the 16-byte pieces per pixel
+  int32_t lgpp;           // >= 0: a flattened pointwise layer (movers without maps)
   int32_t wload;          // steps of a slab each of a strip's waves stages: ceil(maxsteps / kPH)
   int32_t nsteps;         // steps in the whole plan
   int32_t mover_first;    // raise the data movers' wave priority
@@ -160,9 +160,9 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
     // piece and advanced by the uniform step with two carries for the others.
     const int PP = t.slab / BSP_CHUNK;
     const int npieces = t.TPH * t.TPW * PP;
-    // FLAT: a pointwise layer whose pixels were flattened into one row with a power-of-two
-    // number of pieces per pixel; piece -> (pixel, part) is then a shift and a mask, no maps
-    // are kept and the registers go to a longer batch (larger tiles)
+    // FLAT: a pointwise layer whose pixels were flattened into one row; piece -> (pixel, part)
+    // is then one division by a constant, no maps are kept and the registers go to a longer
+    // batch (larger tiles)
     constexpr int XB = FLAT ? kXBatchFlat : kXBatch;
     int xg[FLAT ? 1 : kXBatch], xl[FLAT ? 1 : kXBatch], xq[FLAT ? 1 : kXBatch];
     // the results staging tile: piece q = ltid + 256 k is channels 8 (q & 7).. of pixel q >> 3
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
       xv[u] = u32x4_t{0u, 0u, 0u, 0u};
       if constexpr (FLAT) {
         const int i = ltid + u * kLoaderThreads;
-        const int pix = i >> c.lgpp, part = i & (PP - 1);
+        const int pix = (int)fdiv((uint32_t)i, t.d_pp), part = i - pix * PP;
         if (i < npieces && o.ix + pix < p.J && o.ch0 + part * BSP_CHUNK < p.I)
           xv[u] = *(const u32x4_t*)(o.org + (int64_t)pix * p.I + part * BSP_CHUNK);
         return;
@@ -251,8 +251,8 @@ __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t,
 #pragma unroll
         for (int u = 0; u < XB; ++u) {
           const int i = ltid + u * kLoaderThreads;
-          if (i < npieces)
-            *(u32x4_t*)(lds + (i >> c.lgpp) * t.row_bytes + (i & (PP - 1)) * c.part_bytes) = xv[u];
+          const int pix = (int)fdiv((uint32_t)i, t.d_pp);
+          if (i < npieces) *(u32x4_t*)(lds + pix * t.row_bytes + (i - pix * PP) * c.part_bytes) = xv[u];
         }
         return;
       }
@@ -612,14 +612,9 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
   c.region_bytes = c.maxsteps * (1024 + 16);
   const int64_t wbytes = 4ll * c.region_bytes;
 
-  // flattened pointwise layers with a power-of-two number of pieces per pixel: the movers keep
-  // no maps and move longer batches, so the tiles can be larger
-  int lgpp = -1;
-  if (flattened) {
-    const int pp = bsp_slab_channels(p.I, p.H, p.K) / BSP_CHUNK;
-    if ((pp & (pp - 1)) == 0)
-      for (lgpp = 0; (1 << lgpp) < pp; ++lgpp) {}
-  }
+  // flattened pointwise layers: the movers keep no maps and move longer batches, so the tiles
+  // can be larger
+  const int lgpp = flattened ? 0 : -1;
   const int max_pieces = kLoaderThreads * (lgpp >= 0 ? kXBatchFlat : kXBatch);
   TileCfg t;
   int NT = 0;
