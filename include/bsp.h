@@ -60,7 +60,7 @@ int bsp_version(void);
 
 /* ------------------------------------------------------------------ host side
  * The packer: Gamma + dense W -> block-compressed weights.  Paper Section II
- * ("the zeros are shuffled in ... we shall compact the blocks"), Section III
+ * (the kept blocks are compacted, the zeroed ones dropped), Section III
  * (compressed block row / index storage of Gamma) and Section V-B (weights are
  * compressed so that every move is a whole number of blocks, dense or sparse
  * alike).  All pointers are HOST memory.
@@ -136,8 +136,10 @@ typedef struct bsp_weights {
   int32_t dtype;            /* element type of payload, X and Y: BSP_F32 or BSP_BF16 */
   int32_t reserved;         /* set to 0 */
   int64_t nnzb;             /* kept blocks */
-  const int32_t* row_ptr;   /* device, may be null (not read by the kernels) */
-  const int32_t* col_idx;   /* device, may be null (not read by the kernels) */
+  const int32_t* row_ptr;   /* device copies of bsp_pack's arrays that match `payload`, or both */
+  const int32_t* col_idx;   /* null.  The kernel that streams compressed block rows (FC layers
+                               with 8x8 blocks) reads them on the device when they are given;
+                               with null pointers it is not used. */
   const void* payload;      /* device [nnzb][bo][H][K][bi] */
   const void* plan;         /* device copy of bsp_plan_build's output */
   int64_t plan_bytes;
@@ -258,9 +260,9 @@ int bsp_mask_step(const float* W, int32_t O, int32_t H, int32_t K, int32_t I,
                   uint8_t* gamma, int32_t* zeroed);
 
 /* ------------------------------------------------------------- 8-bit integers
- * The paper deploys 8-bit integer layers (Section I: "we quantize to 8-bit integer
- * computations"; Section III: weights 8 bits, bias 32 bits; Section V: INT8 tensors
- * with power-of-two scales).
+ * The paper deploys 8-bit integer layers (Section I: the sparse model is quantized to
+ * 8-bit integer arithmetic; Section III: weights 8 bits, bias 32 bits; Section V, Eq. (8):
+ * INT8 tensors with power-of-two scales).
  */
 
 /* Host.  Round-to-nearest quantizer of Section V, Eq. (8):

@@ -115,9 +115,10 @@ def draw_layer(name: str, *, B: int, L: int, J: int, I: int, O: int,
     """Draw X ~ N(0, x_std), W ~ N(0, w_std), bias ~ N(0, b_std) and a mask.
 
     ``w_std=None`` uses sqrt(2/(I*H*K)) so a chain of layers keeps O(1)
-    activations.  ``draw_x=False`` still consumes X's stream position (so W,
-    bias and the mask do not depend on whether X was wanted) but returns an
-    empty X; callers chaining layers supply their own activations.
+    activations.  ``draw_x=False`` draws X's values all the same, in pieces
+    that are thrown away, so that W, bias and the mask are exactly those of
+    ``draw_x=True`` for the same seed; it returns an empty X, and callers
+    supply their own activations.
     """
     if dtype not in ("f32", "bf16"):
         raise ValueError(dtype)
@@ -131,7 +132,11 @@ def draw_layer(name: str, *, B: int, L: int, J: int, I: int, O: int,
     if draw_x:
         X = rng.standard_normal((B, L, J, I), dtype=np.float32) * np.float32(x_std)
     else:
-        rng.standard_normal(1, dtype=np.float32)
+        left = B * L * J * I        # the generator fills element by element: pieces = whole
+        while left > 0:
+            n = min(left, 1 << 22)
+            rng.standard_normal(n, dtype=np.float32)
+            left -= n
         X = np.zeros((0, L, J, I), dtype=np.float32)
     W = rng.standard_normal((O, H, K, I), dtype=np.float32) * np.float32(w_std)
     bias = rng.standard_normal((O,), dtype=np.float32) * np.float32(b_std)

@@ -106,18 +106,73 @@ def test_integer_fc_against_int64_einsum_with_extreme_codes():
     assert (z == bias.astype(np.int64)[None, :]).all()
 
 
-def test_planted_mistakes_are_caught():
-    """A tie rule, a clip or a rounding offset changed by one step must fail a pin above."""
-    W = np.array([0.64, -0.64, 0.0125], dtype=np.float64)
-    delta = 0.64 / 128.0
-    half_away = np.sign(W) * np.floor(np.abs(W) / delta + 0.5)           # ties away from zero
-    assert half_away.tolist() != [128.0, -128.0, 2.0]                    # 2.5 -> 3: differs
-    no_clip = np.rint(W / delta)
-    assert no_clip[0] == 128.0                                           # would overflow int8
-    truncating = np.array([8, -8, 24, -24]) >> 4                         # shift without rounding
-    assert truncating.tolist() != [1, 0, 2, -1]
-    ties_away = [int(np.sign(v) * ((abs(v) + 8) // 16)) for v in (8, -8, 24, -24)]
-    assert ties_away != [1, 0, 2, -1]
+def _quantizer_with(bug):
+    """Eq. (8) again with one planted mistake (None: the definition itself)."""
+    def quantize(W, bits=8):
+        W = np.asarray(W, dtype=np.float64)
+        top = float(np.max(np.abs(W))) if W.size else 0.0
+        if top == 0.0:
+            return np.zeros(W.shape, dtype=np.int8), 0.0
+        levels = 2 ** bits if bug == "delta_2N" else 2 ** (bits - 1)
+        delta = top / float(levels)
+        r = W / delta
+        if bug == "ties_away":
+            q = np.sign(r) * np.floor(np.abs(r) + 0.5)
+        elif bug == "truncate":
+            q = np.trunc(r)
+        else:
+            q = np.rint(r)
+        if bug == "no_clip":
+            q = ((q + 128) % 256) - 128                    # what a bare narrowing cast does
+        elif bug == "symmetric_clip":
+            q = np.clip(q, -(2 ** (bits - 1)) + 1, 2 ** (bits - 1) - 1)
+        else:
+            q = np.clip(q, -(2 ** (bits - 1)), 2 ** (bits - 1) - 1)
+        return q.astype(np.int8), delta
+    return quantize
+
+
+def _shift_with(bug):
+    def requant(acc, shift):
+        acc = np.asarray(acc, dtype=np.int64)
+        if shift == 0:
+            y = acc
+        elif bug == "shift_truncates":
+            y = acc >> shift
+        elif bug == "shift_ties_away":
+            y = np.sign(acc) * ((np.abs(acc) + (1 << (shift - 1))) >> shift)
+        else:
+            y = (acc + (1 << (shift - 1))) >> shift
+        if bug == "shift_no_saturation":
+            return (((y + 128) % 256) - 128).astype(np.int8)
+        return np.clip(y, -128, 127).astype(np.int8)
+    return requant
+
+
+def _run_pins(quantize, requant, monkeypatch):
+    """The pins above, run against the given functions; returns how many fail."""
+    failed = 0
+    with monkeypatch.context() as m:
+        m.setattr(oracle, "quantize_eq8", quantize)
+        m.setattr(oracle, "requant_shift", requant)
+        for pin in (test_eq8_hand_example, test_eq8_error_bound_and_grid,
+                    test_requant_shift_against_python_integers):
+            try:
+                pin()
+            except AssertionError:
+                failed += 1
+    return failed
+
+
+def test_unplanted_copies_pass_the_pins(monkeypatch):
+    assert _run_pins(_quantizer_with(None), _shift_with(None), monkeypatch) == 0
+
+
+@pytest.mark.parametrize("bug", ["ties_away", "truncate", "no_clip", "symmetric_clip", "delta_2N",
+                                 "shift_truncates", "shift_ties_away", "shift_no_saturation"])
+def test_planted_mistakes_are_caught(bug, monkeypatch):
+    """A tie rule, a clip, a scale or a rounding offset changed by one step fails a pin."""
+    assert _run_pins(_quantizer_with(bug), _shift_with(bug), monkeypatch) >= 1, bug
 
 
 def test_pack_reference_i8_structure():
