@@ -25,8 +25,12 @@
  * bit for bit.
  *
  * Every function returns an int: BSP_OK or a negative bsp_status.  Nothing
- * aborts, throws or prints.  The library allocates no device memory and keeps
- * no global state; every buffer belongs to the caller.
+ * aborts, throws or prints.  The library allocates no device memory and every
+ * buffer belongs to the caller.  The only state it keeps between calls is a
+ * per-process memo of values that are pure functions of the arguments (the
+ * tile shape picked for a layer shape, the device's CU count, "this kernel may
+ * use more than 64 KB of LDS" set once per kernel); it reads no environment
+ * variable.
  */
 #ifndef BSP_H
 #define BSP_H
@@ -44,7 +48,8 @@ enum bsp_status {
   BSP_ERR_MASK = -3,        /* a Gamma byte is neither 0 nor 1 */
   BSP_ERR_INDEX = -4,       /* row_ptr not monotone / col_idx not ascending or out of range */
   BSP_ERR_DTYPE = -5,       /* unknown element type, or a combination not offered */
-  BSP_ERR_UNSUPPORTED = -6, /* block granularity outside {8x8, 4x16, 16x4} */
+  BSP_ERR_UNSUPPORTED = -6, /* block granularity outside {8x8, 4x16, 16x4}; bsp_conv2d_only: the
+                               layer lies outside the requested kernel family */
   BSP_ERR_CAPACITY = -7,    /* an output buffer is too small */
   BSP_ERR_HIP = -8,         /* the HIP runtime reported an error at launch */
   BSP_ERR_ALIGN = -9        /* a device pointer is not 16-byte aligned */
@@ -134,7 +139,9 @@ typedef struct bsp_weights {
   int32_t O, I, H, K;       /* layer shape (H = K = 1 for a fully-connected layer) */
   int32_t bo, bi;           /* block granularity: 8x8, 4x16 or 16x4 */
   int32_t dtype;            /* element type of payload, X and Y: BSP_F32 or BSP_BF16 */
-  int32_t reserved;         /* set to 0 */
+  int32_t kernels;          /* 0: the library picks the kernel.  Otherwise a mask of
+                               bsp_kernel_family bits the dispatcher may use (the
+                               general-shape kernel is always allowed); for tests and timing */
   int64_t nnzb;             /* kept blocks */
   const int32_t* row_ptr;   /* device copies of bsp_pack's arrays that match `payload`, or both */
   const int32_t* col_idx;   /* null.  The kernel that streams compressed block rows (FC layers
@@ -143,12 +150,18 @@ typedef struct bsp_weights {
   const void* payload;      /* device [nnzb][bo][H][K][bi] */
   const void* plan;         /* device copy of bsp_plan_build's output */
   int64_t plan_bytes;
-  const void* plan_host;    /* optional: the HOST copy of the same plan bytes.  When given,
-                               the launcher reads the plan's step counts from it and can pick
-                               kernels that keep a layer's weights resident in LDS; when null
-                               only the streaming kernels are used.  Must stay valid during
-                               the call, not after. */
+  const void* plan_host;    /* the one HOST pointer: the host copy of the same plan bytes (what
+                               bsp_plan_build wrote).  The launchers size tiles and LDS from the
+                               plan's counts without a device round trip.  Required (NULL is
+                               BSP_ERR_NULL); must stay valid during the call, not after. */
 } bsp_weights;
+
+enum bsp_kernel_family {
+  BSP_KERNEL_ROWS = 1,  /* row-band kernel: activation fragments reused over window rows */
+  BSP_KERNEL_LDS = 2,   /* weights and activations of a slab resident in LDS */
+  BSP_KERNEL_TILE = 4,  /* weights streamed through a register ring */
+  BSP_KERNEL_FC = 8     /* weight-streaming kernels for layers with at most 64 output pixels */
+};
 
 /* Fully-connected layer Y[B][O] = X[B][I] . (Gamma W-bar)^T + bias, work done
  * for kept blocks only.  Paper Section III: a GEMM is handled as a 1x1
@@ -196,6 +209,15 @@ int bsp_conv2d_general(const bsp_weights* w, const void* X, const float* bias, v
                        int32_t B, int32_t L, int32_t J,
                        int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
                        void* stream);
+
+/* Same layer (with the fused epilogue's arguments), but through one kernel family only:
+ * family is one bsp_kernel_family bit, or 0 for the general-shape kernel.  Returns
+ * BSP_ERR_UNSUPPORTED, with nothing launched, when the layer lies outside that family's limits.
+ * For testing each kernel on its own and for timing the dispatcher's choice. */
+int bsp_conv2d_only(const bsp_weights* w, const void* X, const float* bias, const void* residual,
+                    int32_t relu, void* Y, int32_t B, int32_t L, int32_t J,
+                    int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                    int32_t family, void* stream);
 
 /* ------------------------------------------- block-sparse x block-sparse product
  * Paper Section III-A: C = (Gamma A) (Omega B)^t with k x k blocks; a block product is done

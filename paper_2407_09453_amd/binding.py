@@ -17,6 +17,7 @@ BSP_F32 = 0
 BSP_BF16 = 1
 BSP_I8 = 2
 BSP_I32 = 3
+BSP_KERNEL_ROWS, BSP_KERNEL_LDS, BSP_KERNEL_TILE, BSP_KERNEL_FC = 1, 2, 4, 8
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libbsp.so")
@@ -26,7 +27,8 @@ EXPORTS = ("bsp_strerror", "bsp_version", "bsp_pack_count", "bsp_pack", "bsp_unp
            "bsp_validate", "bsp_plan_size", "bsp_plan_build", "bsp_fc", "bsp_conv2d",
            "bsp_conv2d_general", "bsp_quantize", "bsp_conv2d_i8", "bsp_fc_i8",
            "bsp_block_importance", "bsp_select_mask", "bsp_mask_step", "bsp_conv2d_fused",
-           "bsp_fc_fused", "bsp_bcsr_index", "bsp_spgemm_nt")
+           "bsp_fc_fused", "bsp_bcsr_index", "bsp_spgemm_nt",
+           "bsp_conv2d_only", "bsp_bench_copy", "bsp_bench_mfma_bf16", "bsp_bench_lds_read")
 
 
 class BspError(RuntimeError):
@@ -38,7 +40,7 @@ class BspError(RuntimeError):
 class bsp_weights(ctypes.Structure):
     _fields_ = [("O", ctypes.c_int32), ("I", ctypes.c_int32), ("H", ctypes.c_int32),
                 ("K", ctypes.c_int32), ("bo", ctypes.c_int32), ("bi", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("kernels", ctypes.c_int32),
                 ("nnzb", ctypes.c_int64), ("row_ptr", ctypes.c_void_p),
                 ("col_idx", ctypes.c_void_p), ("payload", ctypes.c_void_p),
                 ("plan", ctypes.c_void_p), ("plan_bytes", ctypes.c_int64),
@@ -106,6 +108,9 @@ def load_library():
     lib.bsp_spgemm_nt.argtypes = [ctypes.POINTER(bsp_bcsr), ctypes.POINTER(bsp_bcsr), vp, vp]
     lib.bsp_conv2d_fused.restype = ctypes.c_int
     lib.bsp_conv2d_fused.argtypes = [wp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, i32, vp]
+    lib.bsp_conv2d_only.restype = ctypes.c_int
+    lib.bsp_conv2d_only.argtypes = [wp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, i32,
+                                    i32, vp]
     lib.bsp_fc_fused.restype = ctypes.c_int
     lib.bsp_fc_fused.argtypes = [wp, vp, vp, vp, i32, vp, i32, vp]
     lib.bsp_block_importance.restype = ctypes.c_int
@@ -121,6 +126,12 @@ def load_library():
     lib.bsp_conv2d_i8.argtypes = [wp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp]
     lib.bsp_fc_i8.restype = ctypes.c_int
     lib.bsp_fc_i8.argtypes = [wp, vp, vp, vp, i32, i32, i32, vp]
+    lib.bsp_bench_copy.restype = ctypes.c_int
+    lib.bsp_bench_copy.argtypes = [vp, vp, i64, vp]
+    lib.bsp_bench_mfma_bf16.restype = ctypes.c_int
+    lib.bsp_bench_mfma_bf16.argtypes = [vp, i32, i32, vp, vp]
+    lib.bsp_bench_lds_read.restype = ctypes.c_int
+    lib.bsp_bench_lds_read.argtypes = [vp, i32, i32, vp]
     _lib = lib
     return lib
 
@@ -301,6 +312,14 @@ def bsp_fc_fused(w: bsp_weights, X: int, bias: Optional[int], residual: Optional
                                        stream), "bsp_fc_fused")
 
 
+def bsp_conv2d_only(w: bsp_weights, X: int, bias: Optional[int], residual: Optional[int],
+                    relu: bool, Y: int, B: int, L: int, J: int, stride=(1, 1), pad=(0, 0),
+                    family: int = 0, stream: int = 0) -> None:
+    _check(load_library().bsp_conv2d_only(ctypes.byref(w), X, bias, residual, int(relu), Y, B, L,
+                                          J, stride[0], stride[1], pad[0], pad[1], family, stream),
+           "bsp_conv2d_only")
+
+
 def bsp_conv2d_general(w: bsp_weights, X: int, bias: Optional[int], Y: int, B: int, L: int,
                        J: int, stride=(1, 1), pad=(0, 0), stream: int = 0) -> None:
     _check(load_library().bsp_conv2d_general(ctypes.byref(w), X, bias, Y, B, L, J, stride[0],
@@ -367,9 +386,11 @@ class BspLayer:
         return (B, M, N, self.O)
 
     def conv2d(self, X, stride=(1, 1), pad=(0, 0), out=None, general=False, stream=None,
-               residual=None, relu=False):
+               residual=None, relu=False, family=None):
         """X: torch tensor [B][L][J][I] on the layer's device, contiguous.  ``residual`` (a
-        tensor shaped like the output) and ``relu`` select the fused epilogue."""
+        tensor shaped like the output) and ``relu`` select the fused epilogue.  ``family``
+        (a BSP_KERNEL_* bit, or 0) runs that kernel family only and raises BspError(-6) when
+        the layer lies outside it."""
         import torch
         assert X.is_contiguous() and X.dtype == self.torch_dtype and X.shape[-1] == self.I
         B, L, J, _ = X.shape
@@ -378,6 +399,11 @@ class BspLayer:
                               device=X.device)
         st = torch.cuda.current_stream(X.device).cuda_stream if stream is None else stream
         bias = None if self.d_bias is None else self.d_bias.data_ptr()
+        if family is not None:
+            bsp_conv2d_only(self.struct, X.data_ptr(), bias,
+                            None if residual is None else residual.data_ptr(), relu,
+                            out.data_ptr(), B, L, J, stride, pad, family, st)
+            return out
         if residual is not None or relu:
             assert not general
             if residual is not None:
@@ -422,6 +448,21 @@ def bsp_bcsr_index(row_ptr, col_idx, rows: int, cols: int) -> np.ndarray:
 def bsp_spgemm_nt(A: bsp_bcsr, B: bsp_bcsr, C: int, stream: int = 0) -> None:
     _check(load_library().bsp_spgemm_nt(ctypes.byref(A), ctypes.byref(B), C, stream),
            "bsp_spgemm_nt")
+
+
+# ---------------------------------------------------------- measurement helpers
+def bsp_bench_copy(dst: int, src: int, nbytes: int, stream: int = 0) -> None:
+    _check(load_library().bsp_bench_copy(dst, src, nbytes, stream), "bsp_bench_copy")
+
+
+def bsp_bench_mfma_bf16(sink: int, waves: int, iters: int, clocks: Optional[int] = None,
+                        stream: int = 0) -> None:
+    _check(load_library().bsp_bench_mfma_bf16(sink, waves, iters, clocks, stream),
+           "bsp_bench_mfma_bf16")
+
+
+def bsp_bench_lds_read(sink: int, waves: int, iters: int, stream: int = 0) -> None:
+    _check(load_library().bsp_bench_lds_read(sink, waves, iters, stream), "bsp_bench_lds_read")
 
 
 class BspMatrix:

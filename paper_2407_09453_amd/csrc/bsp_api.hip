@@ -2,22 +2,9 @@
 #include "bsp.h"
 #include "bsp_launch.h"
 
-#include <cstdlib>
-#include <cstring>
 #include <limits>
 
 namespace {
-
-// BSP_KERNEL=general|tile|lds narrows the dispatcher's choice (tuning aid): "tile" skips
-// the LDS-resident kernel, "general" skips both LDS-tiled kernels.
-int kernel_limit() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = std::getenv("BSP_KERNEL");
-    v = !e ? 2 : !std::strcmp(e, "general") ? 0 : !std::strcmp(e, "tile") ? 1 : 2;
-  }
-  return v;
-}
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -25,7 +12,7 @@ int prepare(const bsp_weights* w, const void* X, const float* bias, void* Y, int
             int32_t L, int32_t J, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
             ConvParams* out, bool integer = false) {
   if (!w || (B != 0 && (!X || !Y))) return BSP_ERR_NULL;  // an empty batch needs no X or Y
-  if (!w->plan) return BSP_ERR_NULL;
+  if (!w->plan || !w->plan_host) return BSP_ERR_NULL;
   if (w->nnzb > 0 && !w->payload) return BSP_ERR_NULL;
   if (w->O <= 0 || w->I <= 0 || w->H <= 0 || w->K <= 0 || w->nnzb < 0) return BSP_ERR_SHAPE;
   if (!((w->bo == 8 && w->bi == 8) || (w->bo == 4 && w->bi == 16) || (w->bo == 16 && w->bi == 4)))
@@ -80,17 +67,22 @@ namespace {
 
 int dispatch(const bsp_weights* w, const ConvParams& p, void* stream) {
   if (p.P == 0) return BSP_OK;
-  if (w->dtype == BSP_BF16 && kernel_limit() >= 1) {
+  const int allow = w->kernels ? w->kernels : ~0;
+  if (w->dtype == BSP_BF16) {
     // each launcher declines (UNSUPPORTED, nothing launched) what lies outside its limits
     const bool chunked = bsp_tile_supported(p, w->dtype);  // whole 8-channel chunks
+    hipStream_t st = (hipStream_t)stream;
     int rc = BSP_ERR_UNSUPPORTED;
-    if (chunked) rc = bsp_launch_fc_rows(p, w->dtype, w->bo, w->bi, w->nnzb, (hipStream_t)stream);
+    if (chunked && (allow & BSP_KERNEL_FC)) rc = bsp_launch_fc_rows(p, w->dtype, w->bo, w->bi, w->nnzb, st);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
-    if (chunked) rc = bsp_launch_fc_stream(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
+    if (chunked && (allow & BSP_KERNEL_FC)) rc = bsp_launch_fc_stream(p, w->dtype, w->bo, w->bi, st);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
-    if (kernel_limit() >= 2) rc = bsp_launch_lds(p, w->dtype, w->plan_host, (hipStream_t)stream);
+    // (pointwise layers stay with the LDS-resident kernel until the row-band kernel beats it there)
+    if ((allow & BSP_KERNEL_ROWS) && (p.H > 1 || w->kernels)) rc = bsp_launch_rows(p, w->dtype, w->plan_host, st);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
-    if (chunked) rc = bsp_launch_tile(p, w->dtype, (hipStream_t)stream);
+    if (allow & BSP_KERNEL_LDS) rc = bsp_launch_lds(p, w->dtype, w->plan_host, st);
+    if (rc != BSP_ERR_UNSUPPORTED) return rc;
+    if (chunked && (allow & BSP_KERNEL_TILE)) rc = bsp_launch_tile(p, w->dtype, st);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
   }
   return bsp_launch_general(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
@@ -107,6 +99,32 @@ int bsp_conv2d_general(const bsp_weights* w, const void* X, const float* bias, v
   if (int rc = prepare(w, X, bias, Y, B, L, J, stride_h, stride_w, pad_h, pad_w, &p)) return rc;
   if (p.P == 0) return BSP_OK;
   return bsp_launch_general(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
+}
+
+int bsp_conv2d_only(const bsp_weights* w, const void* X, const float* bias, const void* residual,
+                    int32_t relu, void* Y, int32_t B, int32_t L, int32_t J, int32_t stride_h,
+                    int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t family, void* stream) {
+  ConvParams p;
+  if (int rc = prepare(w, X, bias, Y, B, L, J, stride_h, stride_w, pad_h, pad_w, &p)) return rc;
+  if (residual && !aligned16(residual)) return BSP_ERR_ALIGN;
+  p.residual = residual;
+  p.relu = relu != 0;
+  if (p.P == 0) return BSP_OK;
+  hipStream_t st = (hipStream_t)stream;
+  if (family == 0) return bsp_launch_general(p, w->dtype, w->bo, w->bi, st);
+  if (w->dtype != BSP_BF16) return BSP_ERR_UNSUPPORTED;
+  const bool chunked = bsp_tile_supported(p, w->dtype);
+  switch (family) {
+    case BSP_KERNEL_ROWS: return bsp_launch_rows(p, w->dtype, w->plan_host, st);
+    case BSP_KERNEL_LDS: return bsp_launch_lds(p, w->dtype, w->plan_host, st);
+    case BSP_KERNEL_TILE: return chunked ? bsp_launch_tile(p, w->dtype, st) : BSP_ERR_UNSUPPORTED;
+    case BSP_KERNEL_FC: {
+      if (!chunked) return BSP_ERR_UNSUPPORTED;
+      const int rc = bsp_launch_fc_rows(p, w->dtype, w->bo, w->bi, w->nnzb, st);
+      return rc != BSP_ERR_UNSUPPORTED ? rc : bsp_launch_fc_stream(p, w->dtype, w->bo, w->bi, st);
+    }
+    default: return BSP_ERR_UNSUPPORTED;
+  }
 }
 
 int bsp_conv2d(const bsp_weights* w, const void* X, const float* bias, void* Y, int32_t B,
@@ -153,7 +171,7 @@ int bsp_conv2d_i8(const bsp_weights* w, const int8_t* X, const int32_t* bias, vo
   if (y_dtype != BSP_I8 && y_dtype != BSP_I32) return BSP_ERR_DTYPE;
   if (y_dtype == BSP_I8 && (shift < 0 || shift > 31)) return BSP_ERR_SHAPE;
   if (p.P == 0) return BSP_OK;
-  if (y_dtype == BSP_I8 && kernel_limit() >= 2 && aligned16(X)) {
+  if (y_dtype == BSP_I8 && (!w->kernels || (w->kernels & BSP_KERNEL_LDS)) && aligned16(X)) {
     const int rc = bsp_launch_lds_i8(p, w->plan_host, shift, (hipStream_t)stream);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
   }

@@ -10,6 +10,12 @@
 #include <limits>
 #include <vector>
 
+bool bsp_rows_wanted(int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo, int32_t bi,
+                     int32_t dtype);
+int bsp_rows_section(const int32_t* row_ptr, const int32_t* col_idx, const uint16_t* payload,
+                     int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo, int32_t bi,
+                     std::vector<int32_t>* sec);
+
 namespace {
 
 inline bool granularity_ok(int32_t bo, int32_t bi) {
@@ -110,7 +116,9 @@ const char* bsp_strerror(int code) {
     case BSP_ERR_MASK: return "mask byte is neither 0 nor 1";
     case BSP_ERR_INDEX: return "row_ptr / col_idx malformed";
     case BSP_ERR_DTYPE: return "element type not supported";
-    case BSP_ERR_UNSUPPORTED: return "block granularity not in {8x8, 4x16, 16x4}";
+    case BSP_ERR_UNSUPPORTED:
+      return "unsupported: block granularity not in {8x8, 4x16, 16x4}, or a layer outside the "
+             "requested kernel family";
     case BSP_ERR_CAPACITY: return "output buffer too small";
     case BSP_ERR_HIP: return "HIP runtime error at launch";
     case BSP_ERR_ALIGN: return "device pointer not 16-byte aligned";
@@ -448,7 +456,14 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, const void*
   const int64_t off_slab = off_src + nchunks * BSP_MAXSUB;
   const int64_t off_xdesc = off_slab + (steps_wanted ? pad4((int64_t)nstrips * (nslabs + 1)) : 0);
   const int64_t off_wfrag = off_xdesc + nsteps * 4;
-  const int64_t total = off_wfrag + nsteps * 64 * 4;  // 16 bytes (four words) per lane and step
+  // 16 bytes (four words) per lane and step; then the row-band section, 16-byte aligned
+  const int64_t off_rows = (off_wfrag + nsteps * 64 * 4 + 3) & ~int64_t(3);
+  std::vector<int32_t> rows;
+  if (bsp_rows_wanted(O, H, K, I, bo, bi, dtype))
+    if (int rc = bsp_rows_section(row_ptr, col_idx, out ? (const uint16_t*)payload : nullptr, O, H,
+                                  K, I, bo, bi, &rows))
+      return rc;
+  const int64_t total = off_rows + (int64_t)rows.size();
   if (total > std::numeric_limits<int32_t>::max()) return BSP_ERR_SHAPE;
   if (words_needed) *words_needed = total;
   if (!out) return BSP_OK;
@@ -479,6 +494,8 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, const void*
   out[BSP_PLAN_OFF_WFRAG_W] = (int32_t)off_wfrag;
   out[BSP_PLAN_MAXSTEPS_W] = steps_wanted ? max_steps : 0;
   out[BSP_PLAN_MAXSLABSTEPS_W] = steps_wanted ? max_slab_steps : 0;
+  out[BSP_PLAN_OFF_ROWS_W] = rows.empty() ? 0 : (int32_t)off_rows;
+  if (!rows.empty()) std::memcpy(out + off_rows, rows.data(), sizeof(int32_t) * rows.size());
   std::memcpy(out + off_strip, strip_ptr.data(), sizeof(int32_t) * strip_ptr.size());
   if (nchunks) {
     std::memcpy(out + off_xc, xc_list.data(), sizeof(int32_t) * xc_list.size());

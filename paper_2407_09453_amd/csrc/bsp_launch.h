@@ -26,6 +26,10 @@ int bsp_launch_lds(const ConvParams& p, int dtype, const void* plan_host, hipStr
 // the same for int8 codes with int8 results (sum + bias, rounding right shift, saturation)
 int bsp_launch_lds_i8(const ConvParams& p, const void* plan_host, int shift, hipStream_t st);
 
+// Row-band kernel (bf16, 1xK and 3xK windows, strides 1 and 2; needs the plan's row-band
+// section and its host copy).  BSP_ERR_UNSUPPORTED = not applicable, nothing launched.
+int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);
+
 // 8-bit integer layers: X and payload int8, bias int32 (passed through ConvParams::bias),
 // Y int8 after a rounding right shift (y_i8 = 1) or the int32 sums.
 int bsp_launch_i8(const ConvParams& p, int y_i8, int shift, int bo, int bi, hipStream_t st);

@@ -46,7 +46,7 @@ enum {
   BSP_MAXSUB = 4,
   BSP_PLAN_HEADER_WORDS = 32,
   BSP_PLAN_MAGIC = 0x42535032,
-  BSP_PLAN_VERSION = 3,
+  BSP_PLAN_VERSION = 4,
 };
 
 enum {
@@ -74,7 +74,56 @@ enum {
   BSP_PLAN_OFF_WFRAG_W = 21,
   BSP_PLAN_MAXSTEPS_W = 22,   // most steps in any one strip
   BSP_PLAN_MAXSLABSTEPS_W = 23,  // most steps in any one (strip, slab)
+  BSP_PLAN_OFF_ROWS_W = 24,   // first word of the row-band section, 0 when there is none
 };
+
+// Row-band section (bf16 layers with whole 8-channel groups; read by bsp_rows.hip).
+//
+// Strips here are groups of block rows chosen by the builder so that rows sharing many kept
+// columns sit together (a 16-row matrix-core tile multiplies one activation operand with all
+// of its rows, so a strip runs the union of its rows' columns): two 8x8 block rows, four 4x16
+// block rows or one 16x4 block row per strip, in any order; rstrip gives, per group of four
+// tile rows, the first output channel they produce (-1: none).  The contraction of a strip is
+// a list of items (unit, dx): a unit is a group of `cw` input channels (8, or 4 for 16x4
+// blocks, where every kept block is then exactly one unit and nothing is zero-filled), dx a
+// column of the kernel window; all H rows of the window belong to the item, which is what
+// lets the kernel reuse one activation fragment for H output rows.  `32 / cw` consecutive
+// items form a column step (one MFMA's K extent per window row).  Input channels are cut
+// into slabs of `slab` channels; a column step never crosses a slab.
+//   [0..23]                     header, see enum
+//   rstrip[nstrips][4]          first output channel of tile rows 4q..4q+3, or -1
+//   rslab[nstrips][nslabs+1]    first column step of each (strip, slab)
+//   rdesc[ncs][4]               per lane group: its item as unit_in_slab | dx << 8 (cw 4: two
+//                               items, one per 16-bit half)
+//   rfrag[ncs][H][64][8]        bf16 weights, lane 16q + j of (step, window row dy):
+//                               W[strip row j][dy][dx(item)][unit(item) channels] or 0
+// Strips are stored heaviest first.
+enum {
+  BSP_ROWS_HEADER_WORDS = 24,
+  BSP_ROWS_NSTRIPS_W = 0,
+  BSP_ROWS_SLAB_W = 1,
+  BSP_ROWS_NSLABS_W = 2,
+  BSP_ROWS_NCS_W = 3,
+  BSP_ROWS_RESERVED_W = 4,
+  BSP_ROWS_OFF_STRIP_W = 5,    // offsets in words from the section start
+  BSP_ROWS_OFF_SLAB_W = 6,
+  BSP_ROWS_OFF_DESC_W = 7,
+  BSP_ROWS_OFF_FRAG_W = 8,
+  BSP_ROWS_CW_W = 9,
+  BSP_ROWS_MAXSTEPS_W = 10,       // most column steps in any (strip, slab)
+  BSP_ROWS_MAXSTRIPSTEPS_W = 11,  // most column steps in any strip
+  BSP_ROWS_KEPT_ITEMS_W = 12,     // units in kept blocks (work the mask asks for)
+  BSP_ROWS_UNION_ITEMS_W = 13,    // units the strips run (kept + zero-filled)
+  BSP_ROWS_ZEROS_W = 16,          // four zero words, 16-byte aligned: the source of padding pieces
+  BSP_ROWS_MAXH = 7,
+};
+
+// Channels the row-band kernel stages at a time.
+static inline int32_t bsp_rows_slab(int32_t I, int32_t H, int32_t K) {
+  const int32_t i8 = (I + 7) / 8 * 8;
+  const int32_t cap = (H * K > 1) ? 128 : 256;
+  return i8 < cap ? i8 : cap;
+}
 
 // Channels kept in LDS at a time, as a function of the layer shape alone so
 // that the plan builder and the launcher agree without talking to each other.

@@ -1,0 +1,780 @@
+// Row-band kernel: block-sparse implicit-GEMM convolution for bf16 layers (fp32 accumulation)
+// in which one activation fragment, once in registers, serves every window row.
+//
+// Work split.  A workgroup owns a pixel tile (NI images x NB bands of BR output rows x TW
+// output columns) and SG strips of 16 output channels.  The tile's pixels are seen as
+// columns: a column is BR vertically consecutive output pixels, sixteen columns make a
+// lane tile (the N side of a 16x16 MFMA tile).  A wave owns one strip, NT lane tiles and, when
+// the contraction is split (KS > 1), one share of the strip's column steps.
+//
+// Per slab of input channels the workgroup stages the tile's input patch (halo included,
+// zeros outside the image) in LDS.  A wave then walks its strip's column steps: per step it
+// reads, for each lane tile, the NF = (BR-1)*S + H patch rows of the step's items once, takes
+// the step's H weight fragments (one per window row, streamed from the plan through a ring of
+// registers), and issues H*BR MFMAs per lane tile: output row r, window row dy uses patch row
+// r*S + dy.  So an activation fragment read from LDS feeds up to H MFMAs, and a weight
+// fragment feeds BR*NT.
+//
+// Only kept blocks have items (paper Section I, advantages 3-4); a strip groups block rows
+// with similar kept columns (bsp_plan.h).  Results (+ bias, rounded once) are staged in LDS
+// and leave as 16-byte pieces; a residual add and ReLU can be applied on the way out.
+#include "bsp_launch.h"
+#include "bsp_tile.h"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+
+namespace {
+
+struct RowsArgs {
+  const unsigned char* X;
+  unsigned char* Y;
+  const float* bias;
+  const unsigned char* residual;
+  const int32_t* rstrip;
+  const int32_t* rslab;
+  const int32_t* rdesc;
+  const u32x4_t* rfrag;
+  const unsigned char* zeros;      // sixteen zero bytes (in the plan)
+  int32_t relu;
+  int32_t nstrips, nslabs, ncs;
+  int32_t sc;                      // 16-byte pieces of a staged pixel that hold data (slab / 8)
+  int32_t lscp;                    // log2 of the pieces a staged pixel occupies (power of two >= sc)
+  int32_t swz_shift, swz_mask;     // piece p of pixel q sits in slot p ^ ((q >> shift) & mask)
+  int32_t B, L, J, I, O, M, N;
+  int32_t ph, pw, stride;          // stride = S * gs
+  int32_t gs;                      // input pixels per staged pixel (strided pointwise layers: the stride)
+  int32_t TW, NB, NI, PR, PC, PCp; // PC staged columns that are read, PCp the row pitch (multiple of 16)
+  int32_t tiles_x, tiles_y, ntiles;
+  int32_t ncols;                   // NI * NB * TW
+  int32_t SG, PTW, KS, nsg;
+  int32_t per_xcd;                 // workgroups per XCD slot range
+  int32_t bufbytes;                // one patch buffer
+  int32_t orow;                    // bytes per pixel in the results staging tile
+  int32_t red_bytes;               // LDS bytes of the split-contraction partials
+  int32_t tbl_off;                 // LDS offset of the tables
+  int32_t piece8;                  // results leave as 8-byte pieces (4x16 blocks)
+  int32_t direct;                  // results leave straight from the accumulators, 8 bytes per lane
+  int32_t xlimit, ylimit;          // input / output pixels that exist (the flattened view may end mid-row)
+  int32_t lsg, lptw;               // log2 of SG and PTW
+  FastDiv d_pcp, d_pr, d_np, d_br, d_nsg, d_tpi, d_tx, d_perimg, d_tw;
+};
+
+#ifdef BSP_ROWS_TUNE  // experiments only: per-workgroup phase timestamps
+__device__ long long g_rows_trace[4096 * 16];
+#define ROWS_TRACE(k)                                                              \
+  if (tid == 0 && blockIdx.x < 4096) {                                             \
+    g_rows_trace[blockIdx.x * 16 + (k)] = (long long)wall_clock64();                \
+    if ((k) == 1 || (k) == 2) g_rows_trace[blockIdx.x * 16 + 6 + (k)-1] = (long long)clock64(); \
+  }
+#else
+#define ROWS_TRACE(k)
+#endif
+
+// LDS traffic of the main loop is written out: the compiler cannot see through the
+// global->LDS copies and would otherwise wait for all of them before every LDS read.
+template <int H, int S, int BR>
+constexpr bool row_needed(int fr) {
+  for (int r = 0; r < BR; ++r)
+    for (int dy = 0; dy < H; ++dy)
+      if (r * S + dy == fr) return true;
+  return false;
+}
+
+template <int H, int S, int BR, int NT, bool CW4, int D>
+__global__ __launch_bounds__(576) void conv_rows(RowsArgs a) {
+  constexpr int NF = (BR - 1) * S + H;
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int tid = threadIdx.x;
+  const int nthreads = blockDim.x - 64;  // compute threads; the last wave moves data
+  const int wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
+
+  // workgroup -> (tile, strip group): consecutive workgroups of one XCD share a tile
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  if (slot >= a.per_xcd) return;
+  const int q = xcd * a.per_xcd + slot;
+  const int tile = (int)fdiv((uint32_t)q, a.d_nsg), sgi = q - tile * a.nsg;
+  if (tile >= a.ntiles) return;
+  const int tpi = a.tiles_x * a.tiles_y;
+  const int ig = (int)fdiv((uint32_t)tile, a.d_tpi), trem = tile - ig * tpi;
+  const int ty = (int)fdiv((uint32_t)trem, a.d_tx), tx = trem - ty * a.tiles_x;
+  const int img0 = ig * a.NI, y0 = ty * a.NB * BR, x0 = tx * a.TW;
+
+  ROWS_TRACE(0)
+  int32_t* colbase = (int32_t*)(lds + a.tbl_off);
+  const int nslots = a.PTW * NT * 16;
+  int32_t* colrows = colbase + nslots;
+  int32_t* colpix = colrows + nslots;
+  int32_t* chans = colpix + nslots;
+  if (tid < nslots) {
+    int cb = -1, rows = 0, lp = 0;
+    if (tid < a.ncols) {
+      const int per_img = a.NB * a.TW;
+      const int img = (int)fdiv((uint32_t)tid, a.d_perimg), rem = tid - img * per_img;
+      const int band = (int)fdiv((uint32_t)rem, a.d_tw), x = rem - band * a.TW;
+      lp = (img * a.PR + band * BR * S) * a.PCp + x * S;   // first staged pixel of the column
+      const int gi = img0 + img, gy = y0 + band * BR, gx = x0 + x;
+      if (gi < a.B && gx < a.N && gy < a.M) {
+        cb = (gi * a.M + gy) * a.N + gx;
+        rows = min(BR, a.M - gy);
+      }
+    }
+    colbase[tid] = cb;
+    colrows[tid] = rows;
+    colpix[tid] = lp;
+  }
+  if (tid < a.SG * 4) {
+    const int st = sgi * a.SG + (tid >> 2);
+    chans[tid] = st < a.nstrips ? a.rstrip[st * 4 + (tid & 3)] : -1;
+  }
+
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const bool mover = wave_u * 64 >= nthreads;
+  // SG and PTW are powers of two
+  const int sl_local = wave_u & (a.SG - 1), sub = wave_u >> a.lsg;
+  const int pt = sub & (a.PTW - 1), ks = mover ? -1 : sub >> a.lptw;
+  const int strip = sgi * a.SG + sl_local;
+  const bool active = !mover && strip < a.nstrips && a.ncs > 0;
+
+  f32x4_t acc[NT][BR];
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int r = 0; r < BR; ++r) acc[j][r] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  const int rowbytes = a.PCp << (a.lscp + 4);
+
+  // ---- staging.  Every piece of a slab's patch goes from global memory straight into LDS:
+  // 64 lanes x 16 bytes per request land as one contiguous KiB, so lane l of a request owns
+  // slot base + l and asks for whichever piece belongs there.  Staged pixels outside the
+  // image are cleared once in both buffers and never requested, so they stay zero for every
+  // slab.  stage(sl, w, nw): wave w of nw takes every nw-th staged row.
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
+  const int lppi = 6 - a.lscp;          // log2 of the pixels one request covers
+  const int sub_pix = lane >> a.lscp;   // this lane's pixel within the request
+  const int sidx = lane & ((1 << a.lscp) - 1);  // and its slot within the pixel
+  const int iy0 = y0 * a.stride - a.ph, ix0 = x0 * a.stride - a.pw;
+  const int groups = a.PCp >> lppi;     // requests per staged row
+  const int nrows = a.NI * a.PR;
+  auto stage = [&](int sl, int w, int nw) {
+    const uint32_t buf = lds0 + (sl & 1) * a.bufbytes;
+    // lane j: the j-th staged row of this wave, where it starts in X (or all ones: outside)
+    uint32_t rowsrc = 0xFFFFFFFFu;
+    const int myrow = w + lane * nw;
+    if (myrow < nrows) {
+      const int img = (int)fdiv((uint32_t)myrow, a.d_pr), pr = myrow - img * a.PR;
+      const int gi = img0 + img, gy = iy0 + pr * a.gs;
+      if (gi < a.B && (unsigned)gy < (unsigned)a.L) rowsrc = (uint32_t)((gi * a.L + gy) * a.J) * (uint32_t)a.I * 2u;
+    }
+    const int nrw = (nrows - w + nw - 1) / nw;
+    for (int gq = 0; gq < groups; ++gq) {
+      const int pc = (gq << lppi) + sub_pix;               // staged column of this lane
+      const int cq = sidx ^ ((pc >> a.swz_shift) & a.swz_mask);
+      const int gx = ix0 + pc * a.gs;
+      const int ch = (sl * a.sc + cq) * 8;
+      const bool col_real = cq < a.sc && ch < a.I && pc < a.PC && (unsigned)gx < (unsigned)a.J;
+      const uint32_t col_off = ((uint32_t)gx * (uint32_t)a.I + (uint32_t)ch) * 2u;
+      const uint32_t col_end = (uint32_t)(a.xlimit - gx) * (uint32_t)a.I * 2u;  // rows starting below this exist
+      for (int j = 0; j < nrw; ++j) {
+        const uint32_t src = __builtin_amdgcn_readlane(rowsrc, j);
+        if (src == 0xFFFFFFFFu) continue;
+        const uint32_t dst = buf + ((uint32_t)((w + j * nw) * a.PCp + (gq << lppi)) << (a.lscp + 4));
+        if (col_real && src < col_end)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.X + (src + col_off)),
+                                           (__attribute__((address_space(3))) void*)(uintptr_t)dst, 16, 0, 0);
+      }
+    }
+  };
+  {
+    // clear the staged pixels that lie outside the image (both buffers), then, all waves
+    // together, request the first slab
+    const int npixels = nrows * a.PCp;
+    for (int pix = tid; pix < npixels; pix += blockDim.x) {
+      const int row = (int)fdiv((uint32_t)pix, a.d_pcp), pc = pix - row * a.PCp;
+      const int img = (int)fdiv((uint32_t)row, a.d_pr), pr = row - img * a.PR;
+      const int gi = img0 + img, gy = iy0 + pr * a.gs, gx = ix0 + pc * a.gs;
+      const bool inside = gi < a.B && (unsigned)gy < (unsigned)a.L && (unsigned)gx < (unsigned)a.J &&
+                          (gi * a.L + gy) * a.J + gx < a.xlimit;
+      if (!inside && pc < a.PC) {
+        u32x4_t* p0 = (u32x4_t*)(lds + ((size_t)pix << (a.lscp + 4)));
+        for (int k = 0; k < (1 << a.lscp); ++k) {
+          p0[k] = u32x4_t{0, 0, 0, 0};
+          if (a.nslabs > 1) p0[k + (a.bufbytes >> 4)] = u32x4_t{0, 0, 0, 0};
+        }
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    ROWS_TRACE(8)
+    stage(0, wave_u, (int)(blockDim.x >> 6));
+    ROWS_TRACE(9)
+  }
+
+  if (mover) {
+    // ---- the data mover requests the next slab while the compute waves work on the current
+    // one; the barrier at the end of a slab tells them it has landed and tells the mover that
+    // the other buffer is free.
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();                  // the first slab is in LDS
+    for (int sl = 1; sl < a.nslabs; ++sl) {
+      stage(sl, 0, 1);
+      __builtin_amdgcn_s_waitcnt(0);  // everything requested so far is in LDS
+      __syncthreads();                // slab sl - 1 is done everywhere
+    }
+    __syncthreads();                  // the last slab is done
+  } else {
+    // ---- compute waves.  The strip's column steps, slab after slab; their weight fragments
+    // and descriptors come from the plan through a ring of registers, D steps ahead.
+    const int* rsl = a.rslab + (active ? strip : 0) * (a.nslabs + 1);
+    const int vr = rsl[min(lane, a.nslabs)];  // lane i holds the first step of slab i
+    // A strip's steps are numbered consecutively through all its slabs.  With the
+    // contraction split KS ways (a power of two) this wave takes the steps whose number is
+    // ks modulo KS, so its sequence is one arithmetic progression from start to finish.
+    const int ksm = a.KS - 1;
+    const int s_first = __builtin_amdgcn_readlane(vr, 0), s_end = __builtin_amdgcn_readlane(vr, a.nslabs);
+    int fnext = s_first + ((ks - s_first) & ksm);
+    const uint32_t frag_lane = (uint32_t)lane * 16u, desc_lane = (uint32_t)g * 4u;
+    const unsigned char* fragb = (const unsigned char*)a.rfrag;
+    const unsigned char* descb = (const unsigned char*)a.rdesc;
+    u32x4_t wr[D][H];  // weight fragments of the next D steps of the sequence, oldest in slot 0
+    int dr[D];         // their item descriptors
+    int at[D];         // which step each slot holds
+    // Slot d takes the next step of the sequence (advance) or asks for the step it already
+    // holds again: every pass through the unrolled loop below then issues the same loads,
+    // whatever the step count, which lets the compiler wait for exactly the slot it needs.
+    auto fetch = [&](int d, bool advance) {
+#ifdef BSP_EXP_NOW
+      const int cs = advance ? s_first : at[d];
+#else
+      const int cs = advance ? max(0, min(fnext, s_end - 1)) : at[d];  // past the end: a valid step, never used
+#endif
+      fnext += advance ? a.KS : 0;
+      at[d] = cs;
+      dr[d] = *(const int*)(descb + ((uint32_t)cs * 16u + desc_lane));
+      const uint32_t off = (uint32_t)cs * (uint32_t)(H * 1024) + frag_lane;
+#pragma unroll
+      for (int dy = 0; dy < H; ++dy) wr[d][dy] = *(const u32x4_t*)(fragb + off + dy * 1024);
+    };
+    if (active) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        at[d] = 0;
+        fetch(d, true);
+      }
+    }
+    ROWS_TRACE(10)
+    __builtin_amdgcn_s_waitcnt(0);  // this wave's share of the first patch has landed
+    __syncthreads();                // the first slab's patch and the tables are in LDS
+    ROWS_TRACE(1)
+    int pixb[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) pixb[j] = colpix[(pt * NT + j) * 16 + c];
+
+    for (int sl = 0; sl < a.nslabs; ++sl) {
+      if (active) {
+        const unsigned char* buf = lds + (sl & 1) * a.bufbytes;
+        int lo = __builtin_amdgcn_readlane(vr, sl);
+        const int hi = __builtin_amdgcn_readlane(vr, sl + 1);
+        lo += (ks - lo) & ksm;  // this wave's first step of the slab
+        const int stepd = a.KS * D;
+        for (int cs0 = lo; cs0 < hi; cs0 += stepd) {
+#pragma unroll
+          for (int d = 0; d < D; ++d) {
+            const bool use = cs0 + d * a.KS < hi;
+            if (use) {
+              u32x4_t f[NT][NF];
+              const uint32_t desc = (uint32_t)dr[d];
+#pragma unroll
+              for (int j = 0; j < NT; ++j) {
+                if (CW4) {
+                  uint32_t ad[2];
+#pragma unroll
+                  for (int h = 0; h < 2; ++h) {
+                    const uint32_t it = (desc >> (16 * h)) & 0xFFFFu;
+                    const uint32_t unit = it & 0xFFu, pj = (uint32_t)pixb[j] + (it >> 8);
+                    ad[h] = (((pj << a.lscp) + ((unit >> 1) ^ ((pj >> a.swz_shift) & a.swz_mask))) << 4) +
+                            ((unit & 1u) << 3);
+                  }
+#pragma unroll
+                  for (int fr = 0; fr < NF; ++fr) {
+                    if (!row_needed<H, S, BR>(fr)) continue;
+                    const u32x2_t p0 = *(const u32x2_t*)(buf + ad[0] + fr * rowbytes);
+                    const u32x2_t p1 = *(const u32x2_t*)(buf + ad[1] + fr * rowbytes);
+                    f[j][fr] = u32x4_t{p0.x, p0.y, p1.x, p1.y};
+                  }
+                } else {
+                  const uint32_t unit = desc & 0xFFu, pj = (uint32_t)pixb[j] + ((desc >> 8) & 0xFFu);
+#ifdef BSP_EXP_NOLDS
+                  const uint32_t ad = (uint32_t)lane * 16u + (unit & 0u) + (pj & 0u);
+#else
+                  const uint32_t ad = ((pj << a.lscp) + (unit ^ ((pj >> a.swz_shift) & a.swz_mask))) << 4;
+#endif
+#pragma unroll
+                  for (int fr = 0; fr < NF; ++fr) {
+                    if (!row_needed<H, S, BR>(fr)) continue;
+#ifdef BSP_EXP_NOLDS
+                    f[j][fr] = *(const u32x4_t*)(buf + ad + fr * 1024);
+#else
+                    f[j][fr] = *(const u32x4_t*)(buf + ad + fr * rowbytes);
+#endif
+                  }
+                }
+              }
+#pragma unroll
+              for (int dy = 0; dy < H; ++dy)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+#pragma unroll
+                  for (int r = 0; r < BR; ++r)
+#ifdef BSP_EXP_NOMFMA
+                    acc[j][r] = acc[j][r] + __builtin_bit_cast(f32x4_t, wr[d][dy] ^ f[j][r * S + dy]);
+#else
+                    acc[j][r] = mfma_bf16_16x16x32(wr[d][dy], f[j][r * S + dy], acc[j][r]);
+#endif
+            }
+            // refill the slot only now, in place: requested earlier, the new fragments would
+            // need registers of their own and be copied over once the MFMAs have read the old
+            // ones, and a copy has to wait for its load
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(d, use);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        // the slab's steps need not fill the ring a whole number of times: turn the ring so
+        // that the next step to use is in slot 0 again
+        const int turn = lo < hi ? ((hi - lo + ksm) / a.KS) % D : 0;
+        for (int k = 0; k < turn; ++k) {
+          u32x4_t t[H];
+          const int td = dr[0], ta = at[0];
+#pragma unroll
+          for (int dy = 0; dy < H; ++dy) t[dy] = wr[0][dy];
+#pragma unroll
+          for (int d = 0; d + 1 < D; ++d) {
+            dr[d] = dr[d + 1];
+            at[d] = at[d + 1];
+#pragma unroll
+            for (int dy = 0; dy < H; ++dy) wr[d][dy] = wr[d + 1][dy];
+          }
+          dr[D - 1] = td;
+          at[D - 1] = ta;
+#pragma unroll
+          for (int dy = 0; dy < H; ++dy) wr[D - 1][dy] = t[dy];
+        }
+      }
+      if (sl == 0) { ROWS_TRACE(2) }
+      __syncthreads();  // this slab is done everywhere and the next one has landed
+    }
+  }
+
+  // ---- results: optional sum over the contraction shares, bias, one rounding, staging
+  ROWS_TRACE(3)
+  unsigned char* red = lds;
+  unsigned char* ostage = lds + a.red_bytes;
+  if (a.KS > 1) {
+    if (ks > 0) {
+      const int w = ((ks - 1) * a.PTW + pt) * a.SG + sl_local;
+      f32x4_t* dst = (f32x4_t*)red + (size_t)w * NT * BR * 64;
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int r = 0; r < BR; ++r) dst[(j * BR + r) * 64 + lane] = acc[j][r];
+    }
+    __syncthreads();
+    if (ks == 0) {
+      for (int k = 1; k < a.KS; ++k) {
+        const int w = ((k - 1) * a.PTW + pt) * a.SG + sl_local;
+        const f32x4_t* src = (const f32x4_t*)red + (size_t)w * NT * BR * 64;
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+          for (int r = 0; r < BR; ++r) acc[j][r] += src[(j * BR + r) * 64 + lane];
+      }
+    }
+  }
+  if (a.direct) {
+    // results straight from the accumulators: 8 bytes (four channels of one pixel) per lane
+    if (!mover && ks == 0 && strip < a.nstrips) {
+      const int ch = chans[sl_local * 4 + g];
+      if (ch >= 0) {
+        f32x4_t bv = {0.f, 0.f, 0.f, 0.f};
+        if (a.bias) bv = f32x4_t{a.bias[ch], a.bias[ch + 1], a.bias[ch + 2], a.bias[ch + 3]};
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          const int col = (pt * NT + j) * 16 + c;
+          const int cb = colbase[col], rows = colrows[col];
+          if (cb < 0) continue;
+#pragma unroll
+          for (int r = 0; r < BR; ++r) {
+            if (r >= rows || cb + r * a.N >= a.ylimit) continue;
+            const f32x4_t v = acc[j][r] + bv;
+            u32x2_t o;
+            o.x = pack_bf16x2(v.x, v.y);
+            o.y = pack_bf16x2(v.z, v.w);
+            const uint32_t off = ((uint32_t)(cb + r * a.N) * (uint32_t)a.O + (uint32_t)ch) * 2u;
+            if (a.residual || a.relu)
+              o = post_bf16x4(o, a.residual ? (const uint16_t*)(a.residual + off) : nullptr, 4, true, a.relu);
+            *(u32x2_t*)(a.Y + off) = o;
+          }
+        }
+      }
+    }
+    return;
+  }
+  if (!mover && ks == 0 && strip < a.nstrips) {
+    const int ch = chans[sl_local * 4 + g];
+    if (ch >= 0) {
+      f32x4_t bv = {0.f, 0.f, 0.f, 0.f};
+      if (a.bias) bv = f32x4_t{a.bias[ch], a.bias[ch + 1], a.bias[ch + 2], a.bias[ch + 3]};
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int r = 0; r < BR; ++r) {
+          const f32x4_t v = acc[j][r] + bv;
+          u32x2_t o;
+          o.x = pack_bf16x2(v.x, v.y);
+          o.y = pack_bf16x2(v.z, v.w);
+          const int pix = ((pt * NT + j) * 16 + c) * BR + r;
+          *(u32x2_t*)(ostage + pix * a.orow + (sl_local * 4 + g) * 8) = o;
+        }
+    }
+  }
+  __syncthreads();
+  ROWS_TRACE(4)
+  const int nopix = nslots * BR;
+  if (!a.piece8) {
+    const int np = a.SG * 2;
+    for (int idx = tid; idx < nopix * np; idx += blockDim.x) {
+      const int pix = (int)fdiv((uint32_t)idx, a.d_np), pc = idx - pix * np;
+      const int col = (int)fdiv((uint32_t)pix, a.d_br), r = pix - col * BR;
+      const int cb = colbase[col], ch = chans[pc * 2];
+      if (cb < 0 || r >= colrows[col] || ch < 0 || cb + r * a.N >= a.ylimit) continue;
+      u32x4_t v = *(const u32x4_t*)(ostage + pix * a.orow + pc * 16);
+      const uint32_t off = ((uint32_t)(cb + r * a.N) * (uint32_t)a.O + (uint32_t)ch) * 2u;
+      if (a.residual || a.relu) {
+        const uint16_t* rp = a.residual ? (const uint16_t*)(a.residual + off) : nullptr;
+        const u32x2_t lo2 = post_bf16x4(u32x2_t{v.x, v.y}, rp, 4, true, a.relu);
+        const u32x2_t hi2 = post_bf16x4(u32x2_t{v.z, v.w}, rp ? rp + 4 : nullptr, 4, true, a.relu);
+        v = u32x4_t{lo2.x, lo2.y, hi2.x, hi2.y};
+      }
+      *(u32x4_t*)(a.Y + off) = v;
+    }
+  } else {
+    const int np = a.SG * 4;
+    for (int idx = tid; idx < nopix * np; idx += blockDim.x) {
+      const int pix = (int)fdiv((uint32_t)idx, a.d_np), pc = idx - pix * np;
+      const int col = (int)fdiv((uint32_t)pix, a.d_br), r = pix - col * BR;
+      const int cb = colbase[col], ch = chans[pc];
+      if (cb < 0 || r >= colrows[col] || ch < 0 || cb + r * a.N >= a.ylimit) continue;
+      u32x2_t v = *(const u32x2_t*)(ostage + pix * a.orow + pc * 8);
+      const uint32_t off = ((uint32_t)(cb + r * a.N) * (uint32_t)a.O + (uint32_t)ch) * 2u;
+      if (a.residual || a.relu) {
+        const uint16_t* rp = a.residual ? (const uint16_t*)(a.residual + off) : nullptr;
+        v = post_bf16x4(v, rp, 4, true, a.relu);
+      }
+      *(u32x2_t*)(a.Y + off) = v;
+    }
+  }
+  ROWS_TRACE(5)
+}
+
+int device_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      cus = v;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
+constexpr int kLdsLimit = 160 * 1024;
+
+template <int H, int S, int BR, int NT, bool CW4, int D>
+int launch_inst(const RowsArgs& a, dim3 grid, int threads, size_t ldsb, hipStream_t st) {
+  static bool raised = false;  // dynamic LDS above 64 KB has to be allowed once per kernel
+  if (!raised) {
+    if (hipFuncSetAttribute((const void*)conv_rows<H, S, BR, NT, CW4, D>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit) != hipSuccess)
+      return BSP_ERR_HIP;
+    raised = true;
+  }
+  hipLaunchKernelGGL((conv_rows<H, S, BR, NT, CW4, D>), grid, dim3(threads), ldsb, st, a);
+#ifdef BSP_ROWS_TUNE
+  if (std::getenv("BSP_ROWS_TRACE")) {
+    static long long h[4096 * 16];
+    hipDeviceSynchronize();
+    hipMemcpyFromSymbol(h, HIP_SYMBOL(g_rows_trace), sizeof(h));
+    const int n = std::min<int>(grid.x, 4096);
+    long long t0 = h[0], tend = 0;
+    for (int b = 0; b < n; ++b) { t0 = std::min(t0, h[b * 16]); tend = std::max(tend, h[b * 16 + 5]); }
+    double sum[7] = {0}; double start_sum = 0, start_max = 0, e8 = 0, e9 = 0, e10 = 0;
+    for (int b = 0; b < n; ++b) {
+      for (int k = 1; k < 6; ++k) sum[k] += (double)(h[b * 16 + k] - h[b * 16 + k - 1]);
+      sum[6] += (double)(h[b * 16 + 7] - h[b * 16 + 6]);
+      e8 += (double)(h[b * 16 + 8] - h[b * 16]); e9 += (double)(h[b * 16 + 9] - h[b * 16]); e10 += (double)(h[b * 16 + 10] - h[b * 16]);
+      start_sum += (double)(h[b * 16] - t0); start_max = std::max(start_max, (double)(h[b * 16] - t0));
+    }
+    fprintf(stderr, "  since wg start: cleared %.2f, first slab requested %.2f, ring requested %.2f\n", e8 / n / 100.0, e9 / n / 100.0, e10 / n / 100.0);
+#ifdef BSP_EXP_TWICE
+    {
+      double a1 = 0, a2 = 0, a3 = 0;
+      for (int b = 0; b < n; ++b) { a1 += (double)(h[b*16+12]-h[b*16+11]); a2 += (double)(h[b*16+13]-h[b*16+12]); a3 += (double)(h[b*16+14]-h[b*16+13]); }
+      fprintf(stderr, "  second pass: clear %.2f, request %.2f, land %.2f\n", a1/n/100.0, a2/n/100.0, a3/n/100.0);
+    }
+#endif
+    fprintf(stderr, "trace (us, 100 MHz ticks): kernel span %.2f | wg start avg %.2f max %.2f | stage0 %.2f slab0 %.2f rest %.2f stageout %.2f store %.2f | slab0 shader clock %.0f MHz\n",
+            (tend - t0) / 100.0, start_sum / n / 100.0, start_max / 100.0, sum[1] / n / 100.0, sum[2] / n / 100.0,
+            sum[3] / n / 100.0, sum[4] / n / 100.0, sum[5] / n / 100.0, sum[6] / std::max(1.0, sum[2]) * 100.0);
+  }
+#endif
+  return hipGetLastError() == hipSuccess ? BSP_OK : BSP_ERR_HIP;
+}
+
+template <int H, int S, bool CW4>
+int launch_hs(const RowsArgs& a, int BR, int NT, dim3 grid, int threads, size_t ldsb, hipStream_t st) {
+  constexpr int D = H == 1 ? 8 : (H == 3 ? 4 : 2);
+  if (BR == 7 && NT == 1) return launch_inst<H, S, 7, 1, CW4, D>(a, grid, threads, ldsb, st);
+  if (BR == 4 && NT == 1) return launch_inst<H, S, 4, 1, CW4, D>(a, grid, threads, ldsb, st);
+  if (BR == 4 && NT == 2) return launch_inst<H, S, 4, 2, CW4, D>(a, grid, threads, ldsb, st);
+  return BSP_ERR_UNSUPPORTED;
+}
+
+struct Choice {
+  int BR, NT, TW, NB, NI, SG, PTW, KS;
+  double cost;
+};
+
+struct Geometry {
+  int PR, PC, PCp, lscp, tiles_x, tiles_y, slots, orow;
+  int64_t ntiles, bufbytes, red, body, ldsb;
+};
+
+inline int ceil_log2(int v) {
+  int l = 0;
+  while ((1 << l) < v) ++l;
+  return l;
+}
+
+// Everything that follows from a choice; false when it does not fit.
+bool rows_geometry(const ConvParams& p, int slab, int S, const Choice& c, Geometry* g) {
+  g->slots = c.PTW * c.NT * 16;
+  if (c.NI * c.NB * c.TW > g->slots || c.SG * c.PTW * c.KS > 8) return false;
+  g->PR = (c.NB * c.BR - 1) * S + p.H;
+  if (c.NI * g->PR > 64) return false;  // a wave keeps one staged row per lane
+  g->PC = (c.TW - 1) * S + p.K;
+  g->PCp = (g->PC + 15) & ~15;
+  g->lscp = ceil_log2(slab / 8);
+  if (g->lscp < 2) return false;  // a request covers at most sixteen pixels of a row
+  g->bufbytes = ((int64_t)c.NI * g->PR * g->PCp) << (g->lscp + 4);
+  g->orow = c.SG * 32 + 16;
+  g->red = c.KS > 1 ? (int64_t)(c.KS - 1) * c.PTW * c.SG * c.NT * c.BR * 1024 : 0;
+  const int nslabs = (p.I + slab - 1) / slab;
+  const int64_t patch = nslabs > 1 ? 2 * g->bufbytes : g->bufbytes;
+  g->body = std::max<int64_t>(patch, g->red + (int64_t)g->slots * c.BR * g->orow);
+  g->body = (g->body + 15) & ~15ll;
+  g->ldsb = g->body + (int64_t)g->slots * 12 + c.SG * 16;
+  if (g->ldsb > kLdsLimit) return false;
+  g->tiles_x = (p.N + c.TW - 1) / c.TW;
+  g->tiles_y = ((p.M + c.BR - 1) / c.BR + c.NB - 1) / c.NB;
+  g->ntiles = (int64_t)((p.B + c.NI - 1) / c.NI) * g->tiles_y * g->tiles_x;
+  return true;
+}
+
+}  // namespace
+
+// Tile and role choice.  Cost model (clock cycles, rough): matrix-core time of the busiest
+// SIMD against the time the CU needs to pull in patches and weights, plus fixed costs.
+static bool rows_choose(const ConvParams& p, const int32_t* rs, int S, Choice* best) {
+  const int nstrips = rs[BSP_ROWS_NSTRIPS_W], nslabs = rs[BSP_ROWS_NSLABS_W];
+  const int slab = rs[BSP_ROWS_SLAB_W];
+  const double steps_per_strip = (double)rs[BSP_ROWS_NCS_W] / std::max(1, nstrips);
+  const int cus = device_cus();
+  best->cost = 1e300;
+  for (int BR : {7, 4}) {
+    for (int NT : {1, 2}) {
+      if (BR == 7 && NT == 2) continue;
+      for (int SG : {1, 2, 4, 8}) {
+        if (SG > nstrips && SG != 1) continue;
+        for (int KS : {1, 2, 4}) {
+          for (int PTW : {1, 2, 4, 8}) {
+            const int waves = SG * PTW * KS;
+            if (waves > 8) continue;
+            const int slots = PTW * NT * 16;  // columns a workgroup can hold
+            for (int mode = 0; mode < 3; ++mode) {
+              Choice c{BR, NT, 0, 1, 1, SG, PTW, KS, 0.0};
+              if (mode == 0) {           // whole image rows, several bands
+                c.TW = p.N;
+                if (c.TW > slots) continue;
+                c.NB = std::min(slots / c.TW, (p.M + BR - 1) / BR);
+              } else if (mode == 1) {    // several images, every band of each
+                c.TW = p.N;
+                c.NB = (p.M + BR - 1) / BR;
+                if (c.TW * c.NB > slots) continue;
+                c.NI = std::min(slots / (c.TW * c.NB), p.B);
+                if (c.NI < 2) continue;
+              } else {                   // part of a row
+                if (p.N <= slots) continue;
+                const int parts = (p.N + slots - 1) / slots;
+                c.TW = (p.N + parts - 1) / parts;
+              }
+              Geometry g;
+              if (!rows_geometry(p, slab, S, c, &g)) continue;
+              const int nsg = (nstrips + SG - 1) / SG;
+              const int64_t nwg = g.ntiles * nsg;
+              const double mfma_wave = steps_per_strip * p.H * BR * NT / KS * 16.0;
+              const int wg_per_cu_lds = (int)std::max<int64_t>(1, kLdsLimit / g.ldsb);
+              const int wg_per_cu = std::min(wg_per_cu_lds, std::max(1, 8 / waves));
+              const double conc = (double)cus * wg_per_cu;
+              const double rounds = std::ceil((double)nwg / conc);
+              const double waves_per_simd = std::ceil(waves * wg_per_cu / 4.0);
+              const double t_mfma = rounds * mfma_wave * waves_per_simd;
+              const double t_load = rounds * wg_per_cu * (double)g.bufbytes * nslabs / 48.0;
+              const double wbytes = steps_per_strip * p.H * 1024.0 * SG * PTW;
+              const double t_w = rounds * wg_per_cu * wbytes / 24.0;
+              const double t_mem = t_load + t_w;
+              c.cost = std::max(t_mfma, t_mem) + 0.3 * std::min(t_mfma, t_mem) + 2000.0 + 300.0 * nslabs;
+              if (c.cost < best->cost) *best = c;
+            }
+          }
+        }
+      }
+    }
+  }
+  return best->cost < 1e299;
+}
+
+int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st) {
+  if (dtype != BSP_BF16 || !plan_host) return BSP_ERR_UNSUPPORTED;
+  const int32_t* hdr = (const int32_t*)plan_host;
+  if (hdr[BSP_PLAN_MAGIC_W] != BSP_PLAN_MAGIC || hdr[BSP_PLAN_VERSION_W] != BSP_PLAN_VERSION ||
+      hdr[BSP_PLAN_O_W] != p.O || hdr[BSP_PLAN_I_W] != p.I || hdr[BSP_PLAN_H_W] != p.H ||
+      hdr[BSP_PLAN_K_W] != p.K || hdr[BSP_PLAN_DTYPE_W] != dtype || hdr[BSP_PLAN_OFF_ROWS_W] == 0)
+    return BSP_ERR_UNSUPPORTED;
+  const int32_t* rs = hdr + hdr[BSP_PLAN_OFF_ROWS_W];
+  if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return BSP_ERR_UNSUPPORTED;
+  if (p.H != 1 && p.H != 3) return BSP_ERR_UNSUPPORTED;
+  if ((int64_t)p.B * p.L * p.J * p.I * 2 >= (1ll << 31) || (int64_t)p.P * p.O * 2 >= (1ll << 31))
+    return BSP_ERR_UNSUPPORTED;
+  if (p.P <= 64 && p.H == 1 && p.K == 1) return BSP_ERR_UNSUPPORTED;  // FC layers: streaming kernels
+  const int cw = rs[BSP_ROWS_CW_W];
+  const int slab = rs[BSP_ROWS_SLAB_W];
+  const bool pointwise = p.H == 1 && p.K == 1;
+  const int S = pointwise ? 1 : p.sh;       // staged pixels per output pixel step
+  const int gs = pointwise ? p.sh : 1;      // input pixels per staged pixel
+  ConvParams v = p;                         // the view the tiles are cut from
+  if (pointwise && p.sh == 1 && p.ph == 0 && p.pw == 0) {
+    // a pointwise layer has no geometry: all pixels as rows of sixteen columns
+    const int W = 16;
+    v.B = 1;
+    v.N = v.J = W;
+    v.M = v.L = (p.P + W - 1) / W;
+  }
+  Choice ch;
+  if (!rows_choose(v, rs, S, &ch)) return BSP_ERR_UNSUPPORTED;
+#ifdef BSP_ROWS_TUNE  // experiments only: never defined in the product build
+  if (const char* e = std::getenv("BSP_ROWS_TUNE")) {
+    int q[8];
+    if (sscanf(e, "%d,%d,%d,%d,%d,%d,%d,%d", q, q + 1, q + 2, q + 3, q + 4, q + 5, q + 6, q + 7) == 8)
+      ch = Choice{q[0], q[1], q[2] > 0 ? q[2] : v.N, q[3], q[4], q[5], q[6], q[7], 0.0};
+  }
+  if (std::getenv("BSP_ROWS_VERBOSE"))
+    fprintf(stderr, "rows: M=%d N=%d B=%d I=%d O=%d H=%d s=%d | BR=%d NT=%d TW=%d NB=%d NI=%d SG=%d PTW=%d KS=%d cost=%.0f\n",
+            v.M, v.N, v.B, p.I, p.O, p.H, p.sh, ch.BR, ch.NT, ch.TW, ch.NB, ch.NI, ch.SG, ch.PTW, ch.KS, ch.cost);
+#endif
+  Geometry geo;
+  if (!rows_geometry(v, slab, S, ch, &geo)) return BSP_ERR_UNSUPPORTED;
+
+  RowsArgs a;
+  a.X = (const unsigned char*)p.X;
+  a.Y = (unsigned char*)p.Y;
+  a.bias = p.bias;
+  a.residual = (const unsigned char*)p.residual;
+  a.relu = p.relu;
+  a.rstrip = p.plan + hdr[BSP_PLAN_OFF_ROWS_W] + rs[BSP_ROWS_OFF_STRIP_W];
+  a.rslab = p.plan + hdr[BSP_PLAN_OFF_ROWS_W] + rs[BSP_ROWS_OFF_SLAB_W];
+  a.rdesc = p.plan + hdr[BSP_PLAN_OFF_ROWS_W] + rs[BSP_ROWS_OFF_DESC_W];
+  a.rfrag = (const u32x4_t*)(p.plan + hdr[BSP_PLAN_OFF_ROWS_W] + rs[BSP_ROWS_OFF_FRAG_W]);
+  a.zeros = (const unsigned char*)(p.plan + hdr[BSP_PLAN_OFF_ROWS_W] + BSP_ROWS_ZEROS_W);
+  a.nstrips = rs[BSP_ROWS_NSTRIPS_W];
+  a.nslabs = rs[BSP_ROWS_NSLABS_W];
+  a.ncs = rs[BSP_ROWS_NCS_W];  // 0: an all-zero mask, no step exists anywhere
+  a.sc = slab / 8;
+  a.lscp = geo.lscp;
+  {
+    const int bits = std::min(geo.lscp, 4);  // swizzle: 16 consecutive pixels, 16 distinct bank groups
+    a.swz_shift = 4 - bits;
+    a.swz_mask = (1 << bits) - 1;
+  }
+  a.B = v.B;
+  a.L = v.L;
+  a.J = v.J;
+  a.I = p.I;
+  a.O = p.O;
+  a.M = v.M;
+  a.N = v.N;
+  a.ph = p.ph;
+  a.pw = p.pw;
+  a.stride = p.sh;
+  a.gs = gs;
+  a.TW = ch.TW;
+  a.NB = ch.NB;
+  a.NI = ch.NI;
+  a.PR = geo.PR;
+  a.PC = geo.PC;
+  a.PCp = geo.PCp;
+  a.tiles_x = geo.tiles_x;
+  a.tiles_y = geo.tiles_y;
+  a.ntiles = (int32_t)geo.ntiles;
+  a.ncols = ch.NI * ch.NB * ch.TW;
+  a.SG = ch.SG;
+  a.PTW = ch.PTW;
+  a.KS = ch.KS;
+  a.nsg = (a.nstrips + ch.SG - 1) / ch.SG;
+  a.per_xcd = ((a.ntiles + 7) / 8) * a.nsg;
+  a.bufbytes = (int32_t)geo.bufbytes;
+  a.orow = geo.orow;
+  a.red_bytes = (int32_t)geo.red;
+  a.piece8 = hdr[BSP_PLAN_BO_W] == 4;
+  a.direct = 0;
+#ifdef BSP_ROWS_TUNE
+  if (std::getenv("BSP_ROWS_DIRECT")) a.direct = 1;
+#endif
+  a.tbl_off = (int32_t)geo.body;
+  a.xlimit = p.B * p.L * p.J;
+  a.ylimit = p.P;
+  const int64_t nstage = geo.bufbytes / 16;
+  if (geo.ntiles >= (1 << 24) || nstage >= (1 << 24) || (int64_t)a.per_xcd * 8 >= (1ll << 31))
+    return BSP_ERR_UNSUPPORTED;
+  a.lsg = ceil_log2(ch.SG);
+  a.lptw = ceil_log2(ch.PTW);
+  a.d_nsg = make_fastdiv(a.nsg);
+  a.d_tpi = make_fastdiv(a.tiles_x * a.tiles_y);
+  a.d_tx = make_fastdiv(a.tiles_x);
+  a.d_perimg = make_fastdiv(ch.NB * ch.TW);
+  a.d_tw = make_fastdiv(ch.TW);
+  a.d_pcp = make_fastdiv(a.PCp);
+  a.d_pr = make_fastdiv(a.PR);
+  a.d_np = make_fastdiv(a.piece8 ? ch.SG * 4 : ch.SG * 2);
+  a.d_br = make_fastdiv(ch.BR);
+  // the multiply-high divisions are exact while dividend * divisor < 2^32; staged pixels are
+  // counted up to the next multiple of the workgroup size
+  if ((nstage + 1024) * std::max(a.PCp, a.PR) >= (1ll << 32) ||
+      (int64_t)a.per_xcd * 8 * std::max(a.nsg, a.tiles_x * a.tiles_y) >= (1ll << 32) ||
+      (int64_t)geo.slots * ch.BR * ch.SG * 4 * std::max(ch.SG * 4, ch.BR) >= (1ll << 32))
+    return BSP_ERR_UNSUPPORTED;
+  const int threads = 64 * ch.SG * ch.PTW * ch.KS + 64;  // compute waves + the data mover
+  dim3 grid((unsigned)(a.per_xcd * 8));
+  const size_t ldsb = (size_t)geo.ldsb;
+  if (cw == 4) {
+    if (p.H == 1) return launch_hs<1, 1, true>(a, ch.BR, ch.NT, grid, threads, ldsb, st);
+    return S == 1 ? launch_hs<3, 1, true>(a, ch.BR, ch.NT, grid, threads, ldsb, st)
+                  : launch_hs<3, 2, true>(a, ch.BR, ch.NT, grid, threads, ldsb, st);
+  }
+  if (p.H == 1) return launch_hs<1, 1, false>(a, ch.BR, ch.NT, grid, threads, ldsb, st);
+  return S == 1 ? launch_hs<3, 1, false>(a, ch.BR, ch.NT, grid, threads, ldsb, st)
+                : launch_hs<3, 2, false>(a, ch.BR, ch.NT, grid, threads, ldsb, st);
+}

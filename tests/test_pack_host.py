@@ -23,7 +23,10 @@ def _case(O, I, H, K, bo, bi, seed, kind="bernoulli", d=0.5):
 
 
 def test_header_symbols_exported():
-    text = open(os.path.join(ROOT, "include", "bsp.h")).read()
+    import glob
+    headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
+    assert [os.path.basename(h) for h in headers] == ["bsp.h", "bsp_bench.h"]
+    text = "".join(open(h).read() for h in headers)
     names = set(re.findall(r"\b(bsp_[a-z0-9_]+)\s*\(", text))
     names -= {"bsp_weights"}
     assert {"bsp_pack", "bsp_fc", "bsp_conv2d"} <= names
@@ -121,6 +124,8 @@ def test_error_codes():
     assert lib.bsp_fc(ctypes.byref(w), None, None, 16, 1, None) == -1
     w.O, w.I, w.H, w.K, w.bo, w.bi, w.dtype = 16, 16, 1, 1, 8, 8, 0
     w.plan, w.plan_bytes, w.payload, w.nnzb = 4096, 1024, 4096, 1
+    assert lib.bsp_fc(ctypes.byref(w), 4096, None, 8192, 1, None) == -1    # no host copy of the plan
+    w.plan_host = 4096
     assert lib.bsp_fc(ctypes.byref(w), 4096, None, 8192, -1, None) == -2
     assert lib.bsp_fc(ctypes.byref(w), 4100, None, 8192, 1, None) == -9
     w.bo = 2
