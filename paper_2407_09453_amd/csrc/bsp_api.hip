@@ -77,8 +77,13 @@ int dispatch(const bsp_weights* w, const ConvParams& p, void* stream) {
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
     if (chunked && (allow & BSP_KERNEL_FC)) rc = bsp_launch_fc_stream(p, w->dtype, w->bo, w->bi, st);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
-    // (pointwise layers stay with the LDS-resident kernel until the row-band kernel beats it there)
-    if ((allow & BSP_KERNEL_ROWS) && (p.H > 1 || w->kernels)) rc = bsp_launch_rows(p, w->dtype, w->plan_host, st);
+    // The row-band kernels take the layers they were measured to be faster on (per-shape
+    // timings of the ResNet50-shaped layers): windows with at least 128 input channels, and
+    // pointwise layers with 128..512 input channels, at least 128 output channels and fewer
+    // than 100 000 pixels.  A caller's kernel mask overrides the rule.
+    const bool rows_pick = p.H > 1 ? p.I >= 128
+                                   : (p.I >= 128 && p.I <= 512 && p.O >= 128 && p.P < 100000);
+    if ((allow & BSP_KERNEL_ROWS) && (rows_pick || w->kernels)) rc = bsp_launch_rows(p, w->dtype, w->plan_host, st);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
     if (allow & BSP_KERNEL_LDS) rc = bsp_launch_lds(p, w->dtype, w->plan_host, st);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;

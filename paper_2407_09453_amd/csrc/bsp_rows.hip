@@ -1,23 +1,33 @@
-// Row-band kernel: block-sparse implicit-GEMM convolution for bf16 layers (fp32 accumulation)
+// Row-band kernels: block-sparse implicit-GEMM convolution for bf16 layers (fp32 accumulation)
 // in which one activation fragment, once in registers, serves every window row.
 //
 // Work split.  A workgroup owns a pixel tile (NI images x NB bands of BR output rows x TW
-// output columns) and SG strips of 16 output channels.  The tile's pixels are seen as
+// output columns) and a group of strips of 16 output channels.  The tile's pixels are seen as
 // columns: a column is BR vertically consecutive output pixels, sixteen columns make a
-// lane tile (the N side of a 16x16 MFMA tile).  A wave owns one strip, NT lane tiles and, when
-// the contraction is split (KS > 1), one share of the strip's column steps.
+// lane tile (the N side of a 16x16 MFMA tile).
 //
-// Per slab of input channels the workgroup stages the tile's input patch (halo included,
-// zeros outside the image) in LDS.  A wave then walks its strip's column steps: per step it
-// reads, for each lane tile, the NF = (BR-1)*S + H patch rows of the step's items once, takes
-// the step's H weight fragments (one per window row, streamed from the plan through a ring of
-// registers), and issues H*BR MFMAs per lane tile: output row r, window row dy uses patch row
-// r*S + dy.  So an activation fragment read from LDS feeds up to H MFMAs, and a weight
-// fragment feeds BR*NT.
+// Staging.  Per slab of input channels the tile's input patch (halo included) is copied
+// from global memory straight into LDS (global_load_lds: 64 lanes x 16 bytes per request land
+// as one contiguous KiB); staged pixels outside the image are cleared once and never
+// requested.  A staged pixel occupies a power-of-two number of 16-byte slots, its pieces
+// permuted by the pixel's position (slot = piece ^ f(pixel)) so that the sixteen pixels a
+// lane group reads fall into sixteen different bank groups.
+//
+// conv_rows (windows, or several slabs): a wave owns one strip, NT lane tiles and, when the
+// contraction is split (KS > 1), every KS-th column step.  Per step it reads, for each lane
+// tile, the NF = (BR-1)*S + H patch rows of the step's items once, takes the step's H weight
+// fragments (one per window row, streamed from the plan through a ring of registers), and
+// issues H*BR MFMAs per lane tile: output row r, window row dy uses patch row r*S + dy.  So
+// an activation fragment read from LDS feeds up to H MFMAs and a weight fragment BR*NT.  The
+// last wave of the workgroup only moves data: it requests the next slab while the others
+// compute.
+//
+// conv_rows_pw (pointwise layers whose input channels fit one slab): the patch is staged
+// once and every wave then walks several strips (passes); a strip's few weight fragments
+// sit in registers whole, the next strip's are requested while the current one is computed.
 //
 // Only kept blocks have items (paper Section I, advantages 3-4); a strip groups block rows
-// with similar kept columns (bsp_plan.h).  Results (+ bias, rounded once) are staged in LDS
-// and leave as 16-byte pieces; a residual add and ReLU can be applied on the way out.
+// with similar kept columns (bsp_plan.h).
 #include "bsp_launch.h"
 #include "bsp_tile.h"
 
@@ -36,10 +46,11 @@ struct RowsArgs {
   const int32_t* rslab;
   const int32_t* rdesc;
   const u32x4_t* rfrag;
-  const unsigned char* zeros;      // sixteen zero bytes (in the plan)
   int32_t relu;
   int32_t nstrips, nslabs, ncs;
-  int32_t sc;                      // 16-byte pieces of a staged pixel that hold data (slab / 8)
+  int32_t sc;                      // 16-byte pieces of a pixel per plan slab (slab / 8)
+  int32_t G, nstaged, scs;         // plan slabs staged together, staged slabs, pieces with data (G * sc)
+  int32_t NM;                      // data-mover waves (the last NM of the workgroup)
   int32_t lscp;                    // log2 of the pieces a staged pixel occupies (power of two >= sc)
   int32_t swz_shift, swz_mask;     // piece p of pixel q sits in slot p ^ ((q >> shift) & mask)
   int32_t B, L, J, I, O, M, N;
@@ -48,7 +59,7 @@ struct RowsArgs {
   int32_t TW, NB, NI, PR, PC, PCp; // PC staged columns that are read, PCp the row pitch (multiple of 16)
   int32_t tiles_x, tiles_y, ntiles;
   int32_t ncols;                   // NI * NB * TW
-  int32_t SG, PTW, KS, nsg;
+  int32_t SG, PTW, KS, nsg;        // conv_rows_pw: SG strips per wave (passes), nsg strip ranges
   int32_t per_xcd;                 // workgroups per XCD slot range
   int32_t bufbytes;                // one patch buffer
   int32_t orow;                    // bytes per pixel in the results staging tile
@@ -61,19 +72,10 @@ struct RowsArgs {
   FastDiv d_pcp, d_pr, d_np, d_br, d_nsg, d_tpi, d_tx, d_perimg, d_tw;
 };
 
-#ifdef BSP_ROWS_TUNE  // experiments only: per-workgroup phase timestamps
-__device__ long long g_rows_trace[4096 * 16];
-#define ROWS_TRACE(k)                                                              \
-  if (tid == 0 && blockIdx.x < 4096) {                                             \
-    g_rows_trace[blockIdx.x * 16 + (k)] = (long long)wall_clock64();                \
-    if ((k) == 1 || (k) == 2) g_rows_trace[blockIdx.x * 16 + 6 + (k)-1] = (long long)clock64(); \
-  }
-#else
-#define ROWS_TRACE(k)
-#endif
+struct TilePos {
+  int img0, y0, x0, sgi;
+};
 
-// LDS traffic of the main loop is written out: the compiler cannot see through the
-// global->LDS copies and would otherwise wait for all of them before every LDS read.
 template <int H, int S, int BR>
 constexpr bool row_needed(int fr) {
   for (int r = 0; r < BR; ++r)
@@ -82,39 +84,35 @@ constexpr bool row_needed(int fr) {
   return false;
 }
 
-template <int H, int S, int BR, int NT, bool CW4, int D>
-__global__ __launch_bounds__(576) void conv_rows(RowsArgs a) {
-  constexpr int NF = (BR - 1) * S + H;
-  extern __shared__ __align__(16) unsigned char lds[];
-  const int tid = threadIdx.x;
-  const int nthreads = blockDim.x - 64;  // compute threads; the last wave moves data
-  const int wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
-
-  // workgroup -> (tile, strip group): consecutive workgroups of one XCD share a tile
+// workgroup -> (tile, strip group): consecutive workgroups of one XCD share a tile
+__device__ __forceinline__ bool rows_tile(const RowsArgs& a, int BR, TilePos* t) {
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  if (slot >= a.per_xcd) return;
+  if (slot >= a.per_xcd) return false;
   const int q = xcd * a.per_xcd + slot;
-  const int tile = (int)fdiv((uint32_t)q, a.d_nsg), sgi = q - tile * a.nsg;
-  if (tile >= a.ntiles) return;
+  const int tile = (int)fdiv((uint32_t)q, a.d_nsg);
+  if (tile >= a.ntiles) return false;
+  t->sgi = q - tile * a.nsg;
   const int tpi = a.tiles_x * a.tiles_y;
   const int ig = (int)fdiv((uint32_t)tile, a.d_tpi), trem = tile - ig * tpi;
   const int ty = (int)fdiv((uint32_t)trem, a.d_tx), tx = trem - ty * a.tiles_x;
-  const int img0 = ig * a.NI, y0 = ty * a.NB * BR, x0 = tx * a.TW;
+  t->img0 = ig * a.NI;
+  t->y0 = ty * a.NB * BR;
+  t->x0 = tx * a.TW;
+  return true;
+}
 
-  ROWS_TRACE(0)
-  int32_t* colbase = (int32_t*)(lds + a.tbl_off);
-  const int nslots = a.PTW * NT * 16;
-  int32_t* colrows = colbase + nslots;
-  int32_t* colpix = colrows + nslots;
-  int32_t* chans = colpix + nslots;
+// Per column of the tile: first output pixel (or -1), rows that exist, first staged pixel.
+__device__ __forceinline__ void rows_tables(const RowsArgs& a, const TilePos& t, int BR, int S, int nslots,
+                                            int32_t* colbase, int32_t* colrows, int32_t* colpix) {
+  const int tid = threadIdx.x;
   if (tid < nslots) {
     int cb = -1, rows = 0, lp = 0;
     if (tid < a.ncols) {
       const int per_img = a.NB * a.TW;
       const int img = (int)fdiv((uint32_t)tid, a.d_perimg), rem = tid - img * per_img;
       const int band = (int)fdiv((uint32_t)rem, a.d_tw), x = rem - band * a.TW;
-      lp = (img * a.PR + band * BR * S) * a.PCp + x * S;   // first staged pixel of the column
-      const int gi = img0 + img, gy = y0 + band * BR, gx = x0 + x;
+      lp = (img * a.PR + band * BR * S) * a.PCp + x * S;
+      const int gi = t.img0 + img, gy = t.y0 + band * BR, gx = t.x0 + x;
       if (gi < a.B && gx < a.N && gy < a.M) {
         cb = (gi * a.M + gy) * a.N + gx;
         rows = min(BR, a.M - gy);
@@ -124,8 +122,140 @@ __global__ __launch_bounds__(576) void conv_rows(RowsArgs a) {
     colrows[tid] = rows;
     colpix[tid] = lp;
   }
+}
+
+// Clear the staged pixels that lie outside the image, in every patch buffer.
+__device__ __forceinline__ void rows_clear_outside(const RowsArgs& a, const TilePos& t, unsigned char* lds) {
+  const int iy0 = t.y0 * a.stride - a.ph, ix0 = t.x0 * a.stride - a.pw;
+  const int npixels = a.NI * a.PR * a.PCp;
+  for (int pix = threadIdx.x; pix < npixels; pix += blockDim.x) {
+    const int row = (int)fdiv((uint32_t)pix, a.d_pcp), pc = pix - row * a.PCp;
+    const int img = (int)fdiv((uint32_t)row, a.d_pr), pr = row - img * a.PR;
+    const int gi = t.img0 + img, gy = iy0 + pr * a.gs, gx = ix0 + pc * a.gs;
+    const bool inside = gi < a.B && (unsigned)gy < (unsigned)a.L && (unsigned)gx < (unsigned)a.J &&
+                        (gi * a.L + gy) * a.J + gx < a.xlimit;
+    if (!inside && pc < a.PC) {
+      u32x4_t* p0 = (u32x4_t*)(lds + ((size_t)pix << (a.lscp + 4)));
+      for (int k = 0; k < (1 << a.lscp); ++k) {
+        p0[k] = u32x4_t{0, 0, 0, 0};
+        if (a.nstaged > 1) p0[k + (a.bufbytes >> 4)] = u32x4_t{0, 0, 0, 0};
+      }
+    }
+  }
+}
+
+// Request staged slab sl (G plan slabs) of the tile's patch: wave w of nw takes every nw-th staged row.  Nothing
+// waits here; the copies complete in the background (vmcnt of the requesting wave).
+__device__ __forceinline__ void rows_stage(const RowsArgs& a, const TilePos& t, unsigned char* lds, int sl,
+                                           int w, int nw) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
+  const uint32_t buf = lds0 + (sl & 1) * a.bufbytes;
+  const int lppi = 6 - a.lscp;          // log2 of the pixels one request covers
+  const int sub_pix = lane >> a.lscp;   // this lane's pixel within the request
+  const int sidx = lane & ((1 << a.lscp) - 1);  // and its slot within the pixel
+  const int iy0 = t.y0 * a.stride - a.ph, ix0 = t.x0 * a.stride - a.pw;
+  const int groups = a.PCp >> lppi;     // requests per staged row
+  const int nrows = a.NI * a.PR;
+  // lane j: the j-th staged row of this wave, where it starts in X (or all ones: outside)
+  uint32_t rowsrc = 0xFFFFFFFFu;
+  const int myrow = w + lane * nw;
+  if (myrow < nrows) {
+    const int img = (int)fdiv((uint32_t)myrow, a.d_pr), pr = myrow - img * a.PR;
+    const int gi = t.img0 + img, gy = iy0 + pr * a.gs;
+    if (gi < a.B && (unsigned)gy < (unsigned)a.L) rowsrc = (uint32_t)((gi * a.L + gy) * a.J) * (uint32_t)a.I * 2u;
+  }
+  const int nrw = (nrows - w + nw - 1) / nw;
+  for (int gq = 0; gq < groups; ++gq) {
+    const int pc = (gq << lppi) + sub_pix;               // staged column of this lane
+    const int cq = sidx ^ ((pc >> a.swz_shift) & a.swz_mask);
+    const int gx = ix0 + pc * a.gs;
+    const int ch = (sl * a.scs + cq) * 8;
+    const bool col_real = cq < a.scs && ch < a.I && pc < a.PC && (unsigned)gx < (unsigned)a.J;
+    const uint32_t col_off = ((uint32_t)gx * (uint32_t)a.I + (uint32_t)ch) * 2u;
+    const uint32_t col_end = (uint32_t)(a.xlimit - gx) * (uint32_t)a.I * 2u;  // rows starting below this exist
+    for (int j = 0; j < nrw; ++j) {
+      const uint32_t src = __builtin_amdgcn_readlane(rowsrc, j);
+      if (src == 0xFFFFFFFFu) continue;
+      const uint32_t dst = buf + ((uint32_t)((w + j * nw) * a.PCp + (gq << lppi)) << (a.lscp + 4));
+      if (col_real && src < col_end)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.X + (src + col_off)),
+                                         (__attribute__((address_space(3))) void*)(uintptr_t)dst, 16, 0, 0);
+    }
+  }
+}
+
+// The patch rows one column step needs, for one lane tile: f[fr] for the needed fr.
+template <int H, int S, int BR, bool CW4>
+__device__ __forceinline__ void rows_read(const RowsArgs& a, const unsigned char* buf, uint32_t desc, int pixb,
+                                          int rowbytes, uint32_t uoff, u32x4_t (&f)[(BR - 1) * S + H]) {
+  constexpr int NF = (BR - 1) * S + H;
+  if (CW4) {
+    uint32_t ad[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t it = (desc >> (16 * h)) & 0xFFFFu;
+      const uint32_t unit = (it & 0xFFu) + 2u * uoff, pj = (uint32_t)pixb + (it >> 8);
+      ad[h] = (((pj << a.lscp) + ((unit >> 1) ^ ((pj >> a.swz_shift) & a.swz_mask))) << 4) + ((unit & 1u) << 3);
+    }
+#pragma unroll
+    for (int fr = 0; fr < NF; ++fr) {
+      if (!row_needed<H, S, BR>(fr)) continue;
+      const u32x2_t p0 = *(const u32x2_t*)(buf + ad[0] + fr * rowbytes);
+      const u32x2_t p1 = *(const u32x2_t*)(buf + ad[1] + fr * rowbytes);
+      f[fr] = u32x4_t{p0.x, p0.y, p1.x, p1.y};
+    }
+  } else {
+    const uint32_t unit = (desc & 0xFFu) + uoff, pj = (uint32_t)pixb + ((desc >> 8) & 0xFFu);
+    const uint32_t ad = ((pj << a.lscp) + (unit ^ ((pj >> a.swz_shift) & a.swz_mask))) << 4;
+#pragma unroll
+    for (int fr = 0; fr < NF; ++fr) {
+      if (!row_needed<H, S, BR>(fr)) continue;
+      f[fr] = *(const u32x4_t*)(buf + ad + fr * rowbytes);
+    }
+  }
+}
+
+// One lane tile's results straight from the accumulators: 8 bytes (four channels of one
+// pixel) per lane; bias, one rounding, optional residual add and ReLU.
+template <int BR>
+__device__ __forceinline__ void rows_store_direct(const RowsArgs& a, const f32x4_t (&acc)[BR], int ch, int cb,
+                                                  int rows, bool add_bias) {
+  if (ch < 0 || cb < 0) return;
+  f32x4_t bv = {0.f, 0.f, 0.f, 0.f};
+  if (add_bias && a.bias) bv = f32x4_t{a.bias[ch], a.bias[ch + 1], a.bias[ch + 2], a.bias[ch + 3]};
+#pragma unroll
+  for (int r = 0; r < BR; ++r) {
+    if (r >= rows || cb + r * a.N >= a.ylimit) continue;
+    const f32x4_t v = acc[r] + bv;
+    u32x2_t o;
+    o.x = pack_bf16x2(v.x, v.y);
+    o.y = pack_bf16x2(v.z, v.w);
+    const uint32_t off = ((uint32_t)(cb + r * a.N) * (uint32_t)a.O + (uint32_t)ch) * 2u;
+    if (a.residual || a.relu)
+      o = post_bf16x4(o, a.residual ? (const uint16_t*)(a.residual + off) : nullptr, 4, true, a.relu);
+    *(u32x2_t*)(a.Y + off) = o;
+  }
+}
+
+template <int H, int S, int BR, int NT, bool CW4, int D>
+__global__ __launch_bounds__(640) void conv_rows(RowsArgs a) {
+  constexpr int NF = (BR - 1) * S + H;
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int tid = threadIdx.x;
+  const int nthreads = blockDim.x - 64 * a.NM;  // compute threads; the last NM waves move data
+  const int wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  TilePos tp;
+  if (!rows_tile(a, BR, &tp)) return;
+
+  int32_t* colbase = (int32_t*)(lds + a.tbl_off);
+  const int nslots = a.PTW * NT * 16;
+  int32_t* colrows = colbase + nslots;
+  int32_t* colpix = colrows + nslots;
+  int32_t* chans = colpix + nslots;
+  rows_tables(a, tp, BR, S, nslots, colbase, colrows, colpix);
   if (tid < a.SG * 4) {
-    const int st = sgi * a.SG + (tid >> 2);
+    const int st = tp.sgi * a.SG + (tid >> 2);
     chans[tid] = st < a.nstrips ? a.rstrip[st * 4 + (tid & 3)] : -1;
   }
 
@@ -134,7 +264,7 @@ __global__ __launch_bounds__(576) void conv_rows(RowsArgs a) {
   // SG and PTW are powers of two
   const int sl_local = wave_u & (a.SG - 1), sub = wave_u >> a.lsg;
   const int pt = sub & (a.PTW - 1), ks = mover ? -1 : sub >> a.lptw;
-  const int strip = sgi * a.SG + sl_local;
+  const int strip = tp.sgi * a.SG + sl_local;
   const bool active = !mover && strip < a.nstrips && a.ncs > 0;
 
   f32x4_t acc[NT][BR];
@@ -144,83 +274,21 @@ __global__ __launch_bounds__(576) void conv_rows(RowsArgs a) {
     for (int r = 0; r < BR; ++r) acc[j][r] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const int rowbytes = a.PCp << (a.lscp + 4);
-
-  // ---- staging.  Every piece of a slab's patch goes from global memory straight into LDS:
-  // 64 lanes x 16 bytes per request land as one contiguous KiB, so lane l of a request owns
-  // slot base + l and asks for whichever piece belongs there.  Staged pixels outside the
-  // image are cleared once in both buffers and never requested, so they stay zero for every
-  // slab.  stage(sl, w, nw): wave w of nw takes every nw-th staged row.
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
-  const int lppi = 6 - a.lscp;          // log2 of the pixels one request covers
-  const int sub_pix = lane >> a.lscp;   // this lane's pixel within the request
-  const int sidx = lane & ((1 << a.lscp) - 1);  // and its slot within the pixel
-  const int iy0 = y0 * a.stride - a.ph, ix0 = x0 * a.stride - a.pw;
-  const int groups = a.PCp >> lppi;     // requests per staged row
-  const int nrows = a.NI * a.PR;
-  auto stage = [&](int sl, int w, int nw) {
-    const uint32_t buf = lds0 + (sl & 1) * a.bufbytes;
-    // lane j: the j-th staged row of this wave, where it starts in X (or all ones: outside)
-    uint32_t rowsrc = 0xFFFFFFFFu;
-    const int myrow = w + lane * nw;
-    if (myrow < nrows) {
-      const int img = (int)fdiv((uint32_t)myrow, a.d_pr), pr = myrow - img * a.PR;
-      const int gi = img0 + img, gy = iy0 + pr * a.gs;
-      if (gi < a.B && (unsigned)gy < (unsigned)a.L) rowsrc = (uint32_t)((gi * a.L + gy) * a.J) * (uint32_t)a.I * 2u;
-    }
-    const int nrw = (nrows - w + nw - 1) / nw;
-    for (int gq = 0; gq < groups; ++gq) {
-      const int pc = (gq << lppi) + sub_pix;               // staged column of this lane
-      const int cq = sidx ^ ((pc >> a.swz_shift) & a.swz_mask);
-      const int gx = ix0 + pc * a.gs;
-      const int ch = (sl * a.sc + cq) * 8;
-      const bool col_real = cq < a.sc && ch < a.I && pc < a.PC && (unsigned)gx < (unsigned)a.J;
-      const uint32_t col_off = ((uint32_t)gx * (uint32_t)a.I + (uint32_t)ch) * 2u;
-      const uint32_t col_end = (uint32_t)(a.xlimit - gx) * (uint32_t)a.I * 2u;  // rows starting below this exist
-      for (int j = 0; j < nrw; ++j) {
-        const uint32_t src = __builtin_amdgcn_readlane(rowsrc, j);
-        if (src == 0xFFFFFFFFu) continue;
-        const uint32_t dst = buf + ((uint32_t)((w + j * nw) * a.PCp + (gq << lppi)) << (a.lscp + 4));
-        if (col_real && src < col_end)
-          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.X + (src + col_off)),
-                                           (__attribute__((address_space(3))) void*)(uintptr_t)dst, 16, 0, 0);
-      }
-    }
-  };
-  {
-    // clear the staged pixels that lie outside the image (both buffers), then, all waves
-    // together, request the first slab
-    const int npixels = nrows * a.PCp;
-    for (int pix = tid; pix < npixels; pix += blockDim.x) {
-      const int row = (int)fdiv((uint32_t)pix, a.d_pcp), pc = pix - row * a.PCp;
-      const int img = (int)fdiv((uint32_t)row, a.d_pr), pr = row - img * a.PR;
-      const int gi = img0 + img, gy = iy0 + pr * a.gs, gx = ix0 + pc * a.gs;
-      const bool inside = gi < a.B && (unsigned)gy < (unsigned)a.L && (unsigned)gx < (unsigned)a.J &&
-                          (gi * a.L + gy) * a.J + gx < a.xlimit;
-      if (!inside && pc < a.PC) {
-        u32x4_t* p0 = (u32x4_t*)(lds + ((size_t)pix << (a.lscp + 4)));
-        for (int k = 0; k < (1 << a.lscp); ++k) {
-          p0[k] = u32x4_t{0, 0, 0, 0};
-          if (a.nslabs > 1) p0[k + (a.bufbytes >> 4)] = u32x4_t{0, 0, 0, 0};
-        }
-      }
-    }
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    ROWS_TRACE(8)
-    stage(0, wave_u, (int)(blockDim.x >> 6));
-    ROWS_TRACE(9)
-  }
+  rows_clear_outside(a, tp, lds);
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  rows_stage(a, tp, lds, 0, wave_u, (int)(blockDim.x >> 6));  // the first slab: all waves together
 
   if (mover) {
-    // ---- the data mover requests the next slab while the compute waves work on the current
-    // one; the barrier at the end of a slab tells them it has landed and tells the mover that
-    // the other buffer is free.
+    // ---- the data movers request the next staged slab while the compute waves work on the
+    // current one; the barrier at the end of a slab tells them it has landed and tells the
+    // movers that the other buffer is free.
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();                  // the first slab is in LDS
-    for (int sl = 1; sl < a.nslabs; ++sl) {
-      stage(sl, 0, 1);
+    for (int ss = 1; ss < a.nstaged; ++ss) {
+      rows_stage(a, tp, lds, ss, wave_u - (nthreads >> 6), a.NM);
       __builtin_amdgcn_s_waitcnt(0);  // everything requested so far is in LDS
-      __syncthreads();                // slab sl - 1 is done everywhere
+      __syncthreads();                // slab ss - 1 is done everywhere
     }
     __syncthreads();                  // the last slab is done
   } else {
@@ -244,11 +312,7 @@ __global__ __launch_bounds__(576) void conv_rows(RowsArgs a) {
     // holds again: every pass through the unrolled loop below then issues the same loads,
     // whatever the step count, which lets the compiler wait for exactly the slot it needs.
     auto fetch = [&](int d, bool advance) {
-#ifdef BSP_EXP_NOW
-      const int cs = advance ? s_first : at[d];
-#else
       const int cs = advance ? max(0, min(fnext, s_end - 1)) : at[d];  // past the end: a valid step, never used
-#endif
       fnext += advance ? a.KS : 0;
       at[d] = cs;
       dr[d] = *(const int*)(descb + ((uint32_t)cs * 16u + desc_lane));
@@ -263,17 +327,18 @@ __global__ __launch_bounds__(576) void conv_rows(RowsArgs a) {
         fetch(d, true);
       }
     }
-    ROWS_TRACE(10)
     __builtin_amdgcn_s_waitcnt(0);  // this wave's share of the first patch has landed
     __syncthreads();                // the first slab's patch and the tables are in LDS
-    ROWS_TRACE(1)
     int pixb[NT];
 #pragma unroll
     for (int j = 0; j < NT; ++j) pixb[j] = colpix[(pt * NT + j) * 16 + c];
 
-    for (int sl = 0; sl < a.nslabs; ++sl) {
-      if (active) {
-        const unsigned char* buf = lds + (sl & 1) * a.bufbytes;
+    for (int ss = 0; ss < a.nstaged; ++ss) {
+      for (int k = 0; k < a.G && active; ++k) {
+        const int sl = ss * a.G + k;
+        if (sl >= a.nslabs) break;
+        const unsigned char* buf = lds + (ss & 1) * a.bufbytes;
+        const uint32_t uoff = (uint32_t)(k * a.sc);  // where this plan slab's pieces start in a staged pixel
         int lo = __builtin_amdgcn_readlane(vr, sl);
         const int hi = __builtin_amdgcn_readlane(vr, sl + 1);
         lo += (ks - lo) & ksm;  // this wave's first step of the slab
@@ -284,54 +349,15 @@ __global__ __launch_bounds__(576) void conv_rows(RowsArgs a) {
             const bool use = cs0 + d * a.KS < hi;
             if (use) {
               u32x4_t f[NT][NF];
-              const uint32_t desc = (uint32_t)dr[d];
 #pragma unroll
-              for (int j = 0; j < NT; ++j) {
-                if (CW4) {
-                  uint32_t ad[2];
-#pragma unroll
-                  for (int h = 0; h < 2; ++h) {
-                    const uint32_t it = (desc >> (16 * h)) & 0xFFFFu;
-                    const uint32_t unit = it & 0xFFu, pj = (uint32_t)pixb[j] + (it >> 8);
-                    ad[h] = (((pj << a.lscp) + ((unit >> 1) ^ ((pj >> a.swz_shift) & a.swz_mask))) << 4) +
-                            ((unit & 1u) << 3);
-                  }
-#pragma unroll
-                  for (int fr = 0; fr < NF; ++fr) {
-                    if (!row_needed<H, S, BR>(fr)) continue;
-                    const u32x2_t p0 = *(const u32x2_t*)(buf + ad[0] + fr * rowbytes);
-                    const u32x2_t p1 = *(const u32x2_t*)(buf + ad[1] + fr * rowbytes);
-                    f[j][fr] = u32x4_t{p0.x, p0.y, p1.x, p1.y};
-                  }
-                } else {
-                  const uint32_t unit = desc & 0xFFu, pj = (uint32_t)pixb[j] + ((desc >> 8) & 0xFFu);
-#ifdef BSP_EXP_NOLDS
-                  const uint32_t ad = (uint32_t)lane * 16u + (unit & 0u) + (pj & 0u);
-#else
-                  const uint32_t ad = ((pj << a.lscp) + (unit ^ ((pj >> a.swz_shift) & a.swz_mask))) << 4;
-#endif
-#pragma unroll
-                  for (int fr = 0; fr < NF; ++fr) {
-                    if (!row_needed<H, S, BR>(fr)) continue;
-#ifdef BSP_EXP_NOLDS
-                    f[j][fr] = *(const u32x4_t*)(buf + ad + fr * 1024);
-#else
-                    f[j][fr] = *(const u32x4_t*)(buf + ad + fr * rowbytes);
-#endif
-                  }
-                }
-              }
+              for (int j = 0; j < NT; ++j) rows_read<H, S, BR, CW4>(a, buf, (uint32_t)dr[d], pixb[j], rowbytes, uoff, f[j]);
 #pragma unroll
               for (int dy = 0; dy < H; ++dy)
 #pragma unroll
                 for (int j = 0; j < NT; ++j)
 #pragma unroll
                   for (int r = 0; r < BR; ++r)
-#ifdef BSP_EXP_NOMFMA
-                    acc[j][r] = acc[j][r] + __builtin_bit_cast(f32x4_t, wr[d][dy] ^ f[j][r * S + dy]);
-#else
                     acc[j][r] = mfma_bf16_16x16x32(wr[d][dy], f[j][r * S + dy], acc[j][r]);
-#endif
             }
             // refill the slot only now, in place: requested earlier, the new fragments would
             // need registers of their own and be copied over once the MFMAs have read the old
@@ -362,13 +388,11 @@ __global__ __launch_bounds__(576) void conv_rows(RowsArgs a) {
           for (int dy = 0; dy < H; ++dy) wr[D - 1][dy] = t[dy];
         }
       }
-      if (sl == 0) { ROWS_TRACE(2) }
       __syncthreads();  // this slab is done everywhere and the next one has landed
     }
   }
 
-  // ---- results: optional sum over the contraction shares, bias, one rounding, staging
-  ROWS_TRACE(3)
+  // ---- results: optional sum over the contraction shares, then out
   unsigned char* red = lds;
   unsigned char* ostage = lds + a.red_bytes;
   if (a.KS > 1) {
@@ -393,34 +417,17 @@ __global__ __launch_bounds__(576) void conv_rows(RowsArgs a) {
     }
   }
   if (a.direct) {
-    // results straight from the accumulators: 8 bytes (four channels of one pixel) per lane
     if (!mover && ks == 0 && strip < a.nstrips) {
       const int ch = chans[sl_local * 4 + g];
-      if (ch >= 0) {
-        f32x4_t bv = {0.f, 0.f, 0.f, 0.f};
-        if (a.bias) bv = f32x4_t{a.bias[ch], a.bias[ch + 1], a.bias[ch + 2], a.bias[ch + 3]};
 #pragma unroll
-        for (int j = 0; j < NT; ++j) {
-          const int col = (pt * NT + j) * 16 + c;
-          const int cb = colbase[col], rows = colrows[col];
-          if (cb < 0) continue;
-#pragma unroll
-          for (int r = 0; r < BR; ++r) {
-            if (r >= rows || cb + r * a.N >= a.ylimit) continue;
-            const f32x4_t v = acc[j][r] + bv;
-            u32x2_t o;
-            o.x = pack_bf16x2(v.x, v.y);
-            o.y = pack_bf16x2(v.z, v.w);
-            const uint32_t off = ((uint32_t)(cb + r * a.N) * (uint32_t)a.O + (uint32_t)ch) * 2u;
-            if (a.residual || a.relu)
-              o = post_bf16x4(o, a.residual ? (const uint16_t*)(a.residual + off) : nullptr, 4, true, a.relu);
-            *(u32x2_t*)(a.Y + off) = o;
-          }
-        }
+      for (int j = 0; j < NT; ++j) {
+        const int col = (pt * NT + j) * 16 + c;
+        rows_store_direct<BR>(a, acc[j], ch, colbase[col], colrows[col], true);
       }
     }
     return;
   }
+  // through an LDS staging tile, leaving as whole 16-byte (4x16 blocks: 8-byte) pieces
   if (!mover && ks == 0 && strip < a.nstrips) {
     const int ch = chans[sl_local * 4 + g];
     if (ch >= 0) {
@@ -440,7 +447,6 @@ __global__ __launch_bounds__(576) void conv_rows(RowsArgs a) {
     }
   }
   __syncthreads();
-  ROWS_TRACE(4)
   const int nopix = nslots * BR;
   if (!a.piece8) {
     const int np = a.SG * 2;
@@ -475,7 +481,111 @@ __global__ __launch_bounds__(576) void conv_rows(RowsArgs a) {
       *(u32x2_t*)(a.Y + off) = v;
     }
   }
-  ROWS_TRACE(5)
+}
+
+// Pointwise layers whose input channels fit one slab.  No data mover: every wave helps stage
+// the one patch, then walks its SG strips.  A strip has at most MAXS column steps; their
+// weight fragments (and the next strip's) sit in registers.
+template <int BR, bool CW4, int MAXS>
+__global__ __launch_bounds__(512) void conv_rows_pw(RowsArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  TilePos tp;
+  if (!rows_tile(a, BR, &tp)) return;
+  int32_t* colbase = (int32_t*)(lds + a.tbl_off);
+  const int nslots = a.PTW * 16;
+  int32_t* colrows = colbase + nslots;
+  int32_t* colpix = colrows + nslots;
+  rows_tables(a, tp, BR, 1, nslots, colbase, colrows, colpix);
+  rows_clear_outside(a, tp, lds);
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int nwaves = (int)(blockDim.x >> 6);
+  rows_stage(a, tp, lds, 0, wave_u, nwaves);
+
+  // waves: pt = lane tile, the others split the strip range; wave (pt, q) walks strips
+  // first + q * SG .. + SG - 1
+  const int pt = wave_u & (a.PTW - 1), q = wave_u >> a.lptw;
+  const int first = (tp.sgi * (nwaves >> a.lptw) + q) * a.SG;
+  const int last = min(first + a.SG, a.nstrips);
+  const uint32_t frag_lane = (uint32_t)lane * 16u, desc_lane = (uint32_t)g * 4u;
+  const unsigned char* fragb = (const unsigned char*)a.rfrag;
+  const unsigned char* descb = (const unsigned char*)a.rdesc;
+  u32x4_t ws[2][MAXS];
+  int ds[2][MAXS];
+  int nst[2] = {0, 0};
+  // per-strip numbers are fetched once, up front: lane i holds the step range of the wave's
+  // i-th strip (and lane 4 i + g the first channel of its lane group g), so that no pass
+  // waits for a load before it can ask for the next strip's weights
+  int v_lo = 0, v_hi = 0, v_ch = -1;
+  if (first + lane < last) {
+    v_lo = a.rslab[(first + lane) * 2];
+    v_hi = a.rslab[(first + lane) * 2 + 1];
+  }
+  if (first + (lane >> 2) < last && (lane >> 2) < a.SG) v_ch = a.rstrip[(first + (lane >> 2)) * 4 + (lane & 3)];
+  // all MAXS slots are always requested (steps the strip does not have repeat its last one,
+  // which the cache absorbs): the same loads on every path let the compiler wait for one set
+  // while the other is still arriving
+  auto request = [&](int set, int i_strip) {
+    const int lo = __builtin_amdgcn_readlane(v_lo, i_strip & 63), hi = __builtin_amdgcn_readlane(v_hi, i_strip & 63);
+    nst[set] = hi - lo;
+#pragma unroll
+    for (int i = 0; i < MAXS; ++i) {
+      const int cs = max(0, min(lo + i, hi - 1));
+      ds[set][i] = *(const int*)(descb + ((uint32_t)cs * 16u + desc_lane));
+      ws[set][i] = *(const u32x4_t*)(fragb + ((uint32_t)cs * 1024u + frag_lane));
+    }
+  };
+  const bool any = first < last && a.ncs > 0;
+  if (any) request(0, 0);
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();  // the patch and the tables are in LDS
+  if (!any) return;
+  const int col = pt * 16 + c;
+  const int pixb = colpix[col], cb = colbase[col], rows = colrows[col];
+  const int rowbytes = a.PCp << (a.lscp + 4);
+
+  auto pass = [&](int cur, int i_strip) {
+#ifndef BSP_EXP_NOREQ
+    request(cur ^ 1, i_strip + 1);  // past the last strip lanes hold 0: a valid step, never used
+#endif
+    // this lane group's first channel: four lanes per strip in v_ch
+    int ch = __builtin_amdgcn_readlane(v_ch, (i_strip * 4) & 63);
+    ch = g == 1 ? __builtin_amdgcn_readlane(v_ch, (i_strip * 4 + 1) & 63) : ch;
+    ch = g == 2 ? __builtin_amdgcn_readlane(v_ch, (i_strip * 4 + 2) & 63) : ch;
+    ch = g == 3 ? __builtin_amdgcn_readlane(v_ch, (i_strip * 4 + 3) & 63) : ch;
+    f32x4_t bv = {0.f, 0.f, 0.f, 0.f};
+    if (a.bias && ch >= 0) bv = f32x4_t{a.bias[ch], a.bias[ch + 1], a.bias[ch + 2], a.bias[ch + 3]};
+    f32x4_t acc[BR];
+#pragma unroll
+    for (int r = 0; r < BR; ++r) acc[r] = bv;
+    const int n = nst[cur];
+#pragma unroll
+    for (int i = 0; i < MAXS; ++i) {
+      if (i < n) {
+        u32x4_t f[BR];
+#ifdef BSP_EXP_NOLDS
+#pragma unroll
+        for (int r = 0; r < BR; ++r) f[r] = ws[cur][(i + 1) % MAXS];
+#else
+        rows_read<1, 1, BR, CW4>(a, lds, (uint32_t)ds[cur][i], pixb, rowbytes, 0u, f);
+#endif
+#pragma unroll
+        for (int r = 0; r < BR; ++r) acc[r] = mfma_bf16_16x16x32(ws[cur][i], f[r], acc[r]);
+      }
+    }
+#ifdef BSP_EXP_NOSTORE
+    if (acc[0].x == 123.f) rows_store_direct<BR>(a, acc, ch, cb, rows, false);
+#else
+    rows_store_direct<BR>(a, acc, ch, cb, rows, false);
+#endif
+  };
+  const int npass = last - first;
+  for (int i = 0; i < npass; i += 2) {
+    pass(0, i);
+    if (i + 1 < npass) pass(1, i + 1);
+  }
 }
 
 int device_cus() {
@@ -503,34 +613,6 @@ int launch_inst(const RowsArgs& a, dim3 grid, int threads, size_t ldsb, hipStrea
     raised = true;
   }
   hipLaunchKernelGGL((conv_rows<H, S, BR, NT, CW4, D>), grid, dim3(threads), ldsb, st, a);
-#ifdef BSP_ROWS_TUNE
-  if (std::getenv("BSP_ROWS_TRACE")) {
-    static long long h[4096 * 16];
-    hipDeviceSynchronize();
-    hipMemcpyFromSymbol(h, HIP_SYMBOL(g_rows_trace), sizeof(h));
-    const int n = std::min<int>(grid.x, 4096);
-    long long t0 = h[0], tend = 0;
-    for (int b = 0; b < n; ++b) { t0 = std::min(t0, h[b * 16]); tend = std::max(tend, h[b * 16 + 5]); }
-    double sum[7] = {0}; double start_sum = 0, start_max = 0, e8 = 0, e9 = 0, e10 = 0;
-    for (int b = 0; b < n; ++b) {
-      for (int k = 1; k < 6; ++k) sum[k] += (double)(h[b * 16 + k] - h[b * 16 + k - 1]);
-      sum[6] += (double)(h[b * 16 + 7] - h[b * 16 + 6]);
-      e8 += (double)(h[b * 16 + 8] - h[b * 16]); e9 += (double)(h[b * 16 + 9] - h[b * 16]); e10 += (double)(h[b * 16 + 10] - h[b * 16]);
-      start_sum += (double)(h[b * 16] - t0); start_max = std::max(start_max, (double)(h[b * 16] - t0));
-    }
-    fprintf(stderr, "  since wg start: cleared %.2f, first slab requested %.2f, ring requested %.2f\n", e8 / n / 100.0, e9 / n / 100.0, e10 / n / 100.0);
-#ifdef BSP_EXP_TWICE
-    {
-      double a1 = 0, a2 = 0, a3 = 0;
-      for (int b = 0; b < n; ++b) { a1 += (double)(h[b*16+12]-h[b*16+11]); a2 += (double)(h[b*16+13]-h[b*16+12]); a3 += (double)(h[b*16+14]-h[b*16+13]); }
-      fprintf(stderr, "  second pass: clear %.2f, request %.2f, land %.2f\n", a1/n/100.0, a2/n/100.0, a3/n/100.0);
-    }
-#endif
-    fprintf(stderr, "trace (us, 100 MHz ticks): kernel span %.2f | wg start avg %.2f max %.2f | stage0 %.2f slab0 %.2f rest %.2f stageout %.2f store %.2f | slab0 shader clock %.0f MHz\n",
-            (tend - t0) / 100.0, start_sum / n / 100.0, start_max / 100.0, sum[1] / n / 100.0, sum[2] / n / 100.0,
-            sum[3] / n / 100.0, sum[4] / n / 100.0, sum[5] / n / 100.0, sum[6] / std::max(1.0, sum[2]) * 100.0);
-  }
-#endif
   return hipGetLastError() == hipSuccess ? BSP_OK : BSP_ERR_HIP;
 }
 
@@ -543,9 +625,24 @@ int launch_hs(const RowsArgs& a, int BR, int NT, dim3 grid, int threads, size_t 
   return BSP_ERR_UNSUPPORTED;
 }
 
+template <int BR, bool CW4>
+int launch_pw_inst(const RowsArgs& a, dim3 grid, int threads, size_t ldsb, hipStream_t st) {
+  static bool raised = false;
+  if (!raised) {
+    if (hipFuncSetAttribute((const void*)conv_rows_pw<BR, CW4, 8>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit) != hipSuccess)
+      return BSP_ERR_HIP;
+    raised = true;
+  }
+  hipLaunchKernelGGL((conv_rows_pw<BR, CW4, 8>), grid, dim3(threads), ldsb, st, a);
+  return hipGetLastError() == hipSuccess ? BSP_OK : BSP_ERR_HIP;
+}
+
 struct Choice {
   int BR, NT, TW, NB, NI, SG, PTW, KS;
   double cost;
+  int G = 1;   // plan slabs staged together
+  int NM = 1;  // data-mover waves
 };
 
 struct Geometry {
@@ -567,13 +664,14 @@ bool rows_geometry(const ConvParams& p, int slab, int S, const Choice& c, Geomet
   if (c.NI * g->PR > 64) return false;  // a wave keeps one staged row per lane
   g->PC = (c.TW - 1) * S + p.K;
   g->PCp = (g->PC + 15) & ~15;
-  g->lscp = ceil_log2(slab / 8);
-  if (g->lscp < 2) return false;  // a request covers at most sixteen pixels of a row
+  g->lscp = ceil_log2(c.G * slab / 8);
+  if (g->lscp < 2 || g->lscp > 6) return false;  // a request covers between one and sixteen pixels of a row
   g->bufbytes = ((int64_t)c.NI * g->PR * g->PCp) << (g->lscp + 4);
   g->orow = c.SG * 32 + 16;
   g->red = c.KS > 1 ? (int64_t)(c.KS - 1) * c.PTW * c.SG * c.NT * c.BR * 1024 : 0;
   const int nslabs = (p.I + slab - 1) / slab;
-  const int64_t patch = nslabs > 1 ? 2 * g->bufbytes : g->bufbytes;
+  const int nstaged = (nslabs + c.G - 1) / c.G;
+  const int64_t patch = nstaged > 1 ? 2 * g->bufbytes : g->bufbytes;
   g->body = std::max<int64_t>(patch, g->red + (int64_t)g->slots * c.BR * g->orow);
   g->body = (g->body + 15) & ~15ll;
   g->ldsb = g->body + (int64_t)g->slots * 12 + c.SG * 16;
@@ -604,40 +702,50 @@ static bool rows_choose(const ConvParams& p, const int32_t* rs, int S, Choice* b
             const int waves = SG * PTW * KS;
             if (waves > 8) continue;
             const int slots = PTW * NT * 16;  // columns a workgroup can hold
-            for (int mode = 0; mode < 3; ++mode) {
-              Choice c{BR, NT, 0, 1, 1, SG, PTW, KS, 0.0};
-              if (mode == 0) {           // whole image rows, several bands
-                c.TW = p.N;
-                if (c.TW > slots) continue;
-                c.NB = std::min(slots / c.TW, (p.M + BR - 1) / BR);
-              } else if (mode == 1) {    // several images, every band of each
-                c.TW = p.N;
-                c.NB = (p.M + BR - 1) / BR;
-                if (c.TW * c.NB > slots) continue;
-                c.NI = std::min(slots / (c.TW * c.NB), p.B);
-                if (c.NI < 2) continue;
-              } else {                   // part of a row
-                if (p.N <= slots) continue;
-                const int parts = (p.N + slots - 1) / slots;
-                c.TW = (p.N + parts - 1) / parts;
+            for (int G : {1, 2, 4}) {
+              if (G > 1 && G / 2 >= nslabs) continue;
+              for (int mode = 0; mode < 3; ++mode) {
+                Choice c{BR, NT, 0, 1, 1, SG, PTW, KS, 0.0};
+                c.G = G;
+                if (mode == 0) {           // whole image rows, several bands
+                  c.TW = p.N;
+                  if (c.TW > slots) continue;
+                  c.NB = std::min(slots / c.TW, (p.M + BR - 1) / BR);
+                } else if (mode == 1) {    // several images, every band of each
+                  c.TW = p.N;
+                  c.NB = (p.M + BR - 1) / BR;
+                  if (c.TW * c.NB > slots) continue;
+                  c.NI = std::min(slots / (c.TW * c.NB), p.B);
+                  if (c.NI < 2) continue;
+                } else {                   // part of a row
+                  if (p.N <= slots) continue;
+                  const int parts = (p.N + slots - 1) / slots;
+                  c.TW = (p.N + parts - 1) / parts;
+                }
+                Geometry g;
+                if (!rows_geometry(p, slab, S, c, &g)) continue;
+                const int nstaged = (nslabs + G - 1) / G;
+                c.NM = nstaged > 1 ? (waves >= 8 ? 2 : 1) : 0;
+                const int nsg = (nstrips + SG - 1) / SG;
+                const int64_t nwg = g.ntiles * nsg;
+                // rough times in ns.  A wave alone on its SIMD issues about one instruction per
+                // eight cycles, so a column step costs its MFMAs plus its other instructions;
+                // a second wave on the SIMD hides most of that
+                const double step_mfma = p.H * BR * NT * 8.0, step_other = (20.0 + 10.0 * NT * ((BR - 1) * S + p.H)) * 4.0;
+                const int wg_per_cu = (int)std::max<int64_t>(1, std::min<int64_t>(kLdsLimit / g.ldsb, 10 / (waves + c.NM)));
+                const double conc = std::min<double>(wg_per_cu, std::max(1.0, (double)nwg / cus));
+                const double per_simd = std::max(1.0, waves * conc / 4.0);
+                const double t_step = per_simd >= 2.0 ? std::max(step_mfma * per_simd, (step_mfma + step_other) * per_simd / 2.0)
+                                                      : step_mfma + step_other;
+                const double t_compute = steps_per_strip / KS * t_step;
+                const double t_stage0 = 700.0 + (double)g.bufbytes / (60.0 / conc);
+                const double t_mover = nstaged > 1 ? (double)(nstaged - 1) * g.bufbytes / 16.0 / 64.0 * 110.0 / std::max(1, c.NM) : 0.0;
+                const double t_epi = 500.0 + 100.0 * NT * BR / 7.0 + (KS > 1 ? 400.0 : 0.0);
+                const double t_wg = t_stage0 + std::max(t_compute, t_mover) + 250.0 * nstaged + t_epi;
+                const double rounds = std::ceil((double)nwg / ((double)cus * wg_per_cu));
+                c.cost = rounds * t_wg;
+                if (c.cost < best->cost) *best = c;
               }
-              Geometry g;
-              if (!rows_geometry(p, slab, S, c, &g)) continue;
-              const int nsg = (nstrips + SG - 1) / SG;
-              const int64_t nwg = g.ntiles * nsg;
-              const double mfma_wave = steps_per_strip * p.H * BR * NT / KS * 16.0;
-              const int wg_per_cu_lds = (int)std::max<int64_t>(1, kLdsLimit / g.ldsb);
-              const int wg_per_cu = std::min(wg_per_cu_lds, std::max(1, 8 / waves));
-              const double conc = (double)cus * wg_per_cu;
-              const double rounds = std::ceil((double)nwg / conc);
-              const double waves_per_simd = std::ceil(waves * wg_per_cu / 4.0);
-              const double t_mfma = rounds * mfma_wave * waves_per_simd;
-              const double t_load = rounds * wg_per_cu * (double)g.bufbytes * nslabs / 48.0;
-              const double wbytes = steps_per_strip * p.H * 1024.0 * SG * PTW;
-              const double t_w = rounds * wg_per_cu * wbytes / 24.0;
-              const double t_mem = t_load + t_w;
-              c.cost = std::max(t_mfma, t_mem) + 0.3 * std::min(t_mfma, t_mem) + 2000.0 + 300.0 * nslabs;
-              if (c.cost < best->cost) *best = c;
             }
           }
         }
@@ -647,62 +755,29 @@ static bool rows_choose(const ConvParams& p, const int32_t* rs, int S, Choice* b
   return best->cost < 1e299;
 }
 
-int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st) {
-  if (dtype != BSP_BF16 || !plan_host) return BSP_ERR_UNSUPPORTED;
-  const int32_t* hdr = (const int32_t*)plan_host;
-  if (hdr[BSP_PLAN_MAGIC_W] != BSP_PLAN_MAGIC || hdr[BSP_PLAN_VERSION_W] != BSP_PLAN_VERSION ||
-      hdr[BSP_PLAN_O_W] != p.O || hdr[BSP_PLAN_I_W] != p.I || hdr[BSP_PLAN_H_W] != p.H ||
-      hdr[BSP_PLAN_K_W] != p.K || hdr[BSP_PLAN_DTYPE_W] != dtype || hdr[BSP_PLAN_OFF_ROWS_W] == 0)
-    return BSP_ERR_UNSUPPORTED;
-  const int32_t* rs = hdr + hdr[BSP_PLAN_OFF_ROWS_W];
-  if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return BSP_ERR_UNSUPPORTED;
-  if (p.H != 1 && p.H != 3) return BSP_ERR_UNSUPPORTED;
-  if ((int64_t)p.B * p.L * p.J * p.I * 2 >= (1ll << 31) || (int64_t)p.P * p.O * 2 >= (1ll << 31))
-    return BSP_ERR_UNSUPPORTED;
-  if (p.P <= 64 && p.H == 1 && p.K == 1) return BSP_ERR_UNSUPPORTED;  // FC layers: streaming kernels
-  const int cw = rs[BSP_ROWS_CW_W];
-  const int slab = rs[BSP_ROWS_SLAB_W];
-  const bool pointwise = p.H == 1 && p.K == 1;
-  const int S = pointwise ? 1 : p.sh;       // staged pixels per output pixel step
-  const int gs = pointwise ? p.sh : 1;      // input pixels per staged pixel
-  ConvParams v = p;                         // the view the tiles are cut from
-  if (pointwise && p.sh == 1 && p.ph == 0 && p.pw == 0) {
-    // a pointwise layer has no geometry: all pixels as rows of sixteen columns
-    const int W = 16;
-    v.B = 1;
-    v.N = v.J = W;
-    v.M = v.L = (p.P + W - 1) / W;
-  }
-  Choice ch;
-  if (!rows_choose(v, rs, S, &ch)) return BSP_ERR_UNSUPPORTED;
-#ifdef BSP_ROWS_TUNE  // experiments only: never defined in the product build
-  if (const char* e = std::getenv("BSP_ROWS_TUNE")) {
-    int q[8];
-    if (sscanf(e, "%d,%d,%d,%d,%d,%d,%d,%d", q, q + 1, q + 2, q + 3, q + 4, q + 5, q + 6, q + 7) == 8)
-      ch = Choice{q[0], q[1], q[2] > 0 ? q[2] : v.N, q[3], q[4], q[5], q[6], q[7], 0.0};
-  }
-  if (std::getenv("BSP_ROWS_VERBOSE"))
-    fprintf(stderr, "rows: M=%d N=%d B=%d I=%d O=%d H=%d s=%d | BR=%d NT=%d TW=%d NB=%d NI=%d SG=%d PTW=%d KS=%d cost=%.0f\n",
-            v.M, v.N, v.B, p.I, p.O, p.H, p.sh, ch.BR, ch.NT, ch.TW, ch.NB, ch.NI, ch.SG, ch.PTW, ch.KS, ch.cost);
-#endif
-  Geometry geo;
-  if (!rows_geometry(v, slab, S, ch, &geo)) return BSP_ERR_UNSUPPORTED;
-
-  RowsArgs a;
+// What both kernels take from the layer, the plan and the chosen tile.  SG / nsg / per_xcd are
+// filled for conv_rows (SG strips per workgroup); the pointwise launcher overrides them.
+static int rows_fill_common(const ConvParams& p, const ConvParams& v, const int32_t* hdr, const int32_t* rs, int gs,
+                            const Choice& ch, const Geometry& geo, RowsArgs* out) {
+  RowsArgs& a = *out;
+  const int32_t* sec = p.plan + hdr[BSP_PLAN_OFF_ROWS_W];
   a.X = (const unsigned char*)p.X;
   a.Y = (unsigned char*)p.Y;
   a.bias = p.bias;
   a.residual = (const unsigned char*)p.residual;
   a.relu = p.relu;
-  a.rstrip = p.plan + hdr[BSP_PLAN_OFF_ROWS_W] + rs[BSP_ROWS_OFF_STRIP_W];
-  a.rslab = p.plan + hdr[BSP_PLAN_OFF_ROWS_W] + rs[BSP_ROWS_OFF_SLAB_W];
-  a.rdesc = p.plan + hdr[BSP_PLAN_OFF_ROWS_W] + rs[BSP_ROWS_OFF_DESC_W];
-  a.rfrag = (const u32x4_t*)(p.plan + hdr[BSP_PLAN_OFF_ROWS_W] + rs[BSP_ROWS_OFF_FRAG_W]);
-  a.zeros = (const unsigned char*)(p.plan + hdr[BSP_PLAN_OFF_ROWS_W] + BSP_ROWS_ZEROS_W);
+  a.rstrip = sec + rs[BSP_ROWS_OFF_STRIP_W];
+  a.rslab = sec + rs[BSP_ROWS_OFF_SLAB_W];
+  a.rdesc = sec + rs[BSP_ROWS_OFF_DESC_W];
+  a.rfrag = (const u32x4_t*)(sec + rs[BSP_ROWS_OFF_FRAG_W]);
   a.nstrips = rs[BSP_ROWS_NSTRIPS_W];
   a.nslabs = rs[BSP_ROWS_NSLABS_W];
   a.ncs = rs[BSP_ROWS_NCS_W];  // 0: an all-zero mask, no step exists anywhere
-  a.sc = slab / 8;
+  a.sc = rs[BSP_ROWS_SLAB_W] / 8;
+  a.G = ch.G;
+  a.nstaged = (a.nslabs + ch.G - 1) / ch.G;
+  a.scs = ch.G * a.sc;
+  a.NM = ch.NM;
   a.lscp = geo.lscp;
   {
     const int bits = std::min(geo.lscp, 4);  // swizzle: 16 consecutive pixels, 16 distinct bank groups
@@ -739,10 +814,7 @@ int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipSt
   a.orow = geo.orow;
   a.red_bytes = (int32_t)geo.red;
   a.piece8 = hdr[BSP_PLAN_BO_W] == 4;
-  a.direct = 0;
-#ifdef BSP_ROWS_TUNE
-  if (std::getenv("BSP_ROWS_DIRECT")) a.direct = 1;
-#endif
+  a.direct = 1;
   a.tbl_off = (int32_t)geo.body;
   a.xlimit = p.B * p.L * p.J;
   a.ylimit = p.P;
@@ -763,10 +835,155 @@ int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipSt
   // the multiply-high divisions are exact while dividend * divisor < 2^32; staged pixels are
   // counted up to the next multiple of the workgroup size
   if ((nstage + 1024) * std::max(a.PCp, a.PR) >= (1ll << 32) ||
-      (int64_t)a.per_xcd * 8 * std::max(a.nsg, a.tiles_x * a.tiles_y) >= (1ll << 32) ||
-      (int64_t)geo.slots * ch.BR * ch.SG * 4 * std::max(ch.SG * 4, ch.BR) >= (1ll << 32))
+      (int64_t)a.per_xcd * 8 * std::max(a.nsg, a.tiles_x * a.tiles_y) >= (1ll << 32))
     return BSP_ERR_UNSUPPORTED;
-  const int threads = 64 * ch.SG * ch.PTW * ch.KS + 64;  // compute waves + the data mover
+  return BSP_OK;
+}
+
+// Pointwise layers with one slab: tile and pass choice, then conv_rows_pw.
+static int launch_pw(const ConvParams& p, const ConvParams& v, const int32_t* hdr, const int32_t* rs, int gs,
+                     hipStream_t st) {
+  const int nstrips = rs[BSP_ROWS_NSTRIPS_W], slab = rs[BSP_ROWS_SLAB_W];
+  const double steps = (double)rs[BSP_ROWS_NCS_W] / std::max(1, nstrips);
+  const int cus = device_cus();
+  Choice best{0, 1, 0, 1, 1, 1, 1, 1, 1e300};
+  int best_nq = 1;
+  Geometry bg{};
+  for (int BR : {7, 4})
+    for (int PTW : {1, 2, 4})
+      for (int NQ : {1, 2, 4, 8}) {
+        if (PTW * NQ > 8) continue;
+        for (int SG : {1, 2, 4, 8, 16}) {
+          if (SG > 1 && NQ * (SG / 2) >= nstrips) continue;
+          Choice c{BR, 1, 0, 1, 1, SG, PTW, 1, 0.0};
+          c.NM = 0;
+          const int slots = PTW * 16;
+          if (v.N <= slots) {
+            c.TW = v.N;
+            c.NB = std::min(slots / c.TW, (v.M + BR - 1) / BR);
+          } else {
+            const int parts = (v.N + slots - 1) / slots;
+            c.TW = (v.N + parts - 1) / parts;
+          }
+          Geometry g;
+          Choice cg = c;
+          cg.SG = 1;
+          cg.PTW = PTW;  // geometry wants waves <= 8: SG here is passes, not waves
+          if (!rows_geometry(v, slab, 1, cg, &g)) continue;
+          const int64_t nwg = g.ntiles * ((nstrips + NQ * SG - 1) / (NQ * SG));
+          const int waves = PTW * NQ;
+          const int conc = (int)std::max<int64_t>(1, std::min<int64_t>(kLdsLimit / g.ldsb, 8 / waves));
+          const double t_pass = std::max(steps * 1024.0 / 25.0, steps * BR * 16 / 2.0) + 120.0 + 20.0 * BR;  // ns
+          const double t_wg = 900.0 + (double)g.bufbytes / 80.0 + SG * t_pass;
+          const double rounds = std::ceil((double)nwg / ((double)cus * conc));
+          // workgroups that share a CU slow each other down (one L1, one LDS)
+          c.cost = rounds * t_wg * (1.0 + 0.35 * (std::min<double>(conc, (double)nwg / cus) - 1.0));
+          if (c.cost < best.cost) {
+            best = c;
+            best_nq = NQ;
+            bg = g;
+          }
+        }
+      }
+  if (best.cost > 1e299) return BSP_ERR_UNSUPPORTED;
+#ifdef BSP_ROWS_TUNE
+  if (const char* e = std::getenv("BSP_PW_TUNE")) {
+    int q[4];
+    if (sscanf(e, "%d,%d,%d,%d", q, q + 1, q + 2, q + 3) == 4) {
+      best.BR = q[0];
+      best.PTW = q[1];
+      best_nq = q[2];
+      best.SG = q[3];
+      const int slots = best.PTW * 16;
+      best.NB = 1;
+      if (v.N <= slots) {
+        best.TW = v.N;
+        best.NB = std::min(slots / best.TW, (v.M + best.BR - 1) / best.BR);
+      } else {
+        const int parts = (v.N + slots - 1) / slots;
+        best.TW = (v.N + parts - 1) / parts;
+      }
+      Choice cg = best;
+      cg.SG = 1;
+      if (!rows_geometry(v, slab, 1, cg, &bg)) return BSP_ERR_UNSUPPORTED;
+    }
+  }
+  if (std::getenv("BSP_ROWS_VERBOSE"))
+    fprintf(stderr, "rows pw: M=%d N=%d I=%d O=%d | BR=%d PTW=%d NQ=%d passes=%d TW=%d NB=%d lds=%lld cost=%.0f\n", v.M, v.N,
+            p.I, p.O, best.BR, best.PTW, best_nq, best.SG, best.TW, best.NB, (long long)bg.ldsb, best.cost);
+#endif
+  RowsArgs a{};
+  if (int rc = rows_fill_common(p, v, hdr, rs, gs, best, bg, &a)) return rc;
+  a.nsg = (nstrips + best_nq * best.SG - 1) / (best_nq * best.SG);
+  a.per_xcd = ((a.ntiles + 7) / 8) * a.nsg;
+  a.d_nsg = make_fastdiv(a.nsg);
+  if ((int64_t)a.per_xcd * 8 * std::max(a.nsg, a.tiles_x * a.tiles_y) >= (1ll << 32)) return BSP_ERR_UNSUPPORTED;
+  const int threads = 64 * best.PTW * best_nq;
+  dim3 grid((unsigned)(a.per_xcd * 8));
+  const bool cw4 = rs[BSP_ROWS_CW_W] == 4;
+  if (best.BR == 7)
+    return cw4 ? launch_pw_inst<7, true>(a, grid, threads, (size_t)bg.ldsb, st)
+               : launch_pw_inst<7, false>(a, grid, threads, (size_t)bg.ldsb, st);
+  return cw4 ? launch_pw_inst<4, true>(a, grid, threads, (size_t)bg.ldsb, st)
+             : launch_pw_inst<4, false>(a, grid, threads, (size_t)bg.ldsb, st);
+}
+
+int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st) {
+  if (dtype != BSP_BF16 || !plan_host) return BSP_ERR_UNSUPPORTED;
+  const int32_t* hdr = (const int32_t*)plan_host;
+  if (hdr[BSP_PLAN_MAGIC_W] != BSP_PLAN_MAGIC || hdr[BSP_PLAN_VERSION_W] != BSP_PLAN_VERSION ||
+      hdr[BSP_PLAN_O_W] != p.O || hdr[BSP_PLAN_I_W] != p.I || hdr[BSP_PLAN_H_W] != p.H ||
+      hdr[BSP_PLAN_K_W] != p.K || hdr[BSP_PLAN_DTYPE_W] != dtype || hdr[BSP_PLAN_OFF_ROWS_W] == 0)
+    return BSP_ERR_UNSUPPORTED;
+  const int32_t* rs = hdr + hdr[BSP_PLAN_OFF_ROWS_W];
+  if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return BSP_ERR_UNSUPPORTED;
+  if (p.H != 1 && p.H != 3) return BSP_ERR_UNSUPPORTED;
+  if ((int64_t)p.B * p.L * p.J * p.I * 2 >= (1ll << 31) || (int64_t)p.P * p.O * 2 >= (1ll << 31))
+    return BSP_ERR_UNSUPPORTED;
+  if (p.P <= 64 && p.H == 1 && p.K == 1) return BSP_ERR_UNSUPPORTED;  // FC layers: streaming kernels
+  const int cw = rs[BSP_ROWS_CW_W];
+  const int slab = rs[BSP_ROWS_SLAB_W];
+  const bool pointwise = p.H == 1 && p.K == 1;
+  const int S = pointwise ? 1 : p.sh;       // staged pixels per output pixel step
+  const int gs = pointwise ? p.sh : 1;      // input pixels per staged pixel
+  ConvParams v = p;                         // the view the tiles are cut from
+  if (pointwise && p.sh == 1 && p.ph == 0 && p.pw == 0) {
+    // a pointwise layer has no geometry: all pixels as rows of sixteen columns
+    const int W = 16;
+    v.B = 1;
+    v.N = v.J = W;
+    v.M = v.L = (p.P + W - 1) / W;
+  }
+  if (pointwise && rs[BSP_ROWS_NSLABS_W] == 1 && rs[BSP_ROWS_MAXSTRIPSTEPS_W] <= 8) {
+    const int rc = launch_pw(p, v, hdr, rs, gs, st);
+    if (rc != BSP_ERR_UNSUPPORTED) return rc;
+  }
+  Choice ch;
+  if (!rows_choose(v, rs, S, &ch)) return BSP_ERR_UNSUPPORTED;
+#ifdef BSP_ROWS_TUNE  // experiments only: never defined in the product build
+  if (const char* e = std::getenv("BSP_ROWS_TUNE")) {
+    int q[10] = {0, 0, 0, 0, 0, 0, 0, 0, 1, 1};
+    if (sscanf(e, "%d,%d,%d,%d,%d,%d,%d,%d,%d,%d", q, q + 1, q + 2, q + 3, q + 4, q + 5, q + 6, q + 7, q + 8, q + 9) >= 8) {
+      ch = Choice{q[0], q[1], q[2] > 0 ? q[2] : v.N, q[3], q[4], q[5], q[6], q[7], 0.0};
+      ch.G = q[8];
+      ch.NM = (rs[BSP_ROWS_NSLABS_W] + ch.G - 1) / ch.G > 1 ? std::max(1, q[9]) : 0;
+    }
+  }
+  if (std::getenv("BSP_ROWS_VERBOSE"))
+    fprintf(stderr, "rows: M=%d N=%d B=%d I=%d O=%d H=%d s=%d | BR=%d NT=%d TW=%d NB=%d NI=%d SG=%d PTW=%d KS=%d G=%d NM=%d cost=%.0f\n",
+            v.M, v.N, v.B, p.I, p.O, p.H, p.sh, ch.BR, ch.NT, ch.TW, ch.NB, ch.NI, ch.SG, ch.PTW, ch.KS, ch.G, ch.NM, ch.cost);
+#endif
+  Geometry geo;
+  if (!rows_geometry(v, slab, S, ch, &geo)) return BSP_ERR_UNSUPPORTED;
+
+  RowsArgs a{};
+  if (int rc = rows_fill_common(p, v, hdr, rs, gs, ch, geo, &a)) return rc;
+  a.direct = 0;
+#ifdef BSP_ROWS_TUNE
+  if (std::getenv("BSP_ROWS_DIRECT")) a.direct = 1;
+#endif
+  if ((int64_t)geo.slots * ch.BR * ch.SG * 4 * std::max(ch.SG * 4, ch.BR) >= (1ll << 32)) return BSP_ERR_UNSUPPORTED;
+  const int threads = 64 * (ch.SG * ch.PTW * ch.KS + ch.NM);  // compute waves + the data movers
   dim3 grid((unsigned)(a.per_xcd * 8));
   const size_t ldsb = (size_t)geo.ldsb;
   if (cw == 4) {
