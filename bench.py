@@ -24,10 +24,78 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
-# HBM bytes per launch of the dispatcher's kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of this script, each scaled by the same counter's reading for a device copy of known
-# size (summary: profiles/conv_lds_bf16_c1_counters.md)
-MEASURED_TRAFFIC_BYTES = {"c1": 29_681_518}
+# HBM bytes per launch of the dispatcher's kernel for the default workload, from two
+# rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE), each scaled by the same
+# counter's reading for a device copy of known size; the summary names the commit it was
+# taken at (profiles/conv_lds_bf16_c1_counters.md)
+MEASURED_TRAFFIC = {"c1": {"bytes": 29_681_518, "commit": "feef9ad"}}
+
+
+def measured_peaks(dev):
+    """What this GPU sustains: a stream copy through HBM (GB/s, read + write) and a loop of
+    independent bf16 MFMAs on register operands (TFLOP/s), each the best of a few launches."""
+    import torch
+    import paper_2407_09453_amd as bsp
+    st = torch.cuda.current_stream(dev)
+    n = 512 << 20
+    src = torch.empty(n, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    src.fill_(1)
+    sink = torch.zeros(8192, dtype=torch.float32, device=dev)
+    waves, iters = 8192, 2000
+
+    def best(fn, reps=5):
+        out = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(st)
+            fn()
+            b.record(st)
+            torch.cuda.synchronize()
+            out.append(a.elapsed_time(b))
+        return min(out)
+
+    copy_ms = best(lambda: bsp.bsp_bench_copy(dst.data_ptr(), src.data_ptr(), n, st.cuda_stream))
+    mfma_ms = best(lambda: bsp.bsp_bench_mfma_bf16(sink.data_ptr(), waves, iters, None, st.cuda_stream))
+    del src, dst
+    return {"hbm_copy_GBs": round(2 * n / copy_ms / 1e6, 1),
+            "mfma_bf16_TFLOPs": round(waves * iters * 8 * 16384 / mfma_ms / 1e9, 1)}
+
+
+def time_launches(launch, steps, warmup, dev, use_graph=True):
+    """Average time of one step, ms: `steps` back-to-back calls of launch(i, stream) timed
+    between synchronisations (wall clock) and with HIP events on the launch stream.  With
+    use_graph the calls are captured once into a HIP graph on a side stream and the graph
+    is replayed: what remains between kernels is the GPU's own dispatch, not the Python loop."""
+    import torch
+    for i in range(warmup):
+        launch(i, None)
+    torch.cuda.synchronize()
+    if use_graph:
+        side = torch.cuda.Stream(device=dev)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(steps):
+                    launch(i, side.cuda_stream)
+        torch.cuda.synchronize()
+        graph.replay()                      # one untimed replay
+        torch.cuda.synchronize()
+        run = graph.replay
+    else:
+        def run():
+            for i in range(steps):
+                launch(i, None)
+    stream = torch.cuda.current_stream(dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    e0.record(stream)
+    run()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t
+    return wall * 1e3 / steps, e0.elapsed_time(e1) / steps
 
 
 def algorithmic_bytes(c, nnzb: int) -> int:
@@ -54,6 +122,13 @@ def pick_case(name: str):
         for c in config_cases(2):
             if c.name.endswith(want):
                 return c, f"config2: conv1x1 256->1024 @14x14 batch 32 bf16, {want}"
+    if ":" in name:      # one layer of a network-shaped stack, e.g. resnet50:layer3.1.conv2
+        net, lname = name.split(":", 1)
+        cfg = 3 if net == "resnet50" else 4
+        for c in config_cases(cfg):
+            if c.meta.get("net") == net and c.name == lname:
+                return c, (f"{net} {lname}: conv{c.H}x{c.K} s{c.stride[0]} {c.I}->{c.O} on "
+                           f"{c.B}x{c.L}x{c.J}, 8x8 blocks, half kept")
     raise SystemExit(f"unknown workload {name}")
 
 
@@ -101,6 +176,8 @@ def bench_i8(args) -> int:
     ms_wall_d, _ = timed(dense)
     ops = 2 * c.P * layer.nnzb * c.bo * c.bi * c.H * c.K
     achieved = nbytes / (ms_ev * 1e-3) / 1e9
+    traffic = None if args.general or args.mask != "synthetic" or args.fused \
+        else MEASURED_TRAFFIC.get(args.workload)
     out = {
         "metric": "effective nonzero TOP/s (2*P*nnzb*bo*bi*H*K / t), 50% 8x8 block-sparse int8 conv",
         "value": round(ops / (ms_wall * 1e-3) / 1e12, 4), "unit": "TOP/s", "n_gpus": 1,
@@ -111,9 +188,12 @@ def bench_i8(args) -> int:
                                "int8, W 64x3x3x64 int8 codes (Eq. 8), int32 bias, int8 out >> 9",
                    "block": "8x8", "nnzb": layer.nnzb, "buffer_sets": nsets,
                    "kernel": "dispatch", "delta": delta},
-        "speedup_vs_dense_mask": round(ms_wall_d / ms_wall, 4),
-        "dense_mask_ms_per_step": round(ms_wall_d, 6),
+        "speedup_vs_dense_mask": None if ms_wall_d is None else round(ms_wall_d / ms_wall, 4),
+        "dense_mask_ms_per_step": None if ms_wall_d is None else round(ms_wall_d, 6),
         "event_ms_per_step": round(ms_ev, 6),
+        "timing": ("K launches captured into one HIP graph, one replay timed between synchronisations"
+                   if args.graph else "K launches issued from the Python loop"),
+        "eager_ms_per_step": round(ms_eager, 6),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
                      "algorithmic_bytes": int(nbytes)},
@@ -186,6 +266,9 @@ def bench_spgemm(args) -> int:
                    "nnzb_a": Am.nnzb, "nnzb_b": Bm.nnzb},
         "speedup_vs_dense_mask": round(ms_d / ms, 4), "dense_mask_ms_per_step": round(ms_d, 6),
         "event_ms_per_step": round(ms_ev, 6),
+        "timing": ("K launches captured into one HIP graph, one replay timed between synchronisations"
+                   if args.graph else "K launches issued from the Python loop"),
+        "eager_ms_per_step": round(ms_eager, 6),
         "roofline": {"bound": "mfma", "achieved": round(flops / (ms_ev * 1e-3) / 1e12, 3),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(flops / (ms_ev * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5),
@@ -207,70 +290,100 @@ def bench_spgemm(args) -> int:
     return 0
 
 
-def bench_network(args, net: str) -> int:
-    """Per-layer timing of a whole network-shaped stack: every layer on its own
-    resident N(0,1) input (layers are independent: glue such as pooling is not
-    part of the path), kept-block mask vs all-ones mask through the same
-    dispatcher.  A step is one launch of every layer."""
+def network_rows(args, net: str, peaks, reps: int = 20):
+    """Per-layer timing of a whole network-shaped stack: every layer on its own resident
+    N(0,1) input (layers are independent: glue such as pooling is not part of the path), the
+    kept-block mask and the all-ones mask through the same dispatcher.  Each layer is timed
+    as `reps` back-to-back launches replayed from a HIP graph over three rotating buffer sets
+    (median of five replays).  Returns one row per layer with the layer's roofline floor
+    (published peaks), the fraction reached, and the ceiling on the speed-up over the
+    all-ones mask that the measured sustained peaks allow."""
     import torch
     import paper_2407_09453_amd as bsp
     from synthetic import config_cases
 
     dev = torch.device("cuda:0")
     cfg = 3 if net == "resnet50" else 4
-    stream = torch.cuda.current_stream(dev)
-    rows = []
     gen = torch.Generator(device=dev)
     gen.manual_seed(2407)
+    F = peaks["mfma_bf16_TFLOPs"] * 1e12
+    BW = peaks["hbm_copy_GBs"] * 1e9
+    rows = []
     for c in config_cases(cfg, draw_x=False):
         if c.meta.get("net") != net:
             continue
         sparse = bsp.BspLayer(c.W, c.gamma, c.bo, c.bi, c.dtype, bias=c.bias)
         dense = bsp.BspLayer(c.W, np.ones_like(c.gamma), c.bo, c.bi, c.dtype, bias=c.bias)
-        X = torch.randn((c.B, c.L, c.J, c.I), device=dev, generator=gen).to(torch.bfloat16)
-        Y = torch.empty(sparse.out_shape(c.B, c.L, c.J, c.stride, c.pad), dtype=torch.bfloat16,
-                        device=dev)
+        nb = 3
+        Xs = [torch.randn((c.B, c.L, c.J, c.I), device=dev, generator=gen).to(torch.bfloat16)
+              for _ in range(nb)]
+        Ys = [torch.empty(sparse.out_shape(c.B, c.L, c.J, c.stride, c.pad), dtype=torch.bfloat16,
+                          device=dev) for _ in range(nb)]
         res = {}
         for name, lay in (("sparse", sparse), ("dense", dense)):
-            for _ in range(args.warmup):
-                lay.conv2d(X, c.stride, c.pad, out=Y, general=args.general)
-            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                   for _ in range(args.steps)]
-            torch.cuda.synchronize()
-            for a, b in evs:
-                a.record(stream)
-                lay.conv2d(X, c.stride, c.pad, out=Y, general=args.general)
-                b.record(stream)
-            torch.cuda.synchronize()
-            res[name] = float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e3
+            def launch(i, st, lay=lay):
+                lay.conv2d(Xs[i % nb], c.stride, c.pad, out=Ys[i % nb], general=args.general, stream=st)
+            ts = [time_launches(launch, reps, 2, dev)[1] * 1e3 for _ in range(5)]
+            res[name] = float(np.median(ts))
         fl = flops_nonzero(c, sparse.nnzb)
+        fl_d = flops_nonzero(c, int(c.gamma.size))
         by = algorithmic_bytes(c, sparse.nnzb)
+        by_d = algorithmic_bytes(c, int(c.gamma.size))
+        floor_us = max(fl / (MFMA_BF16_PEAK_TFLOPS * 1e12), by / (HBM_PEAK_GBS * 1e9)) * 1e6
+        bound = "mfma" if fl / (MFMA_BF16_PEAK_TFLOPS * 1e12) > by / (HBM_PEAK_GBS * 1e9) else "hbm"
+        ceiling = max(fl_d / F, by_d / BW) / max(fl / F, by / BW)
         rows.append({"layer": c.name, "I": c.I, "O": c.O, "HxK": f"{c.H}x{c.K}", "in": f"{c.L}x{c.J}",
                      "stride": c.stride[0], "nnzb": sparse.nnzb, "blocks": int(c.gamma.size),
                      "us": round(res["sparse"], 2), "us_dense_mask": round(res["dense"], 2),
                      "speedup": round(res["dense"] / res["sparse"], 3),
+                     "speedup_ceiling": round(ceiling, 3),
                      "TFLOPs_nz": round(fl / res["sparse"] / 1e6, 2),
-                     "GBs": round(by / res["sparse"] / 1e3, 1), "flops_nz": fl, "bytes": by})
-        del sparse, dense, X, Y
+                     "GBs": round(by / res["sparse"] / 1e3, 1), "bound": bound,
+                     "floor_us": round(floor_us, 2), "roofline_frac": round(floor_us / res["sparse"], 4),
+                     "flops_nz": fl, "bytes": by})
+        del sparse, dense, Xs, Ys
+    return rows
+
+
+def network_summary(rows):
     tot = sum(r["us"] for r in rows)
     totd = sum(r["us_dense_mask"] for r in rows)
     fl = sum(r["flops_nz"] for r in rows)
-    print(f"{'layer':28s} {'I':>5s} {'O':>5s} {'HxK':>4s} {'in':>8s} {'us':>8s} {'dense':>8s} {'x':>6s} "
-          f"{'TF/s':>7s} {'GB/s':>7s}", file=sys.stderr)
+    floor = sum(r["floor_us"] for r in rows)
+    return {"layers": len(rows), "us": round(tot, 1), "us_dense_mask": round(totd, 1),
+            "TFLOPs_nz": round(fl / tot / 1e6, 2), "speedup_vs_dense_mask": round(totd / tot, 4),
+            "roofline_floor_us": round(floor, 1), "roofline_frac": round(floor / tot, 4)}
+
+
+def bench_network(args, net: str) -> int:
+    import torch
+    dev = torch.device("cuda:0")
+    peaks = measured_peaks(dev)
+    rows = network_rows(args, net, peaks, reps=args.steps)
+    print(f"{'layer':28s} {'I':>5s} {'O':>5s} {'HxK':>4s} {'in':>8s} {'us':>8s} {'dense':>8s} {'x':>6s} {'ceil':>5s} "
+          f"{'TF/s':>7s} {'GB/s':>7s} {'bound':>5s} {'floor':>6s} {'frac':>6s}", file=sys.stderr)
     for r in rows:
         print(f"{r['layer']:28s} {r['I']:5d} {r['O']:5d} {r['HxK']:>4s} {r['in']:>8s} {r['us']:8.1f} "
-              f"{r['us_dense_mask']:8.1f} {r['speedup']:6.2f} {r['TFLOPs_nz']:7.1f} {r['GBs']:7.0f}",
-              file=sys.stderr)
+              f"{r['us_dense_mask']:8.1f} {r['speedup']:6.2f} {r['speedup_ceiling']:5.2f} {r['TFLOPs_nz']:7.1f} "
+              f"{r['GBs']:7.0f} {r['bound']:>5s} {r['floor_us']:6.1f} {r['roofline_frac']:6.3f}", file=sys.stderr)
+    sm = network_summary(rows)
     out = {
         "metric": "effective nonzero TFLOP/s (2*P*nnzb*bo*bi*H*K / t), 50% 8x8 block-sparse layers",
-        "value": round(fl / tot / 1e6, 4), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(tot / 1e3, 6), "higher_is_better": True,
+        "value": sm["TFLOPs_nz"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(sm["us"] / 1e3, 6), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{net}-shaped conv+FC stack, batch {rows and 32 if net == 'resnet50' else 16}, "
+        "config": {"workload": f"{net}-shaped conv+FC stack, batch {32 if net == 'resnet50' else 16}, "
                                "8x8 blocks, half the blocks kept per layer (first conv dense)",
-                   "layers": len(rows), "timing": "median of per-launch HIP event pairs, summed over layers"},
-        "speedup_vs_dense_mask": round(totd / tot, 4),
-        "dense_mask_ms_per_step": round(totd / 1e3, 6),
+                   "layers": len(rows),
+                   "timing": "per layer: back-to-back launches replayed from a HIP graph, median of five "
+                             "replays, summed over layers"},
+        "speedup_vs_dense_mask": sm["speedup_vs_dense_mask"],
+        "dense_mask_ms_per_step": round(sm["us_dense_mask"] / 1e3, 6),
+        "measured_peaks": peaks,
+        "roofline": {"bound": "mixed", "achieved": None, "peak": None, "unit": "us",
+                     "frac": sm["roofline_frac"], "traffic": None,
+                     "floor_us": sm["roofline_floor_us"],
+                     "note": "sum over layers of max(flops/2.5 PFLOP/s, bytes/8 TB/s) over the summed time"},
         "layers": rows,
     }
     print(json.dumps(out))
@@ -283,7 +396,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c1",
-                    help="c1 (default), c0, c2:<bo>x<bi>.d<density>, c1_i8, spgemm, resnet50, vgg16, inception_v3")
+                    help="c1 (default), c0, c2:<bo>x<bi>.d<density>, c1_i8, spgemm, resnet50, vgg16, inception_v3, "
+                         "or one layer of a stack as <net>:<layer name>")
     ap.add_argument("--sets", type=int, default=0,
                     help="distinct X/Y buffer sets cycled through (0 = enough to exceed 256 MB)")
     ap.add_argument("--mask", default="synthetic", choices=["synthetic", "l2", "l1", "var"],
@@ -294,6 +408,13 @@ def main() -> int:
                          "comparison, the plain layer followed by torch's add and relu)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--general", action="store_true", help="force the general-shape kernel")
+    ap.add_argument("--no-dense-mask", dest="dense_mask", action="store_false",
+                    help="skip the all-ones-mask comparator (profiling runs: only the layer's own launches)")
+    ap.add_argument("--no-graph", dest="graph", action="store_false",
+                    help="issue the timed launches from the Python loop instead of replaying "
+                         "them from one captured HIP graph")
+    ap.add_argument("--no-network-summary", dest="network_summary", action="store_false",
+                    help="skip the ResNet50-shaped stack summary folded into the default line")
     ap.add_argument("--no-multi-stream", dest="multi_stream", action="store_false",
                     help="skip the extra four-stream throughput measurement")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -364,24 +485,13 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t) * 1e3 / steps
 
-    def timed(lay, steps, warmup):
-        for i in range(warmup):
-            step(lay, i)
-        torch.cuda.synchronize()
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        t = time.perf_counter()
-        e0.record(stream)
-        for i in range(steps):
-            step(lay, i)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t
-        return wall * 1e3 / steps, e0.elapsed_time(e1) / steps
+    def timed(lay, graph):
+        return time_launches(lambda i, st: step(lay, i, st), args.steps, args.warmup, dev,
+                             use_graph=graph)
 
     def per_launch_us(lay, steps):
-        """Average duration of one kernel launch from HIP events recorded on the
-        launch stream right before and after each launch."""
+        """Duration of one launch from HIP events recorded on the launch stream right before
+        and after it (includes the launch's own start-up and drain)."""
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                for _ in range(steps)]
         torch.cuda.synchronize()
@@ -393,10 +503,13 @@ def main() -> int:
         d = np.array([a.elapsed_time(b) for a, b in evs]) * 1e3
         return float(d.mean()), float(np.median(d)), float(d.min())
 
-    ms_wall, ms_ev = timed(layer, args.steps, args.warmup)
-    ms_wall_d, ms_ev_d = timed(dense, args.steps, args.warmup)
-    k_avg, k_med, k_min = per_launch_us(layer, args.steps)
-    kd_avg, kd_med, kd_min = per_launch_us(dense, args.steps)
+    # the K timed steps: replayed from a HIP graph (default) or issued from the Python loop
+    ms_wall, ms_ev = timed(layer, args.graph)
+    ms_wall_d, ms_ev_d = timed(dense, args.graph) if args.dense_mask else (None, None)
+    ms_eager, ms_eager_ev = timed(layer, False) if args.graph else (ms_wall, ms_ev)
+    k_avg, k_med, k_min = per_launch_us(layer, min(args.steps, 200))
+    kd_avg = per_launch_us(dense, min(args.steps, 200))[0] if args.dense_mask else None
+    peaks = measured_peaks(dev)
 
     ms_multi = timed_streams(layer, args.steps, 4) if args.multi_stream else None
     ms_unfused = None
@@ -420,6 +533,27 @@ def main() -> int:
     # the K back-to-back launches (what `rocprofv3 --kernel-trace --stats` reports per kernel,
     # plus the gap between consecutive launches)
     achieved = nbytes / (ms_ev * 1e-3) / 1e9
+    traffic = None if args.general or args.mask != "synthetic" or args.fused \
+        else MEASURED_TRAFFIC.get(args.workload)
+    mfma_bound = c.dtype == "bf16" and fl / (MFMA_BF16_PEAK_TFLOPS * 1e12) > nbytes / (HBM_PEAK_GBS * 1e9)
+    if mfma_bound:   # the layer's floor is the matrix cores' (nonzero flop at the dense bf16 peak)
+        ach = fl / (ms_ev * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 5), "traffic": None,
+                "algorithmic_flops": fl,
+                "frac_of_wall": round(fl / (ms_wall * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5),
+                "frac_of_measured_mfma": round(ach / peaks["mfma_bf16_TFLOPs"], 5),
+                "hbm_frac": round(achieved / HBM_PEAK_GBS, 5)}
+    else:
+        roof = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
+                "traffic": None if traffic is None else traffic["bytes"],
+                "traffic_commit": None if traffic is None else traffic["commit"],
+                "algorithmic_bytes": nbytes,
+                "frac_of_wall": round(nbytes / (ms_wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 5),
+                "frac_of_measured_copy": round(achieved / peaks["hbm_copy_GBs"], 5),
+                "mfma_frac_of_measured": round(fl / (ms_ev * 1e-3) / 1e12 / peaks["mfma_bf16_TFLOPs"], 5)
+                if c.dtype == "bf16" else None}
     out = {
         "metric": "effective nonzero TFLOP/s (2*P*nnzb*bo*bi*H*K / t), 50% 8x8 block-sparse conv",
         "value": round(value, 4),
@@ -436,11 +570,14 @@ def main() -> int:
         "config": {"workload": workload, "block": f"{c.bo}x{c.bi}", "nnzb": layer.nnzb,
                    "density": round(layer.nnzb / c.gamma.size, 4), "buffer_sets": nsets,
                    "kernel": "general" if args.general else "dispatch"},
-        "speedup_vs_dense_mask": round(ms_wall_d / ms_wall, 4),
-        "dense_mask_ms_per_step": round(ms_wall_d, 6),
+        "speedup_vs_dense_mask": None if ms_wall_d is None else round(ms_wall_d / ms_wall, 4),
+        "dense_mask_ms_per_step": None if ms_wall_d is None else round(ms_wall_d, 6),
         "event_ms_per_step": round(ms_ev, 6),
+        "timing": ("K launches captured into one HIP graph, one replay timed between synchronisations"
+                   if args.graph else "K launches issued from the Python loop"),
+        "eager_ms_per_step": round(ms_eager, 6),
         "event_pair_us": {"avg": round(k_avg, 3), "median": round(k_med, 3), "min": round(k_min, 3),
-                          "dense_mask_avg": round(kd_avg, 3),
+                          "dense_mask_avg": None if kd_avg is None else round(kd_avg, 3),
                           "note": "one launch between two events: includes launch and drain"},
         "multi_stream": None if ms_multi is None else
         {"streams": 4, "ms_per_step": round(ms_multi, 6),
@@ -452,17 +589,19 @@ def main() -> int:
         "fused_epilogue": bool(args.fused),
         "unfused_ms_per_step": None if ms_unfused is None else round(ms_unfused, 6),
         "mask": args.mask, "mask_select_ms": None if select_ms is None else round(select_ms, 3),
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
-                     "traffic": None if args.general else MEASURED_TRAFFIC_BYTES.get(args.workload),
-                     "algorithmic_bytes": nbytes},
+        "roofline": roof,
+        "measured_peaks": peaks,
     }
+    if args.workload == "c1" and args.network_summary and not (args.general or args.fused
+                                                                or args.mask != "synthetic"):
+        out["resnet50"] = network_summary(network_rows(args, "resnet50", peaks, reps=20))
 
     if args.copy_calibration:
-        for i in range(5):
-            Ys[i % nsets].view(-1)[:Xs[0].numel()].copy_(Xs[i % nsets].view(-1)[:Ys[0].numel()])
+        nb_copy = int(min(Xs[0].numel(), Ys[0].numel()) * Xs[0].element_size()) & ~15
+        for i in range(5):   # the library's own copy kernel (bench_copy), nb_copy bytes read and written
+            bsp.bsp_bench_copy(Ys[i % nsets].data_ptr(), Xs[i % nsets].data_ptr(), nb_copy, stream.cuda_stream)
         torch.cuda.synchronize()
-        out["copy_calibration_bytes"] = int(min(Xs[0].numel(), Ys[0].numel()) * Xs[0].element_size())
+        out["copy_calibration_bytes"] = nb_copy
 
     if not args.no_cpu_baseline:
         import oracle

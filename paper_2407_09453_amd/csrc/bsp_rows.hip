@@ -547,9 +547,7 @@ __global__ __launch_bounds__(512) void conv_rows_pw(RowsArgs a) {
   const int rowbytes = a.PCp << (a.lscp + 4);
 
   auto pass = [&](int cur, int i_strip) {
-#ifndef BSP_EXP_NOREQ
     request(cur ^ 1, i_strip + 1);  // past the last strip lanes hold 0: a valid step, never used
-#endif
     // this lane group's first channel: four lanes per strip in v_ch
     int ch = __builtin_amdgcn_readlane(v_ch, (i_strip * 4) & 63);
     ch = g == 1 ? __builtin_amdgcn_readlane(v_ch, (i_strip * 4 + 1) & 63) : ch;
@@ -565,21 +563,12 @@ __global__ __launch_bounds__(512) void conv_rows_pw(RowsArgs a) {
     for (int i = 0; i < MAXS; ++i) {
       if (i < n) {
         u32x4_t f[BR];
-#ifdef BSP_EXP_NOLDS
-#pragma unroll
-        for (int r = 0; r < BR; ++r) f[r] = ws[cur][(i + 1) % MAXS];
-#else
         rows_read<1, 1, BR, CW4>(a, lds, (uint32_t)ds[cur][i], pixb, rowbytes, 0u, f);
-#endif
 #pragma unroll
         for (int r = 0; r < BR; ++r) acc[r] = mfma_bf16_16x16x32(ws[cur][i], f[r], acc[r]);
       }
     }
-#ifdef BSP_EXP_NOSTORE
-    if (acc[0].x == 123.f) rows_store_direct<BR>(a, acc, ch, cb, rows, false);
-#else
     rows_store_direct<BR>(a, acc, ch, cb, rows, false);
-#endif
   };
   const int npass = last - first;
   for (int i = 0; i < npass; i += 2) {
