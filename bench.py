@@ -27,8 +27,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
 # HBM bytes per launch of the dispatcher's kernel for the default workload, from two
 # rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE), each scaled by the same
 # counter's reading for a device copy of known size; the summary names the commit it was
-# taken at (profiles/conv_lds_bf16_c1_counters.md)
-MEASURED_TRAFFIC = {"c1": {"bytes": 29_681_518, "commit": "feef9ad"}}
+# taken at (profiles/conv_lds_bf16_c1.md)
+MEASURED_TRAFFIC = {"c1": {"bytes": 29_595_203, "commit": "bd5d8d8"}}
 
 
 def measured_peaks(dev):
@@ -540,7 +540,7 @@ def main() -> int:
         ach = fl / (ms_ev * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 5), "traffic": None,
-                "algorithmic_flops": fl,
+                "algorithmic_flops": fl, "algorithmic_bytes": nbytes,
                 "frac_of_wall": round(fl / (ms_wall * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5),
                 "frac_of_measured_mfma": round(ach / peaks["mfma_bf16_TFLOPs"], 5),
                 "hbm_frac": round(achieved / HBM_PEAK_GBS, 5)}
