@@ -160,7 +160,8 @@ enum bsp_kernel_family {
   BSP_KERNEL_ROWS = 1,  /* row-band kernel: activation fragments reused over window rows */
   BSP_KERNEL_LDS = 2,   /* weights and activations of a slab resident in LDS */
   BSP_KERNEL_TILE = 4,  /* weights streamed through a register ring */
-  BSP_KERNEL_FC = 8     /* weight-streaming kernels for layers with at most 64 output pixels */
+  BSP_KERNEL_FC = 8,    /* weight-streaming kernels for layers with at most 64 output pixels */
+  BSP_KERNEL_PW = 16    /* pointwise layers: all input channels of a pixel tile resident in LDS */
 };
 
 /* Fully-connected layer Y[B][O] = X[B][I] . (Gamma W-bar)^T + bias, work done

@@ -17,7 +17,7 @@ BSP_F32 = 0
 BSP_BF16 = 1
 BSP_I8 = 2
 BSP_I32 = 3
-BSP_KERNEL_ROWS, BSP_KERNEL_LDS, BSP_KERNEL_TILE, BSP_KERNEL_FC = 1, 2, 4, 8
+BSP_KERNEL_ROWS, BSP_KERNEL_LDS, BSP_KERNEL_TILE, BSP_KERNEL_FC, BSP_KERNEL_PW = 1, 2, 4, 8, 16
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libbsp.so")

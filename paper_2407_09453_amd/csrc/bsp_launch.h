@@ -30,6 +30,10 @@ int bsp_launch_lds_i8(const ConvParams& p, const void* plan_host, int shift, hip
 // section and its host copy).  BSP_ERR_UNSUPPORTED = not applicable, nothing launched.
 int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);
 
+// Pointwise kernel (bf16, 1x1 windows without padding, any stride, all input channels in one
+// slab of the row-band section).  BSP_ERR_UNSUPPORTED = not applicable, nothing launched.
+int bsp_launch_pw(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);
+
 // 8-bit integer layers: X and payload int8, bias int32 (passed through ConvParams::bias),
 // Y int8 after a rounding right shift (y_i8 = 1) or the int32 sums.
 int bsp_launch_i8(const ConvParams& p, int y_i8, int shift, int bo, int bi, hipStream_t st);

@@ -46,7 +46,7 @@ enum {
   BSP_MAXSUB = 4,
   BSP_PLAN_HEADER_WORDS = 32,
   BSP_PLAN_MAGIC = 0x42535032,
-  BSP_PLAN_VERSION = 4,
+  BSP_PLAN_VERSION = 5,
 };
 
 enum {
@@ -97,7 +97,7 @@ enum {
 //                               items, one per 16-bit half)
 //   rfrag[ncs][H][64][8]        bf16 weights, lane 16q + j of (step, window row dy):
 //                               W[strip row j][dy][dx(item)][unit(item) channels] or 0
-// Strips are stored heaviest first.
+// Strips are stored heaviest first, or in window order (BSP_ROWS_WINDOW_W).
 enum {
   BSP_ROWS_HEADER_WORDS = 24,
   BSP_ROWS_NSTRIPS_W = 0,
@@ -114,16 +114,25 @@ enum {
   BSP_ROWS_MAXSTRIPSTEPS_W = 11,  // most column steps in any strip
   BSP_ROWS_KEPT_ITEMS_W = 12,     // units in kept blocks (work the mask asks for)
   BSP_ROWS_UNION_ITEMS_W = 13,    // units the strips run (kept + zero-filled)
+  BSP_ROWS_WINDOW_W = 14,         // strips per window of output channels (see bsp_rows_window), 0: none
   BSP_ROWS_ZEROS_W = 16,          // four zero words, 16-byte aligned: the source of padding pieces
   BSP_ROWS_MAXH = 7,
 };
 
-// Channels the row-band kernel stages at a time.
-static inline int32_t bsp_rows_slab(int32_t I, int32_t H, int32_t K) {
+// Channels of one slab of the row-band section: windows are staged 128 channels at a time;
+// a pointwise layer keeps all its channels in LDS (one slab) as long as a unit number fits
+// the descriptor's eight bits (256 units of `cw` channels).
+static inline int32_t bsp_rows_slab(int32_t I, int32_t H, int32_t K, int32_t cw) {
   const int32_t i8 = (I + 7) / 8 * 8;
-  const int32_t cap = (H * K > 1) ? 128 : 256;
+  const int32_t cap = (H * K > 1) ? 128 : 256 * cw;
   return i8 < cap ? i8 : cap;
 }
+
+// Strips per window of output channels.  Pointwise layers group block rows into strips only
+// within windows of 64 output channels (four strips) and keep the strips in window order:
+// strip s then produces channels of window s / 4 only.  Other layers group rows freely and
+// order the strips heaviest first (0).
+static inline int32_t bsp_rows_window(int32_t H, int32_t K) { return H * K == 1 ? 4 : 0; }
 
 // Channels kept in LDS at a time, as a function of the layer shape alone so
 // that the plan builder and the launcher agree without talking to each other.

@@ -1,4 +1,4 @@
-// Row-band kernels: block-sparse implicit-GEMM convolution for bf16 layers (fp32 accumulation)
+// Row-band kernel: block-sparse implicit-GEMM convolution for bf16 layers (fp32 accumulation)
 // in which one activation fragment, once in registers, serves every window row.
 //
 // Work split.  A workgroup owns a pixel tile (NI images x NB bands of BR output rows x TW
@@ -13,7 +13,7 @@
 // permuted by the pixel's position (slot = piece ^ f(pixel)) so that the sixteen pixels a
 // lane group reads fall into sixteen different bank groups.
 //
-// conv_rows (windows, or several slabs): a wave owns one strip, NT lane tiles and, when the
+// conv_rows: a wave owns one strip, NT lane tiles and, when the
 // contraction is split (KS > 1), every KS-th column step.  Per step it reads, for each lane
 // tile, the NF = (BR-1)*S + H patch rows of the step's items once, takes the step's H weight
 // fragments (one per window row, streamed from the plan through a ring of registers), and
@@ -22,9 +22,7 @@
 // last wave of the workgroup only moves data: it requests the next slab while the others
 // compute.
 //
-// conv_rows_pw (pointwise layers whose input channels fit one slab): the patch is staged
-// once and every wave then walks several strips (passes); a strip's few weight fragments
-// sit in registers whole, the next strip's are requested while the current one is computed.
+// Pointwise (1x1) layers are not served here (bsp_pw.hip).
 //
 // Only kept blocks have items (paper Section I, advantages 3-4); a strip groups block rows
 // with similar kept columns (bsp_plan.h).
@@ -55,11 +53,11 @@ struct RowsArgs {
   int32_t swz_shift, swz_mask;     // piece p of pixel q sits in slot p ^ ((q >> shift) & mask)
   int32_t B, L, J, I, O, M, N;
   int32_t ph, pw, stride;          // stride = S * gs
-  int32_t gs;                      // input pixels per staged pixel (strided pointwise layers: the stride)
+  int32_t gs;                      // input pixels per staged pixel (1)
   int32_t TW, NB, NI, PR, PC, PCp; // PC staged columns that are read, PCp the row pitch (multiple of 16)
   int32_t tiles_x, tiles_y, ntiles;
   int32_t ncols;                   // NI * NB * TW
-  int32_t SG, PTW, KS, nsg;        // conv_rows_pw: SG strips per wave (passes), nsg strip ranges
+  int32_t SG, PTW, KS, nsg;        // strips, lane-tile groups and contraction shares per workgroup; strip groups
   int32_t per_xcd;                 // workgroups per XCD slot range
   int32_t bufbytes;                // one patch buffer
   int32_t orow;                    // bytes per pixel in the results staging tile
@@ -67,7 +65,7 @@ struct RowsArgs {
   int32_t tbl_off;                 // LDS offset of the tables
   int32_t piece8;                  // results leave as 8-byte pieces (4x16 blocks)
   int32_t direct;                  // results leave straight from the accumulators, 8 bytes per lane
-  int32_t xlimit, ylimit;          // input / output pixels that exist (the flattened view may end mid-row)
+  int32_t xlimit, ylimit;          // input / output pixels that exist
   int32_t lsg, lptw;               // log2 of SG and PTW
   FastDiv d_pcp, d_pr, d_np, d_br, d_nsg, d_tpi, d_tx, d_perimg, d_tw;
 };
@@ -483,100 +481,6 @@ __global__ __launch_bounds__(640) void conv_rows(RowsArgs a) {
   }
 }
 
-// Pointwise layers whose input channels fit one slab.  No data mover: every wave helps stage
-// the one patch, then walks its SG strips.  A strip has at most MAXS column steps; their
-// weight fragments (and the next strip's) sit in registers.
-template <int BR, bool CW4, int MAXS>
-__global__ __launch_bounds__(512) void conv_rows_pw(RowsArgs a) {
-  extern __shared__ __align__(16) unsigned char lds[];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
-  TilePos tp;
-  if (!rows_tile(a, BR, &tp)) return;
-  int32_t* colbase = (int32_t*)(lds + a.tbl_off);
-  const int nslots = a.PTW * 16;
-  int32_t* colrows = colbase + nslots;
-  int32_t* colpix = colrows + nslots;
-  rows_tables(a, tp, BR, 1, nslots, colbase, colrows, colpix);
-  rows_clear_outside(a, tp, lds);
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
-  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  const int nwaves = (int)(blockDim.x >> 6);
-  rows_stage(a, tp, lds, 0, wave_u, nwaves);
-
-  // waves: pt = lane tile, the others split the strip range; wave (pt, q) walks strips
-  // first + q * SG .. + SG - 1
-  const int pt = wave_u & (a.PTW - 1), q = wave_u >> a.lptw;
-  const int first = (tp.sgi * (nwaves >> a.lptw) + q) * a.SG;
-  const int last = min(first + a.SG, a.nstrips);
-  const uint32_t frag_lane = (uint32_t)lane * 16u, desc_lane = (uint32_t)g * 4u;
-  const unsigned char* fragb = (const unsigned char*)a.rfrag;
-  const unsigned char* descb = (const unsigned char*)a.rdesc;
-  u32x4_t ws[2][MAXS];
-  int ds[2][MAXS];
-  int nst[2] = {0, 0};
-  // per-strip numbers are fetched once, up front: lane i holds the step range of the wave's
-  // i-th strip (and lane 4 i + g the first channel of its lane group g), so that no pass
-  // waits for a load before it can ask for the next strip's weights
-  int v_lo = 0, v_hi = 0, v_ch = -1;
-  if (first + lane < last) {
-    v_lo = a.rslab[(first + lane) * 2];
-    v_hi = a.rslab[(first + lane) * 2 + 1];
-  }
-  if (first + (lane >> 2) < last && (lane >> 2) < a.SG) v_ch = a.rstrip[(first + (lane >> 2)) * 4 + (lane & 3)];
-  // all MAXS slots are always requested (steps the strip does not have repeat its last one,
-  // which the cache absorbs): the same loads on every path let the compiler wait for one set
-  // while the other is still arriving
-  auto request = [&](int set, int i_strip) {
-    const int lo = __builtin_amdgcn_readlane(v_lo, i_strip & 63), hi = __builtin_amdgcn_readlane(v_hi, i_strip & 63);
-    nst[set] = hi - lo;
-#pragma unroll
-    for (int i = 0; i < MAXS; ++i) {
-      const int cs = max(0, min(lo + i, hi - 1));
-      ds[set][i] = *(const int*)(descb + ((uint32_t)cs * 16u + desc_lane));
-      ws[set][i] = *(const u32x4_t*)(fragb + ((uint32_t)cs * 1024u + frag_lane));
-    }
-  };
-  const bool any = first < last && a.ncs > 0;
-  if (any) request(0, 0);
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();  // the patch and the tables are in LDS
-  if (!any) return;
-  const int col = pt * 16 + c;
-  const int pixb = colpix[col], cb = colbase[col], rows = colrows[col];
-  const int rowbytes = a.PCp << (a.lscp + 4);
-
-  auto pass = [&](int cur, int i_strip) {
-    request(cur ^ 1, i_strip + 1);  // past the last strip lanes hold 0: a valid step, never used
-    // this lane group's first channel: four lanes per strip in v_ch
-    int ch = __builtin_amdgcn_readlane(v_ch, (i_strip * 4) & 63);
-    ch = g == 1 ? __builtin_amdgcn_readlane(v_ch, (i_strip * 4 + 1) & 63) : ch;
-    ch = g == 2 ? __builtin_amdgcn_readlane(v_ch, (i_strip * 4 + 2) & 63) : ch;
-    ch = g == 3 ? __builtin_amdgcn_readlane(v_ch, (i_strip * 4 + 3) & 63) : ch;
-    f32x4_t bv = {0.f, 0.f, 0.f, 0.f};
-    if (a.bias && ch >= 0) bv = f32x4_t{a.bias[ch], a.bias[ch + 1], a.bias[ch + 2], a.bias[ch + 3]};
-    f32x4_t acc[BR];
-#pragma unroll
-    for (int r = 0; r < BR; ++r) acc[r] = bv;
-    const int n = nst[cur];
-#pragma unroll
-    for (int i = 0; i < MAXS; ++i) {
-      if (i < n) {
-        u32x4_t f[BR];
-        rows_read<1, 1, BR, CW4>(a, lds, (uint32_t)ds[cur][i], pixb, rowbytes, 0u, f);
-#pragma unroll
-        for (int r = 0; r < BR; ++r) acc[r] = mfma_bf16_16x16x32(ws[cur][i], f[r], acc[r]);
-      }
-    }
-    rows_store_direct<BR>(a, acc, ch, cb, rows, false);
-  };
-  const int npass = last - first;
-  for (int i = 0; i < npass; i += 2) {
-    pass(0, i);
-    if (i + 1 < npass) pass(1, i + 1);
-  }
-}
-
 int device_cus() {
   static int cus = 0;
   if (cus == 0) {
@@ -612,19 +516,6 @@ int launch_hs(const RowsArgs& a, int BR, int NT, dim3 grid, int threads, size_t 
   if (BR == 4 && NT == 1) return launch_inst<H, S, 4, 1, CW4, D>(a, grid, threads, ldsb, st);
   if (BR == 4 && NT == 2) return launch_inst<H, S, 4, 2, CW4, D>(a, grid, threads, ldsb, st);
   return BSP_ERR_UNSUPPORTED;
-}
-
-template <int BR, bool CW4>
-int launch_pw_inst(const RowsArgs& a, dim3 grid, int threads, size_t ldsb, hipStream_t st) {
-  static bool raised = false;
-  if (!raised) {
-    if (hipFuncSetAttribute((const void*)conv_rows_pw<BR, CW4, 8>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit) != hipSuccess)
-      return BSP_ERR_HIP;
-    raised = true;
-  }
-  hipLaunchKernelGGL((conv_rows_pw<BR, CW4, 8>), grid, dim3(threads), ldsb, st, a);
-  return hipGetLastError() == hipSuccess ? BSP_OK : BSP_ERR_HIP;
 }
 
 struct Choice {
@@ -744,8 +635,7 @@ static bool rows_choose(const ConvParams& p, const int32_t* rs, int S, Choice* b
   return best->cost < 1e299;
 }
 
-// What both kernels take from the layer, the plan and the chosen tile.  SG / nsg / per_xcd are
-// filled for conv_rows (SG strips per workgroup); the pointwise launcher overrides them.
+// What the kernel takes from the layer, the plan and the chosen tile.
 static int rows_fill_common(const ConvParams& p, const ConvParams& v, const int32_t* hdr, const int32_t* rs, int gs,
                             const Choice& ch, const Geometry& geo, RowsArgs* out) {
   RowsArgs& a = *out;
@@ -829,94 +719,6 @@ static int rows_fill_common(const ConvParams& p, const ConvParams& v, const int3
   return BSP_OK;
 }
 
-// Pointwise layers with one slab: tile and pass choice, then conv_rows_pw.
-static int launch_pw(const ConvParams& p, const ConvParams& v, const int32_t* hdr, const int32_t* rs, int gs,
-                     hipStream_t st) {
-  const int nstrips = rs[BSP_ROWS_NSTRIPS_W], slab = rs[BSP_ROWS_SLAB_W];
-  const double steps = (double)rs[BSP_ROWS_NCS_W] / std::max(1, nstrips);
-  const int cus = device_cus();
-  Choice best{0, 1, 0, 1, 1, 1, 1, 1, 1e300};
-  int best_nq = 1;
-  Geometry bg{};
-  for (int BR : {7, 4})
-    for (int PTW : {1, 2, 4})
-      for (int NQ : {1, 2, 4, 8}) {
-        if (PTW * NQ > 8) continue;
-        for (int SG : {1, 2, 4, 8, 16}) {
-          if (SG > 1 && NQ * (SG / 2) >= nstrips) continue;
-          Choice c{BR, 1, 0, 1, 1, SG, PTW, 1, 0.0};
-          c.NM = 0;
-          const int slots = PTW * 16;
-          if (v.N <= slots) {
-            c.TW = v.N;
-            c.NB = std::min(slots / c.TW, (v.M + BR - 1) / BR);
-          } else {
-            const int parts = (v.N + slots - 1) / slots;
-            c.TW = (v.N + parts - 1) / parts;
-          }
-          Geometry g;
-          Choice cg = c;
-          cg.SG = 1;
-          cg.PTW = PTW;  // geometry wants waves <= 8: SG here is passes, not waves
-          if (!rows_geometry(v, slab, 1, cg, &g)) continue;
-          const int64_t nwg = g.ntiles * ((nstrips + NQ * SG - 1) / (NQ * SG));
-          const int waves = PTW * NQ;
-          const int conc = (int)std::max<int64_t>(1, std::min<int64_t>(kLdsLimit / g.ldsb, 8 / waves));
-          const double t_pass = std::max(steps * 1024.0 / 25.0, steps * BR * 16 / 2.0) + 120.0 + 20.0 * BR;  // ns
-          const double t_wg = 900.0 + (double)g.bufbytes / 80.0 + SG * t_pass;
-          const double rounds = std::ceil((double)nwg / ((double)cus * conc));
-          // workgroups that share a CU slow each other down (one L1, one LDS)
-          c.cost = rounds * t_wg * (1.0 + 0.35 * (std::min<double>(conc, (double)nwg / cus) - 1.0));
-          if (c.cost < best.cost) {
-            best = c;
-            best_nq = NQ;
-            bg = g;
-          }
-        }
-      }
-  if (best.cost > 1e299) return BSP_ERR_UNSUPPORTED;
-#ifdef BSP_ROWS_TUNE
-  if (const char* e = std::getenv("BSP_PW_TUNE")) {
-    int q[4];
-    if (sscanf(e, "%d,%d,%d,%d", q, q + 1, q + 2, q + 3) == 4) {
-      best.BR = q[0];
-      best.PTW = q[1];
-      best_nq = q[2];
-      best.SG = q[3];
-      const int slots = best.PTW * 16;
-      best.NB = 1;
-      if (v.N <= slots) {
-        best.TW = v.N;
-        best.NB = std::min(slots / best.TW, (v.M + best.BR - 1) / best.BR);
-      } else {
-        const int parts = (v.N + slots - 1) / slots;
-        best.TW = (v.N + parts - 1) / parts;
-      }
-      Choice cg = best;
-      cg.SG = 1;
-      if (!rows_geometry(v, slab, 1, cg, &bg)) return BSP_ERR_UNSUPPORTED;
-    }
-  }
-  if (std::getenv("BSP_ROWS_VERBOSE"))
-    fprintf(stderr, "rows pw: M=%d N=%d I=%d O=%d | BR=%d PTW=%d NQ=%d passes=%d TW=%d NB=%d lds=%lld cost=%.0f\n", v.M, v.N,
-            p.I, p.O, best.BR, best.PTW, best_nq, best.SG, best.TW, best.NB, (long long)bg.ldsb, best.cost);
-#endif
-  RowsArgs a{};
-  if (int rc = rows_fill_common(p, v, hdr, rs, gs, best, bg, &a)) return rc;
-  a.nsg = (nstrips + best_nq * best.SG - 1) / (best_nq * best.SG);
-  a.per_xcd = ((a.ntiles + 7) / 8) * a.nsg;
-  a.d_nsg = make_fastdiv(a.nsg);
-  if ((int64_t)a.per_xcd * 8 * std::max(a.nsg, a.tiles_x * a.tiles_y) >= (1ll << 32)) return BSP_ERR_UNSUPPORTED;
-  const int threads = 64 * best.PTW * best_nq;
-  dim3 grid((unsigned)(a.per_xcd * 8));
-  const bool cw4 = rs[BSP_ROWS_CW_W] == 4;
-  if (best.BR == 7)
-    return cw4 ? launch_pw_inst<7, true>(a, grid, threads, (size_t)bg.ldsb, st)
-               : launch_pw_inst<7, false>(a, grid, threads, (size_t)bg.ldsb, st);
-  return cw4 ? launch_pw_inst<4, true>(a, grid, threads, (size_t)bg.ldsb, st)
-             : launch_pw_inst<4, false>(a, grid, threads, (size_t)bg.ldsb, st);
-}
-
 int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st) {
   if (dtype != BSP_BF16 || !plan_host) return BSP_ERR_UNSUPPORTED;
   const int32_t* hdr = (const int32_t*)plan_host;
@@ -929,24 +731,12 @@ int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipSt
   if (p.H != 1 && p.H != 3) return BSP_ERR_UNSUPPORTED;
   if ((int64_t)p.B * p.L * p.J * p.I * 2 >= (1ll << 31) || (int64_t)p.P * p.O * 2 >= (1ll << 31))
     return BSP_ERR_UNSUPPORTED;
-  if (p.P <= 64 && p.H == 1 && p.K == 1) return BSP_ERR_UNSUPPORTED;  // FC layers: streaming kernels
+  if (p.H == 1 && p.K == 1) return BSP_ERR_UNSUPPORTED;  // pointwise layers: bsp_pw.hip
   const int cw = rs[BSP_ROWS_CW_W];
   const int slab = rs[BSP_ROWS_SLAB_W];
-  const bool pointwise = p.H == 1 && p.K == 1;
-  const int S = pointwise ? 1 : p.sh;       // staged pixels per output pixel step
-  const int gs = pointwise ? p.sh : 1;      // input pixels per staged pixel
-  ConvParams v = p;                         // the view the tiles are cut from
-  if (pointwise && p.sh == 1 && p.ph == 0 && p.pw == 0) {
-    // a pointwise layer has no geometry: all pixels as rows of sixteen columns
-    const int W = 16;
-    v.B = 1;
-    v.N = v.J = W;
-    v.M = v.L = (p.P + W - 1) / W;
-  }
-  if (pointwise && rs[BSP_ROWS_NSLABS_W] == 1 && rs[BSP_ROWS_MAXSTRIPSTEPS_W] <= 8) {
-    const int rc = launch_pw(p, v, hdr, rs, gs, st);
-    if (rc != BSP_ERR_UNSUPPORTED) return rc;
-  }
+  const int S = p.sh;   // staged pixels per output pixel step
+  const int gs = 1;     // input pixels per staged pixel
+  const ConvParams& v = p;
   Choice ch;
   if (!rows_choose(v, rs, S, &ch)) return BSP_ERR_UNSUPPORTED;
 #ifdef BSP_ROWS_TUNE  // experiments only: never defined in the product build

@@ -43,21 +43,23 @@ int group_union(const Bits& b, const std::vector<int>& g, std::vector<uint64_t>&
 // Block rows -> strips of `rps` rows with small unions: greedy (heaviest unplaced row
 // first, then the rows that add the fewest new columns), then pairwise swaps between
 // strips while the sum of the unions drops.
-std::vector<std::vector<int>> group_rows(const Bits& bits, int nbr, int rps) {
+// Groups rows first .. first + count - 1 only (a window of output channels), or all of them.
+std::vector<std::vector<int>> group_rows(const Bits& bits, int nbr, int rps, int first = 0, int count = -1) {
   std::vector<std::vector<int>> groups;
+  if (count < 0) count = nbr - first;
   if (rps == 1) {
-    for (int r = 0; r < nbr; ++r) groups.push_back({r});
+    for (int r = first; r < first + count; ++r) groups.push_back({r});
     return groups;
   }
   const int W = bits.words;
-  std::vector<int> order(nbr);
-  std::iota(order.begin(), order.end(), 0);
-  std::vector<int> pc(nbr);
-  for (int r = 0; r < nbr; ++r) pc[r] = popcount1(bits.row(r), W);
+  std::vector<int> order(count);
+  std::iota(order.begin(), order.end(), first);
+  std::vector<int> pc(nbr, 0);
+  for (int r = first; r < first + count; ++r) pc[r] = popcount1(bits.row(r), W);
   std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return pc[a] > pc[b]; });
   std::vector<char> used(nbr, 0);
   std::vector<uint64_t> u(W);
-  for (int oi = 0; oi < nbr; ++oi) {
+  for (int oi = 0; oi < count; ++oi) {
     const int seed = order[oi];
     if (used[seed]) continue;
     used[seed] = 1;
@@ -65,7 +67,7 @@ std::vector<std::vector<int>> group_rows(const Bits& bits, int nbr, int rps) {
     std::copy(bits.row(seed), bits.row(seed) + W, u.begin());
     while ((int)g.size() < rps) {
       int best = -1, best_cost = std::numeric_limits<int>::max();
-      for (int oj = 0; oj < nbr; ++oj) {
+      for (int oj = 0; oj < count; ++oj) {
         const int r = order[oj];
         if (used[r]) continue;
         const int cost = popcount_or(u.data(), bits.row(r), W) * 4096 - pc[r];
@@ -132,7 +134,7 @@ int bsp_rows_section(const int32_t* row_ptr, const int32_t* col_idx, const uint1
   const int cw = bi == 4 ? 4 : 8;              // channels per contraction item
   const int ips = 32 / cw;                     // items per column step: 4 or 8
   const int nunits = (int)cdiv(I, cw);         // contraction units (channel groups) of the layer
-  const int slab = bsp_rows_slab(I, H, K);
+  const int slab = bsp_rows_slab(I, H, K, cw);
   const int upslab = slab / cw;                // units per slab
   const int nslabs = (int)cdiv(nunits, upslab);
   const int64_t HK = (int64_t)H * K;
@@ -148,7 +150,20 @@ int bsp_rows_section(const int32_t* row_ptr, const int32_t* col_idx, const uint1
       const int u0 = c * bi / cw, u1 = std::min<int>(nunits, (c + 1) * bi / cw);
       for (int u = u0; u < u1; ++u) bits.row(r)[u >> 6] |= 1ull << (u & 63);
     }
-  std::vector<std::vector<int>> groups = group_rows(bits, nbr, rps);
+  // Pointwise layers: rows are grouped within windows of 64 output channels, and the strips
+  // of a window stay together, in window order: a workgroup that takes whole windows then
+  // produces whole 128-byte lines of every output pixel.
+  const int wstrips = bsp_rows_window(H, K);
+  std::vector<std::vector<int>> groups;
+  if (wstrips == 0) {
+    groups = group_rows(bits, nbr, rps);
+  } else {
+    const int wrows = wstrips * rps;
+    for (int r0 = 0; r0 < nbr; r0 += wrows) {
+      std::vector<std::vector<int>> g = group_rows(bits, nbr, rps, r0, std::min(wrows, nbr - r0));
+      groups.insert(groups.end(), g.begin(), g.end());
+    }
+  }
   const int nstrips = (int)groups.size();
 
   // per strip: kept units (union), column steps per slab
@@ -174,7 +189,8 @@ int bsp_rows_section(const int32_t* row_ptr, const int32_t* col_idx, const uint1
   // heaviest strips first: a workgroup takes consecutive strips, which then cost alike
   std::vector<int> order(nstrips);
   std::iota(order.begin(), order.end(), 0);
-  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return steps_of[a] > steps_of[b]; });
+  if (wstrips == 0)
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return steps_of[a] > steps_of[b]; });
 
   int64_t ncs = 0;
   for (int t = 0; t < nstrips; ++t) ncs += steps_of[t];
@@ -196,6 +212,7 @@ int bsp_rows_section(const int32_t* row_ptr, const int32_t* col_idx, const uint1
   s[BSP_ROWS_OFF_DESC_W] = (int32_t)off_rdesc;
   s[BSP_ROWS_OFF_FRAG_W] = (int32_t)off_rfrag;
   s[BSP_ROWS_CW_W] = cw;
+  s[BSP_ROWS_WINDOW_W] = wstrips;
   int32_t* rstrip = s + off_rstrip;
   int32_t* rslab = s + off_rslab;
   int32_t* rdesc = s + off_rdesc;

@@ -1,5 +1,5 @@
 """The row-band kernel on its own (bsp_conv2d_only with BSP_KERNEL_ROWS) against the oracle,
-element by element: 3xK and 1xK windows, strides 1 and 2, all granularities, ragged image
+element by element: 3xK and 1xK windows (K > 1), strides 1 and 2, all granularities, ragged image
 sizes and tile tails, empty strips, fused epilogue (needs a GPU)."""
 import numpy as np
 import pytest
@@ -35,9 +35,6 @@ SHAPES = [
     (2, 15, 15, 64, 64, 3, 3, 2, 1),       # stride 2
     (1, 28, 28, 136, 16, 3, 3, 2, 1),      # two slabs, the second with one chunk
     (2, 9, 20, 264, 24, 3, 3, 1, 0),       # no padding, three slabs
-    (4, 14, 14, 256, 128, 1, 1, 1, 0),     # pointwise, flattened
-    (16, 7, 7, 520, 64, 1, 1, 1, 0),       # pointwise, three slabs
-    (2, 28, 28, 64, 256, 1, 1, 2, 0),      # strided pointwise (downsample)
     (2, 12, 12, 32, 16, 1, 3, 1, (0, 1)),  # 1x3
     (2, 12, 12, 32, 16, 3, 1, 1, (1, 0)),  # 3x1
     (1, 17, 17, 128, 64, 1, 7, 1, (0, 3)),  # 1x7
@@ -76,7 +73,7 @@ def test_rows_kernel_empty_block_rows():
 
 def test_rows_kernel_fused_epilogue():
     import torch
-    for (H, K, p) in ((3, 3, 1), (1, 1, 0)):
+    for (H, K, p) in ((3, 3, 1), (1, 3, (0, 1))):
         c = draw_layer("rows", B=2, L=14, J=14, I=64, O=64, H=H, K=K, stride=1, pad=p,
                        dtype="bf16", seed=8400 + H, b_std=0.5)
         rng = np.random.default_rng(1)
@@ -98,6 +95,11 @@ def test_rows_kernel_config1_full_size():
 def test_rows_kernel_declines_what_it_cannot_do():
     c = draw_layer("rows", B=1, L=9, J=9, I=64, O=64, H=5, K=5, stride=1, pad=2, dtype="bf16",
                    seed=1)
+    with pytest.raises(bsp.BspError) as e:
+        _run_rows(c)
+    assert e.value.code == -6
+    # pointwise layers belong to the pointwise kernel
+    c = draw_layer("rows", B=2, L=14, J=14, I=64, O=64, H=1, K=1, stride=1, pad=0, dtype="bf16", seed=1)
     with pytest.raises(bsp.BspError) as e:
         _run_rows(c)
     assert e.value.code == -6
