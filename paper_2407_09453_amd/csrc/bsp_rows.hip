@@ -68,7 +68,19 @@ struct RowsArgs {
   int32_t xlimit, ylimit;          // input / output pixels that exist
   int32_t lsg, lptw;               // log2 of SG and PTW
   FastDiv d_pcp, d_pr, d_np, d_br, d_nsg, d_tpi, d_tx, d_perimg, d_tw;
+#ifdef BSP_ROWS_TUNE
+  long long* trace;
+#endif
 };
+
+#ifdef BSP_ROWS_TUNE
+#define ROWS_MARK(k)                                                                                       \
+  do {                                                                                                     \
+    if (a.trace && (threadIdx.x & 63) == 0) a.trace[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 8 + (k)] = wall_clock64(); \
+  } while (0)
+#else
+#define ROWS_MARK(k)
+#endif
 
 struct TilePos {
   int img0, y0, x0, sgi;
@@ -251,10 +263,14 @@ __global__ __launch_bounds__(640) void conv_rows(RowsArgs a) {
   int32_t* colrows = colbase + nslots;
   int32_t* colpix = colrows + nslots;
   int32_t* chans = colpix + nslots;
+  ROWS_MARK(0);
   rows_tables(a, tp, BR, S, nslots, colbase, colrows, colpix);
+  // the output channels of the workgroup's strips: asked for now, put into LDS only when the
+  // results are (a wait for this load any earlier would also wait for the patch's copies)
+  int chan_v = -1;
   if (tid < a.SG * 4) {
     const int st = tp.sgi * a.SG + (tid >> 2);
-    chans[tid] = st < a.nstrips ? a.rstrip[st * 4 + (tid & 3)] : -1;
+    if (st < a.nstrips) chan_v = a.rstrip[st * 4 + (tid & 3)];
   }
 
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
@@ -272,10 +288,11 @@ __global__ __launch_bounds__(640) void conv_rows(RowsArgs a) {
     for (int r = 0; r < BR; ++r) acc[j][r] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const int rowbytes = a.PCp << (a.lscp + 4);
+  // (cleared pixels and requested pixels are disjoint: no barrier between the two)
   rows_clear_outside(a, tp, lds);
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
+  ROWS_MARK(1);
   rows_stage(a, tp, lds, 0, wave_u, (int)(blockDim.x >> 6));  // the first slab: all waves together
+  ROWS_MARK(2);
 
   if (mover) {
     // ---- the data movers request the next staged slab while the compute waves work on the
@@ -298,7 +315,14 @@ __global__ __launch_bounds__(640) void conv_rows(RowsArgs a) {
     // contraction split KS ways (a power of two) this wave takes the steps whose number is
     // ks modulo KS, so its sequence is one arithmetic progression from start to finish.
     const int ksm = a.KS - 1;
-    const int s_first = __builtin_amdgcn_readlane(vr, 0), s_end = __builtin_amdgcn_readlane(vr, a.nslabs);
+    // the strip's first and last step as scalar loads: they do not queue behind the patch's
+    // copies the way the table above does, and the first weights can be asked for at once
+    uint32_t s_first_u, s_end_u;
+    asm volatile("s_load_dword %0, %2, 0x0\n\ts_load_dword %1, %3, 0x0\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&s"(s_first_u), "=&s"(s_end_u)
+                 : "s"(rsl), "s"(rsl + a.nslabs)
+                 : "memory");
+    const int s_first = (int)s_first_u, s_end = (int)s_end_u;
     int fnext = s_first + ((ks - s_first) & ksm);
     const uint32_t frag_lane = (uint32_t)lane * 16u, desc_lane = (uint32_t)g * 4u;
     const unsigned char* fragb = (const unsigned char*)a.rfrag;
@@ -325,8 +349,11 @@ __global__ __launch_bounds__(640) void conv_rows(RowsArgs a) {
         fetch(d, true);
       }
     }
+    ROWS_MARK(3);
+    if (tid < a.SG * 4) chans[tid] = chan_v;  // (wave 0 is a compute wave)
     __builtin_amdgcn_s_waitcnt(0);  // this wave's share of the first patch has landed
     __syncthreads();                // the first slab's patch and the tables are in LDS
+    ROWS_MARK(4);
     int pixb[NT];
 #pragma unroll
     for (int j = 0; j < NT; ++j) pixb[j] = colpix[(pt * NT + j) * 16 + c];
@@ -390,6 +417,7 @@ __global__ __launch_bounds__(640) void conv_rows(RowsArgs a) {
     }
   }
 
+  ROWS_MARK(5);
   // ---- results: optional sum over the contraction shares, then out
   unsigned char* red = lds;
   unsigned char* ostage = lds + a.red_bytes;
@@ -445,6 +473,7 @@ __global__ __launch_bounds__(640) void conv_rows(RowsArgs a) {
     }
   }
   __syncthreads();
+  ROWS_MARK(6);
   const int nopix = nslots * BR;
   if (!a.piece8) {
     const int np = a.SG * 2;
@@ -479,6 +508,10 @@ __global__ __launch_bounds__(640) void conv_rows(RowsArgs a) {
       *(u32x2_t*)(a.Y + off) = v;
     }
   }
+#ifdef BSP_ROWS_TUNE
+  __builtin_amdgcn_s_waitcnt(0);
+#endif
+  ROWS_MARK(7);
 }
 
 int device_cus() {
@@ -758,6 +791,9 @@ int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipSt
   RowsArgs a{};
   if (int rc = rows_fill_common(p, v, hdr, rs, gs, ch, geo, &a)) return rc;
   a.direct = 0;
+#ifdef BSP_ROWS_TUNE
+  if (const char* e = std::getenv("BSP_PW_TRACE_PTR")) a.trace = (long long*)std::strtoull(e, nullptr, 16);
+#endif
 #ifdef BSP_ROWS_TUNE
   if (std::getenv("BSP_ROWS_DIRECT")) a.direct = 1;
 #endif
