@@ -25,7 +25,9 @@ arithmetic.
 Pins (tests/test_oracle_pins.py): the paper's worked index example for
 Eq. (1); the closed form of Eq. (4); a dense library convolution and matmul
 for the all-ones mask; a scatter-form brute force on tiny shapes; linearity
-over blocks; bias-only for the empty mask.  The stride / padding / output-size
+over blocks; bias-only for the empty mask; the three-layer chain against the
+same chain built from a library convolution with explicit bf16 casts, and
+against a hand case with identity weights.  The stride / padding / output-size
 conventions are not fixed by the paper: for those the oracle is pinned only
 to the usual deep-learning-framework convention (parity unpinned by the
 paper itself).
@@ -146,6 +148,19 @@ def conv2d_fused(X, W, bias, gamma, bo, bi, stride=(1, 1), pad=(0, 0), residual=
     if relu:
         y = np.maximum(y, 0.0)
     return y
+
+
+def bottleneck(X, layers, bo, bi, residual=None, dtype: str = "bf16") -> np.ndarray:
+    """A chain of three layers kept on chip between them (paper Section VI, depth-wise
+    tiling of consecutive layers): 1x1 -> 3x3 (padding 1) -> 1x1, a ReLU after each, the
+    residual added before the last one.  `layers` is [(W, bias, gamma)] * 3.  Tiling does
+    not change the arithmetic: this is the three layers one after the other, each result
+    rounded to the storage type before the next layer reads it (as it would be if it went
+    through memory); returns fp64, the caller's comparison supplying the last rounding."""
+    (W1, b1, g1), (W2, b2, g2), (W3, b3, g3) = layers
+    t1 = round_to_storage(conv2d_fused(X, W1, b1, g1, bo, bi, (1, 1), (0, 0), relu=True, dtype=dtype), dtype)
+    t2 = round_to_storage(conv2d_fused(t1, W2, b2, g2, bo, bi, (1, 1), (1, 1), relu=True, dtype=dtype), dtype)
+    return conv2d_fused(t2, W3, b3, g3, bo, bi, (1, 1), (0, 0), residual=residual, relu=True, dtype=dtype)
 
 
 def conv2d_at(X, W, bias, gamma, bo, bi, positions: np.ndarray,

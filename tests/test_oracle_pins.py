@@ -384,3 +384,68 @@ def test_fused_epilogue_against_library_ops():
     assert (plain == oracle.conv2d(X, W, bias, gamma, 8, 8, (1, 1), (1, 1))).all()
     only_relu = oracle.conv2d_fused(X, W, bias, gamma, 8, 8, (1, 1), (1, 1), relu=True)
     assert (only_relu >= 0).all() and (only_relu[plain > 0.01] > 0).all()
+
+
+def _chain_case(rng, B, L, J, I, C, O, density=0.6):
+    def layer(o, h, i, std):
+        W = oracle.round_to_storage(rng.standard_normal((o, h, h, i)) * std, "bf16")
+        b = rng.standard_normal(o).astype(np.float32) * 0.5
+        g = (rng.random((o // 8, i // 8)) < density).astype(np.uint8)
+        return W, b, g
+    X = oracle.round_to_storage(rng.standard_normal((B, L, J, I)), "bf16")
+    return X, [layer(C, 1, I, 0.2), layer(C, 3, C, 0.1), layer(O, 1, C, 0.2)]
+
+
+def test_bottleneck_chain_against_library_ops():
+    """1x1 -> relu -> 3x3 -> relu -> 1x1 -> + residual -> relu, every layer by torch's fp64
+    convolution and every hand-over by torch's bf16 cast."""
+    import torch
+    rng = np.random.default_rng(33)
+    B, L, J, I, C, O = 2, 7, 9, 32, 16, 32
+    X, layers = _chain_case(rng, B, L, J, I, C, O)
+    R = oracle.round_to_storage(rng.standard_normal((B, L, J, O)), "bf16")
+
+    def tconv(x, W, b, g, pad):
+        Wm = oracle.apply_mask(W, g, 8, 8)
+        y = torch.nn.functional.conv2d(x.permute(0, 3, 1, 2),
+                                       torch.from_numpy(Wm.astype(np.float64)).permute(0, 3, 1, 2),
+                                       torch.from_numpy(b.astype(np.float64)), padding=pad)
+        return y.permute(0, 2, 3, 1).to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+    t = torch.from_numpy(X.astype(np.float64))
+    t = torch.relu(tconv(t, *layers[0], 0))
+    t = torch.relu(tconv(t, *layers[1], 1))
+    want = torch.relu(tconv(t, *layers[2], 0) + torch.from_numpy(R.astype(np.float64))).numpy()
+    got = oracle.bottleneck(X, layers, 8, 8, residual=R)
+    # a bf16 tie moved by the cast's fp32 hop in an early layer can move a later value by a
+    # few ulp: nearly all values agree exactly, the rest within a loose bound
+    assert (np.abs(got - want) > 0).mean() < 0.02
+    assert np.abs(got - want).max() <= 2.0 ** -5 * max(1.0, np.abs(want).max())
+
+
+def test_bottleneck_chain_identity_weights_by_hand():
+    """Identity 1x1 layers and a 3x3 whose only tap is the centre (identity) make the chain
+    relu(relu(x) + r); a 3x3 whose only tap is (0, 0) shifts the image by one pixel down and
+    right, with zeros entering at the top and left edge (padding 1)."""
+    rng = np.random.default_rng(34)
+    B, L, J, C = 1, 5, 6, 8
+    X = oracle.round_to_storage(rng.standard_normal((B, L, J, C)), "bf16")
+    R = oracle.round_to_storage(rng.standard_normal((B, L, J, C)), "bf16")
+    eye = np.eye(C, dtype=np.float32).reshape(C, 1, 1, C)
+    zero = np.zeros(C, dtype=np.float32)
+    ones = np.ones((1, 1), dtype=np.uint8)
+    centre = np.zeros((C, 3, 3, C), dtype=np.float32)
+    centre[:, 1, 1, :] = np.eye(C)
+    got = oracle.bottleneck(X, [(eye, zero, ones), (centre, zero, ones), (eye, zero, ones)], 8, 8, residual=R)
+    assert (got == np.maximum(np.maximum(X, 0) + R, 0)).all()
+    corner = np.zeros((C, 3, 3, C), dtype=np.float32)
+    corner[:, 0, 0, :] = np.eye(C)
+    got = oracle.bottleneck(X, [(eye, zero, ones), (corner, zero, ones), (eye, zero, ones)], 8, 8)
+    want = np.zeros_like(X, dtype=np.float64)
+    want[:, 1:, 1:, :] = np.maximum(X, 0)[:, :-1, :-1, :]
+    assert (got == want).all()
+    # a zero mask on the middle layer leaves only biases: relu(b3 + W3 relu(b2))
+    b2 = np.arange(C, dtype=np.float32) - 3
+    b3 = np.full(C, 0.25, dtype=np.float32)
+    got = oracle.bottleneck(X, [(eye, zero, ones), (centre, b2, np.zeros((1, 1), np.uint8)), (eye, b3, ones)], 8, 8)
+    assert (got == np.broadcast_to(np.maximum(np.maximum(b2, 0) + b3, 0).astype(np.float64), got.shape)).all()
