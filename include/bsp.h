@@ -220,6 +220,26 @@ int bsp_conv2d_only(const bsp_weights* w, const void* X, const float* bias, cons
                     int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
                     int32_t family, void* stream);
 
+/* Three consecutive layers on one output tile, the two intermediates kept on chip (paper
+ * Section VI: depth-wise tiling of consecutive layers, tiles never leaving the chip between
+ * them).  The chain is 1x1 (w1: I -> C), 3x3 with stride 1 and padding 1 (w2: C -> C), 1x1
+ * (w3: C -> O):
+ *   T1 = act(round(conv(X, w1) + bias1)),  T2 = act(round(conv(T1, w2) + bias2)),
+ *   Y  = round(act(round(conv(T2, w3) + bias3) + residual))
+ * with act = ReLU when relu != 0 and the identity otherwise: exactly what three bsp_conv2d
+ * calls with the fused epilogue give (each intermediate is rounded to bf16 where it would
+ * have been stored), without T1 and T2 ever reaching memory.
+ *   w1, w2, w3   bf16 layers with 8x8 or 4x16 blocks and plans from bsp_plan_build
+ *   X            device [B][L][J][I] bf16;  Y device [B][L][J][O] bf16
+ *   bias1..3     device float or null;  residual device, shape and type of Y, or null
+ * Returns BSP_ERR_UNSUPPORTED, with nothing launched, when the chain is not of this form or
+ * its intermediates do not fit the 160 KB of LDS (the caller then runs the layers one by one).
+ * Asynchronous.  Errors: NULL, SHAPE, UNSUPPORTED, DTYPE, ALIGN, HIP. */
+int bsp_bottleneck(const bsp_weights* w1, const bsp_weights* w2, const bsp_weights* w3,
+                   const void* X, const float* bias1, const float* bias2, const float* bias3,
+                   const void* residual, int32_t relu, void* Y,
+                   int32_t B, int32_t L, int32_t J, void* stream);
+
 /* ------------------------------------------- block-sparse x block-sparse product
  * Paper Section III-A: C = (Gamma A) (Omega B)^t with k x k blocks; a block product is done
  * if and only if both blocks are kept (the paper merges the two sorted lists of kept block

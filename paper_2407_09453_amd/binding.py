@@ -28,7 +28,7 @@ EXPORTS = ("bsp_strerror", "bsp_version", "bsp_pack_count", "bsp_pack", "bsp_unp
            "bsp_conv2d_general", "bsp_quantize", "bsp_conv2d_i8", "bsp_fc_i8",
            "bsp_block_importance", "bsp_select_mask", "bsp_mask_step", "bsp_conv2d_fused",
            "bsp_fc_fused", "bsp_bcsr_index", "bsp_spgemm_nt",
-           "bsp_conv2d_only", "bsp_bench_copy", "bsp_bench_mfma_bf16", "bsp_bench_lds_read")
+           "bsp_conv2d_only", "bsp_bottleneck", "bsp_bench_copy", "bsp_bench_mfma_bf16", "bsp_bench_lds_read")
 
 
 class BspError(RuntimeError):
@@ -111,6 +111,8 @@ def load_library():
     lib.bsp_conv2d_only.restype = ctypes.c_int
     lib.bsp_conv2d_only.argtypes = [wp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, i32,
                                     i32, vp]
+    lib.bsp_bottleneck.restype = ctypes.c_int
+    lib.bsp_bottleneck.argtypes = [wp, wp, wp, vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, vp]
     lib.bsp_fc_fused.restype = ctypes.c_int
     lib.bsp_fc_fused.argtypes = [wp, vp, vp, vp, i32, vp, i32, vp]
     lib.bsp_block_importance.restype = ctypes.c_int
@@ -318,6 +320,34 @@ def bsp_conv2d_only(w: bsp_weights, X: int, bias: Optional[int], residual: Optio
     _check(load_library().bsp_conv2d_only(ctypes.byref(w), X, bias, residual, int(relu), Y, B, L,
                                           J, stride[0], stride[1], pad[0], pad[1], family, stream),
            "bsp_conv2d_only")
+
+
+def bsp_bottleneck(w1: bsp_weights, w2: bsp_weights, w3: bsp_weights, X: int,
+                   bias1: Optional[int], bias2: Optional[int], bias3: Optional[int],
+                   residual: Optional[int], relu: bool, Y: int, B: int, L: int, J: int,
+                   stream: int = 0) -> None:
+    _check(load_library().bsp_bottleneck(ctypes.byref(w1), ctypes.byref(w2), ctypes.byref(w3), X,
+                                         bias1, bias2, bias3, residual, int(relu), Y, B, L, J,
+                                         stream), "bsp_bottleneck")
+
+
+def bottleneck(l1: "BspLayer", l2: "BspLayer", l3: "BspLayer", X, residual=None, relu=True,
+               out=None, stream=None):
+    """Marshals three BspLayers (1x1, 3x3, 1x1) and torch tensors into bsp_bottleneck."""
+    import torch
+    assert X.is_contiguous() and X.dtype == torch.bfloat16 and X.shape[-1] == l1.I
+    B, L, J, _ = X.shape
+    if out is None:
+        out = torch.empty((B, L, J, l3.O), dtype=torch.bfloat16, device=X.device)
+    if residual is not None:
+        assert residual.is_contiguous() and residual.dtype == out.dtype and residual.shape == out.shape
+    st = torch.cuda.current_stream(X.device).cuda_stream if stream is None else stream
+
+    def bp(l):
+        return None if l.d_bias is None else l.d_bias.data_ptr()
+    bsp_bottleneck(l1.struct, l2.struct, l3.struct, X.data_ptr(), bp(l1), bp(l2), bp(l3),
+                   None if residual is None else residual.data_ptr(), relu, out.data_ptr(), B, L, J, st)
+    return out
 
 
 def bsp_conv2d_general(w: bsp_weights, X: int, bias: Optional[int], Y: int, B: int, L: int,

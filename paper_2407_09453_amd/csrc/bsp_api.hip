@@ -108,6 +108,25 @@ int bsp_conv2d_general(const bsp_weights* w, const void* X, const float* bias, v
   return bsp_launch_general(p, w->dtype, w->bo, w->bi, (hipStream_t)stream);
 }
 
+int bsp_bottleneck(const bsp_weights* w1, const bsp_weights* w2, const bsp_weights* w3, const void* X,
+                   const float* bias1, const float* bias2, const float* bias3, const void* residual,
+                   int32_t relu, void* Y, int32_t B, int32_t L, int32_t J, void* stream) {
+  if (!w1 || !w2 || !w3) return BSP_ERR_NULL;
+  for (const bsp_weights* w : {w1, w2, w3}) {
+    if (!w->plan || !w->plan_host) return BSP_ERR_NULL;
+    if (w->dtype != BSP_BF16) return w->dtype == BSP_F32 ? BSP_ERR_UNSUPPORTED : BSP_ERR_DTYPE;
+    if (!aligned16(w->plan)) return BSP_ERR_ALIGN;
+  }
+  if (B < 0 || L < 1 || J < 1) return BSP_ERR_SHAPE;
+  if (B == 0) return BSP_OK;
+  if (!X || !Y) return BSP_ERR_NULL;
+  if (!aligned16(X) || !aligned16(Y) || (residual && !aligned16(residual))) return BSP_ERR_ALIGN;
+  for (const float* b : {bias1, bias2, bias3})
+    if (reinterpret_cast<uintptr_t>(b) & 3u) return BSP_ERR_ALIGN;
+  return bsp_launch_chain(w1, w2, w3, X, bias1, bias2, bias3, residual, Y, B, L, J, relu != 0,
+                          (hipStream_t)stream);
+}
+
 int bsp_conv2d_only(const bsp_weights* w, const void* X, const float* bias, const void* residual,
                     int32_t relu, void* Y, int32_t B, int32_t L, int32_t J, int32_t stride_h,
                     int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t family, void* stream) {

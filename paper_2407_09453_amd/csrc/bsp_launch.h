@@ -34,6 +34,12 @@ int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipSt
 // slab of the row-band section).  BSP_ERR_UNSUPPORTED = not applicable, nothing launched.
 int bsp_launch_pw(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);
 
+// Three-layer chain 1x1 -> 3x3 -> 1x1 with the intermediates in LDS (bsp_chain.hip).
+// BSP_ERR_UNSUPPORTED = not of that form or too large for LDS, nothing launched.
+int bsp_launch_chain(const bsp_weights* w1, const bsp_weights* w2, const bsp_weights* w3, const void* X,
+                     const float* bias1, const float* bias2, const float* bias3, const void* residual, void* Y,
+                     int B, int L, int J, int relu, hipStream_t st);
+
 // 8-bit integer layers: X and payload int8, bias int32 (passed through ConvParams::bias),
 // Y int8 after a rounding right shift (y_i8 = 1) or the int32 sums.
 int bsp_launch_i8(const ConvParams& p, int y_i8, int shift, int bo, int bi, hipStream_t st);
