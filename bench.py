@@ -290,6 +290,74 @@ def bench_spgemm(args) -> int:
     return 0
 
 
+def bench_bottleneck(args) -> int:
+    """ResNet50-shaped bottlenecks (layer1: 256 -> 64 -> 256 on 56x56, layer3: 1024 -> 256 ->
+    1024 on 14x14; batch 32, 8x8 blocks, half kept): bsp_bottleneck, which keeps the two
+    intermediates in LDS, against the same three layers launched one by one."""
+    import torch
+    import paper_2407_09453_amd as bsp
+    from synthetic import draw_layer
+
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(2407)
+    out = []
+    for name, (B, L, J, I, C, O) in (("layer1", (32, 56, 56, 256, 64, 256)),
+                                     ("layer3", (32, 14, 14, 1024, 256, 1024))):
+        specs = ((I, C, 1, 0), (C, C, 3, 1), (C, O, 1, 0))
+        cs = [draw_layer(f"{name}.{k}", B=1, L=3, J=3, I=i, O=o, H=h, K=h, pad=p, dtype="bf16",
+                         mask_kind="exact", density=0.5, seed=7700 + k, b_std=0.3)
+              for k, (i, o, h, p) in enumerate(specs)]
+        ls = [bsp.BspLayer(c.W, c.gamma, 8, 8, "bf16", bias=c.bias) for c in cs]
+        nb = 3
+        Xs = [torch.randn((B, L, J, I), device=dev, generator=gen).to(torch.bfloat16) for _ in range(nb)]
+        Ys = [torch.empty((B, L, J, O), dtype=torch.bfloat16, device=dev) for _ in range(nb)]
+        T1 = torch.empty((B, L, J, C), dtype=torch.bfloat16, device=dev)
+        T2 = torch.empty_like(T1)
+
+        def fused(i, st):
+            bsp.bottleneck(ls[0], ls[1], ls[2], Xs[i % nb], residual=Xs[i % nb], relu=True,
+                           out=Ys[i % nb], stream=st, force=True)
+
+        def separate(i, st):
+            ls[0].conv2d(Xs[i % nb], out=T1, relu=True, stream=st)
+            ls[1].conv2d(T1, (1, 1), (1, 1), out=T2, relu=True, stream=st)
+            ls[2].conv2d(T2, out=Ys[i % nb], residual=Xs[i % nb], relu=True, stream=st)
+
+        res = {}
+        for key, fn in (("fused", fused), ("separate", separate)):
+            ts = [time_launches(fn, args.steps, args.warmup, dev)[1] * 1e3 for _ in range(5)]
+            res[key] = float(np.median(ts))
+        P = B * L * J
+        flops = 2 * P * sum(l.nnzb * 64 * c.H * c.K for l, c in zip(ls, cs))
+        wbytes = sum(l.nnzb * 128 * c.H * c.K for l, c in zip(ls, cs))
+        # one read of X (also the residual), one write of Y; separately T1 and T2 also go out and back
+        by_fused = P * (I + O) * 2 + wbytes
+        by_sep = P * (I + 2 * C + 2 * C + O + O) * 2 + wbytes
+        floor = max(flops / (MFMA_BF16_PEAK_TFLOPS * 1e12), by_fused / (HBM_PEAK_GBS * 1e9)) * 1e6
+        out.append({"block": name, "shape": f"{I}->{C}->{O} on {B}x{L}x{J}",
+                    "fused_us": round(res["fused"], 2), "separate_us": round(res["separate"], 2),
+                    "speedup": round(res["separate"] / res["fused"], 3),
+                    "TFLOPs_nz": round(flops / res["fused"] / 1e6, 2),
+                    "algorithmic_MB_fused": round(by_fused / 1e6, 2),
+                    "algorithmic_MB_separate": round(by_sep / 1e6, 2),
+                    "floor_us": round(floor, 2), "roofline_frac": round(floor / res["fused"], 4)})
+    b1 = out[0]
+    print(json.dumps({
+        "metric": "effective nonzero TFLOP/s of a fused ResNet50 layer1 bottleneck (1x1 -> 3x3 -> 1x1 + residual)",
+        "value": b1["TFLOPs_nz"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(b1["fused_us"] / 1e3, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "ResNet50-shaped bottlenecks, batch 32, 8x8 blocks, half kept; "
+                               "one launch with the intermediates in LDS against three launches"},
+        "roofline": {"bound": "hbm", "achieved": round(b1["algorithmic_MB_fused"] / b1["fused_us"] * 1e3, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(b1["algorithmic_MB_fused"] / b1["fused_us"] * 1e3 / HBM_PEAK_GBS, 5),
+                     "traffic": None},
+        "blocks": out}))
+    return 0
+
+
 def network_rows(args, net: str, peaks, reps: int = 20):
     """Per-layer timing of a whole network-shaped stack: every layer on its own resident
     N(0,1) input (layers are independent: glue such as pooling is not part of the path), the
@@ -396,7 +464,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c1",
-                    help="c1 (default), c0, c2:<bo>x<bi>.d<density>, c1_i8, spgemm, resnet50, vgg16, inception_v3, "
+                    help="c1 (default), c0, c2:<bo>x<bi>.d<density>, c1_i8, spgemm, bottleneck, resnet50, vgg16, inception_v3, "
                          "or one layer of a stack as <net>:<layer name>")
     ap.add_argument("--sets", type=int, default=0,
                     help="distinct X/Y buffer sets cycled through (0 = enough to exceed 256 MB)")
@@ -431,6 +499,10 @@ def main() -> int:
         if args.steps == 400:
             args.steps, args.warmup = 50, 5
         return bench_spgemm(args)
+    if args.workload == "bottleneck":
+        if args.steps == 400:
+            args.steps, args.warmup = 30, 5
+        return bench_bottleneck(args)
     if args.workload in ("resnet50", "vgg16", "inception_v3"):
         if args.steps == 400:
             args.steps, args.warmup = 30, 5

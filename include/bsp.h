@@ -161,7 +161,9 @@ enum bsp_kernel_family {
   BSP_KERNEL_LDS = 2,   /* weights and activations of a slab resident in LDS */
   BSP_KERNEL_TILE = 4,  /* weights streamed through a register ring */
   BSP_KERNEL_FC = 8,    /* weight-streaming kernels for layers with at most 64 output pixels */
-  BSP_KERNEL_PW = 16    /* pointwise layers: all input channels of a pixel tile resident in LDS */
+  BSP_KERNEL_PW = 16,   /* pointwise layers: all input channels of a pixel tile resident in LDS */
+  BSP_KERNEL_CHAIN = 32 /* bsp_bottleneck only: run the fused chain even where the library
+                           expects the three layers one by one to be faster */
 };
 
 /* Fully-connected layer Y[B][O] = X[B][I] . (Gamma W-bar)^T + bias, work done
@@ -232,8 +234,11 @@ int bsp_conv2d_only(const bsp_weights* w, const void* X, const float* bias, cons
  *   w1, w2, w3   bf16 layers with 8x8 or 4x16 blocks and plans from bsp_plan_build
  *   X            device [B][L][J][I] bf16;  Y device [B][L][J][O] bf16
  *   bias1..3     device float or null;  residual device, shape and type of Y, or null
- * Returns BSP_ERR_UNSUPPORTED, with nothing launched, when the chain is not of this form or
- * its intermediates do not fit the 160 KB of LDS (the caller then runs the layers one by one).
+ * Returns BSP_ERR_UNSUPPORTED, with nothing launched, when the chain is not of this form, when
+ * its intermediates do not fit the 160 KB of LDS, or when streaming the three layers' weights
+ * once per output band would cost more memory traffic than keeping the intermediates on chip
+ * saves (deep layers on small images); the caller then runs the layers one by one.  Setting
+ * BSP_KERNEL_CHAIN in the `kernels` field of any of the three overrides the last reason.
  * Asynchronous.  Errors: NULL, SHAPE, UNSUPPORTED, DTYPE, ALIGN, HIP. */
 int bsp_bottleneck(const bsp_weights* w1, const bsp_weights* w2, const bsp_weights* w3,
                    const void* X, const float* bias1, const float* bias2, const float* bias3,

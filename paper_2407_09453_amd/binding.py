@@ -18,6 +18,7 @@ BSP_BF16 = 1
 BSP_I8 = 2
 BSP_I32 = 3
 BSP_KERNEL_ROWS, BSP_KERNEL_LDS, BSP_KERNEL_TILE, BSP_KERNEL_FC, BSP_KERNEL_PW = 1, 2, 4, 8, 16
+BSP_KERNEL_CHAIN = 32
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libbsp.so")
@@ -332,8 +333,9 @@ def bsp_bottleneck(w1: bsp_weights, w2: bsp_weights, w3: bsp_weights, X: int,
 
 
 def bottleneck(l1: "BspLayer", l2: "BspLayer", l3: "BspLayer", X, residual=None, relu=True,
-               out=None, stream=None):
-    """Marshals three BspLayers (1x1, 3x3, 1x1) and torch tensors into bsp_bottleneck."""
+               out=None, stream=None, force=False):
+    """Marshals three BspLayers (1x1, 3x3, 1x1) and torch tensors into bsp_bottleneck.
+    ``force`` sets BSP_KERNEL_CHAIN for the call."""
     import torch
     assert X.is_contiguous() and X.dtype == torch.bfloat16 and X.shape[-1] == l1.I
     B, L, J, _ = X.shape
@@ -345,8 +347,14 @@ def bottleneck(l1: "BspLayer", l2: "BspLayer", l3: "BspLayer", X, residual=None,
 
     def bp(l):
         return None if l.d_bias is None else l.d_bias.data_ptr()
-    bsp_bottleneck(l1.struct, l2.struct, l3.struct, X.data_ptr(), bp(l1), bp(l2), bp(l3),
-                   None if residual is None else residual.data_ptr(), relu, out.data_ptr(), B, L, J, st)
+    saved = l1.struct.kernels
+    if force:
+        l1.struct.kernels = saved | BSP_KERNEL_CHAIN
+    try:
+        bsp_bottleneck(l1.struct, l2.struct, l3.struct, X.data_ptr(), bp(l1), bp(l2), bp(l3),
+                       None if residual is None else residual.data_ptr(), relu, out.data_ptr(), B, L, J, st)
+    finally:
+        l1.struct.kernels = saved
     return out
 
 

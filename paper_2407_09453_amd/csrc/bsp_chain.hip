@@ -21,6 +21,7 @@
 #include "bsp_tile.h"
 
 #include <algorithm>
+#include <cstdlib>
 
 namespace {
 
@@ -31,6 +32,7 @@ struct LayerPlan {
   const unsigned char* rfrag;
   const float* bias;
   int32_t nstrips, nslabs, sc;  // sc: 16-byte pieces per slab
+  int64_t wbytes;               // weight fragments of the whole layer
 };
 
 struct ChainArgs {
@@ -44,17 +46,49 @@ struct ChainArgs {
   int32_t CT;                        // lane tiles per chunk of phase A
   int32_t pitchX, xs_shift, xs_mask; // staged input pixel: bytes, swizzle
   int32_t pitchC, cs_shift, cs_mask; // T1 / T2 pixel
-  int32_t xbuf;                      // bytes of one chunk buffer
+  int32_t xbuf, nbuf;                // bytes of one chunk buffer; how many there are (2 or 4)
+  int32_t odbl;                      // two output images in phase C (one barrier per round) or one (two)
+  int32_t adv_pix, adv_rem;          // 4096 / pitchX and 4096 % pitchX: from one request of a mover to its next
   int32_t t1_off;                    // LDS offset of T1 (and of the output image of phase C)
   int32_t opitch;                    // bytes per pixel of the output image
   int32_t relu;
   FastDiv d_J, d_pitchX, d_ct;
+#ifdef BSP_ROWS_TUNE
+  long long* trace;
+#endif
 };
+
+#ifdef BSP_ROWS_TUNE
+#define CH_MARK(k)                                                                                   \
+  do {                                                                                               \
+    if (a.trace && lane == 0) a.trace[((size_t)blockIdx.x * 16 + wave) * 8 + (k)] = wall_clock64(); \
+  } while (0)
+#else
+#define CH_MARK(k)
+#endif
 
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 constexpr int kComputeA = 12;  // compute waves of phase A; the other four move data
+
+// Four bf16 results (v) plus four residual values already in registers (r), the activation,
+// one more rounding: post_bf16x4's arithmetic without a trip through memory.
+__device__ __forceinline__ u32x2_t post_reg(u32x2_t v, u32x2_t r, bool has_r, int relu) {
+  float f[4] = {bf16_bits_to_f32((uint16_t)(v.x & 0xFFFF)), bf16_bits_to_f32((uint16_t)(v.x >> 16)),
+                bf16_bits_to_f32((uint16_t)(v.y & 0xFFFF)), bf16_bits_to_f32((uint16_t)(v.y >> 16))};
+  if (has_r) {
+    f[0] += bf16_bits_to_f32((uint16_t)(r.x & 0xFFFF));
+    f[1] += bf16_bits_to_f32((uint16_t)(r.x >> 16));
+    f[2] += bf16_bits_to_f32((uint16_t)(r.y & 0xFFFF));
+    f[3] += bf16_bits_to_f32((uint16_t)(r.y >> 16));
+  }
+  if (relu) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) f[k] = fmaxf(f[k], 0.f);
+  }
+  return u32x2_t{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3])};
+}
 
 template <int BR>
 __global__ __launch_bounds__(1024) void conv_chain(ChainArgs a) {
@@ -73,35 +107,64 @@ __global__ __launch_bounds__(1024) void conv_chain(ChainArgs a) {
   unsigned char* T2 = lds;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
 
+  CH_MARK(0);
   // ---- T1's border must read as zero: clear all of it (phase A overwrites the inside)
   {
     const int n16 = ((BR + 2) * a.Jp * a.pitchC) >> 4;
     for (int i = tid; i < n16; i += (int)blockDim.x) ((u32x4_t*)T1)[i] = u32x4_t{0, 0, 0, 0};
   }
 
+  CH_MARK(1);
   // ================= phase A
   if (wave >= kComputeA) {
-    // ---- data movers: chunk k goes to buffer k & 1; barrier k tells the compute waves it has
-    // landed and tells the movers that chunk k - 1 has been consumed (its buffer is free)
-    const int mw = wave - kComputeA, nmw = 16 - kComputeA;
+    // ---- data movers: chunk k goes to buffer k % nbuf; its KiB requests are dealt out to the
+    // four movers (request rq to mover rq % 4), so that asking for a chunk is short.  Barrier k
+    // tells the compute waves that chunk k has landed and everybody that chunk k - 1 has been
+    // consumed: its buffer then takes chunk k + nbuf - 1, nbuf - 1 chunks being in flight while
+    // one is worked on.  A wave's copies complete in order, so "chunk k has landed" is "at
+    // most as many of my requests are outstanding as I made for the chunks after it"; for
+    // the last chunks (one of which may have requests that are skipped) that is zero.
+    const int mw = wave - kComputeA;
     const int nreq = (CH * a.pitchX) >> 10;
+    const int nbm = a.nbuf - 1;  // (two or four buffers)
+    const int per = (nreq - mw + 3) >> 2;  // my requests per chunk
     auto request = [&](int k) {
-      const uint32_t buf = lds0 + (uint32_t)(k & 1) * (uint32_t)a.xbuf;
-      for (int rq = mw; rq < nreq; rq += nmw) {
-        const uint32_t o = (uint32_t)rq * 1024u + (uint32_t)lane * 16u;
-        const uint32_t lp = fdiv(o, a.d_pitchX);
-        const uint32_t piece = ((o - lp * (uint32_t)a.pitchX) >> 4) ^ ((lp >> a.xs_shift) & (uint32_t)a.xs_mask);
+      const uint32_t buf = lds0 + (uint32_t)(k & nbm) * (uint32_t)a.xbuf;
+      const uint32_t o0 = (uint32_t)mw * 1024u + (uint32_t)lane * 16u;
+      uint32_t lp = fdiv(o0, a.d_pitchX);
+      uint32_t rem = o0 - lp * (uint32_t)a.pitchX;
+      for (int rq = mw; rq < nreq; rq += 4) {
+        const uint32_t piece = (rem >> 4) ^ ((lp >> a.xs_shift) & (uint32_t)a.xs_mask);
         const uint32_t q = (uint32_t)k * (uint32_t)CH + lp;
         if (q < (uint32_t)npx && piece * 8u < (uint32_t)a.I)
           __builtin_amdgcn_global_load_lds((gptr_t)(a.X + ((gp0 + q) * (uint32_t)a.I + piece * 8u) * 2u),
                                            (lptr_t)(uintptr_t)(buf + (uint32_t)rq * 1024u), 16, 0, 0);
+        rem += (uint32_t)a.adv_rem;
+        lp += (uint32_t)a.adv_pix;
+        if (rem >= (uint32_t)a.pitchX) {
+          rem -= (uint32_t)a.pitchX;
+          ++lp;
+        }
       }
     };
-    request(0);
+    // wait until at most n of this wave's copies are outstanding (n a multiple of `per`)
+    auto wait_le = [&](int n) {
+      switch (n) {
+#define BSP_CASE(v) \
+  case v: __builtin_amdgcn_s_waitcnt(0x0F70 | ((v) & 15) | (((v) >> 4) << 14)); break;
+        BSP_CASE(1) BSP_CASE(2) BSP_CASE(3) BSP_CASE(4) BSP_CASE(6) BSP_CASE(8) BSP_CASE(9) BSP_CASE(12)
+        BSP_CASE(16) BSP_CASE(18) BSP_CASE(24) BSP_CASE(32) BSP_CASE(36) BSP_CASE(48)
+#undef BSP_CASE
+        default: __builtin_amdgcn_s_waitcnt(0); break;
+      }
+    };
+    for (int k = 0; k < nbm && k < nch; ++k) request(k);  // the first chunks
     for (int k = 0; k < nch; ++k) {
-      __builtin_amdgcn_s_waitcnt(0);
-      __syncthreads();  // barrier k
-      if (k + 1 < nch) request(k + 1);
+      const int after = min(nbm - 1, nch - 1 - k);  // chunks asked for after chunk k so far
+      if (k + nbm >= nch) __builtin_amdgcn_s_waitcnt(0);
+      else wait_le(after * per);
+      __builtin_amdgcn_s_barrier();  // barrier k (the bare instruction: a fence would wait for every copy in flight)
+      if (k + nbm < nch) request(k + nbm);
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();  // T1 is complete
@@ -127,16 +190,30 @@ __global__ __launch_bounds__(1024) void conv_chain(ChainArgs a) {
     };
     const bool mine = wave < nitems;
     Item first = setup(mine ? wave : 0);
+    // A wave with a single item whose strip has at most eight steps keeps that strip's
+    // weights in registers for all chunks.
+    const bool resident = nitems <= kComputeA && first.hi - first.lo <= 8;
+    u32x4_t wres[8];
+    int dres[8];
+#pragma unroll
+    for (int d = 0; d < 8; ++d) {
+      wres[d] = u32x4_t{0, 0, 0, 0};
+      dres[d] = 0;
+      if (resident && mine && first.lo + d < first.hi) {
+        dres[d] = *(const int*)(a.l1.rdesc + ((uint32_t)(first.lo + d) * 16u + (uint32_t)g * 4u));
+        wres[d] = *(const u32x4_t*)(a.l1.rfrag + ((uint32_t)(first.lo + d) * 1024u + (uint32_t)lane * 16u));
+      }
+    }
     for (int k = 0; k < nch; ++k) {
-      // the first item's first step, asked for before the wait for the chunk
+      // (streamed weights) the first item's first step, asked for before the wait for the chunk
       int d0 = 0;
       u32x4_t w0 = {0, 0, 0, 0};
-      if (mine && first.lo < first.hi) {
+      if (!resident && mine && first.lo < first.hi) {
         d0 = *(const int*)(a.l1.rdesc + ((uint32_t)first.lo * 16u + (uint32_t)g * 4u));
         w0 = *(const u32x4_t*)(a.l1.rfrag + ((uint32_t)first.lo * 1024u + (uint32_t)lane * 16u));
       }
       __syncthreads();  // barrier k (the clearing of T1 above is also behind it)
-      const unsigned char* xb = lds + (k & 1) * a.xbuf;
+      const unsigned char* xb = lds + (k & (a.nbuf - 1)) * a.xbuf;
       for (int item = wave; item < nitems; item += kComputeA) {
         Item it = first;
         if (item != wave) {
@@ -150,14 +227,25 @@ __global__ __launch_bounds__(1024) void conv_chain(ChainArgs a) {
         const uint32_t swz = ((uint32_t)lp >> a.xs_shift) & (uint32_t)a.xs_mask;
         const uint32_t base = (uint32_t)lp * (uint32_t)a.pitchX;
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-        for (int cs = it.lo; cs < it.hi; ++cs) {  // one step ahead
-          const int nx = min(cs + 1, it.hi - 1);
-          const int d1 = *(const int*)(a.l1.rdesc + ((uint32_t)nx * 16u + (uint32_t)g * 4u));
-          const u32x4_t w1 = *(const u32x4_t*)(a.l1.rfrag + ((uint32_t)nx * 1024u + (uint32_t)lane * 16u));
-          const u32x4_t f = *(const u32x4_t*)(xb + base + ((((uint32_t)d0 & 0xFFu) ^ swz) << 4));
-          acc = mfma_bf16_16x16x32(w0, f, acc);
-          d0 = d1;
-          w0 = w1;
+        if (resident) {
+          const int ns = it.hi - it.lo;
+          u32x4_t f[8];
+#pragma unroll
+          for (int d = 0; d < 8; ++d)
+            if (d < ns) f[d] = *(const u32x4_t*)(xb + base + ((((uint32_t)dres[d] & 0xFFu) ^ swz) << 4));
+#pragma unroll
+          for (int d = 0; d < 8; ++d)
+            if (d < ns) acc = mfma_bf16_16x16x32(wres[d], f[d], acc);
+        } else {
+          for (int cs = it.lo; cs < it.hi; ++cs) {  // one step ahead
+            const int nx = min(cs + 1, it.hi - 1);
+            const int d1 = *(const int*)(a.l1.rdesc + ((uint32_t)nx * 16u + (uint32_t)g * 4u));
+            const u32x4_t w1 = *(const u32x4_t*)(a.l1.rfrag + ((uint32_t)nx * 1024u + (uint32_t)lane * 16u));
+            const u32x4_t f = *(const u32x4_t*)(xb + base + ((((uint32_t)d0 & 0xFFu) ^ swz) << 4));
+            acc = mfma_bf16_16x16x32(w0, f, acc);
+            d0 = d1;
+            w0 = w1;
+          }
         }
         // bias, ReLU, one rounding, into T1 (zero border untouched)
         const int q = k * CH + lp;
@@ -176,6 +264,7 @@ __global__ __launch_bounds__(1024) void conv_chain(ChainArgs a) {
     __syncthreads();  // T1 is complete
   }
 
+  CH_MARK(2);
   // ================= phase B: 3x3 from T1 into T2 (which reuses the chunk buffers)
   {
     const int ctb = (a.J + 15) >> 4;  // column tiles
@@ -239,7 +328,9 @@ __global__ __launch_bounds__(1024) void conv_chain(ChainArgs a) {
       }
     }
   }
+  CH_MARK(3);
   __syncthreads();  // T2 is complete, T1 is free
+  CH_MARK(4);
 
   // ================= phase C: 1x1 from T2, a round of 64 pixels x 16 strips at a time
   {
@@ -267,7 +358,22 @@ __global__ __launch_bounds__(1024) void conv_chain(ChainArgs a) {
         df1 = *(const int*)(a.l3.rdesc + ((uint32_t)s1 * 16u + (uint32_t)g * 4u));
         wf1 = *(const u32x4_t*)(a.l3.rfrag + ((uint32_t)s1 * 1024u + (uint32_t)lane * 16u));
       }
+      const int cpp = min(32, (a.O - range0) >> 3);  // 16-byte pieces per pixel in this pass
       for (int round = 0; round < nrounds; ++round) {
+        // what this thread will write at the end of the round, and the residual that goes
+        // with it: asked for now, used after the round's arithmetic
+        bool ovalid[2];
+        uint32_t ooff[2];
+        u32x4_t res[2];
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+          const int i = tid + it * 1024, pixel = i >> 5, kk = i & 31;
+          const int p2 = round * 64 + pixel;
+          ovalid[it] = kk < cpp && p2 < npx2;
+          ooff[it] = ((yp0 + (uint32_t)p2) * (uint32_t)a.O + (uint32_t)(range0 + kk * 8)) * 2u;
+          res[it] = u32x4_t{0, 0, 0, 0};
+          if (ovalid[it] && a.residual) res[it] = *(const u32x4_t*)(a.residual + ooff[it]);
+        }
         f32x4_t acc[4];
         uint32_t base[4], swz[4];
 #pragma unroll
@@ -299,34 +405,36 @@ __global__ __launch_bounds__(1024) void conv_chain(ChainArgs a) {
           d1 = d2;
           w1 = w2;
         }
-        // the round's results as whole output lines in LDS
+        // the round's results as whole output lines in LDS (two images used in turn, so one
+        // barrier per round is enough)
+        unsigned char* oi = ot + (a.odbl ? (round & 1) * (64 * a.opitch) : 0);
         if (chan >= 0) {
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
             const f32x4_t v = acc[t] + bv;
-            *(u32x2_t*)(ot + (t * 16 + c) * a.opitch + (chan - range0) * 2) =
+            *(u32x2_t*)(oi + (t * 16 + c) * a.opitch + (chan - range0) * 2) =
                 u32x2_t{pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
           }
         }
         __syncthreads();
-        {
-          const int cpp = min(32, (a.O - range0) >> 3);  // 16-byte pieces per pixel in this pass
-          for (int i = tid; i < 64 * 32; i += (int)blockDim.x) {
-            const int pixel = i >> 5, kk = i & 31;
-            const int p2 = round * 64 + pixel;
-            if (kk >= cpp || p2 >= npx2) continue;
-            u32x4_t v = *(const u32x4_t*)(ot + pixel * a.opitch + kk * 16);
-            const uint32_t off = ((yp0 + (uint32_t)p2) * (uint32_t)a.O + (uint32_t)(range0 + kk * 8)) * 2u;
-            const uint16_t* rp = a.residual ? (const uint16_t*)(a.residual + off) : nullptr;
-            const u32x2_t l2 = post_bf16x4(u32x2_t{v.x, v.y}, rp, 4, true, a.relu);
-            const u32x2_t h2 = post_bf16x4(u32x2_t{v.z, v.w}, rp ? rp + 4 : nullptr, 4, true, a.relu);
-            *(u32x4_t*)(a.Y + off) = u32x4_t{l2.x, l2.y, h2.x, h2.y};
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+          if (!ovalid[it]) continue;
+          const int i = tid + it * 1024, pixel = i >> 5, kk = i & 31;
+          const u32x4_t v = *(const u32x4_t*)(oi + pixel * a.opitch + kk * 16);
+          u32x2_t l2 = {v.x, v.y}, h2 = {v.z, v.w};
+          if (a.residual || a.relu) {
+            l2 = post_reg(l2, u32x2_t{res[it].x, res[it].y}, a.residual != nullptr, a.relu);
+            h2 = post_reg(h2, u32x2_t{res[it].z, res[it].w}, a.residual != nullptr, a.relu);
           }
+          *(u32x4_t*)(a.Y + ooff[it]) = u32x4_t{l2.x, l2.y, h2.x, h2.y};
         }
-        __syncthreads();
+        if (!a.odbl) __syncthreads();
       }
+      __syncthreads();  // before the next pass reuses the images
     }
   }
+  CH_MARK(5);
 }
 
 constexpr int kLdsLimit = 160 * 1024;
@@ -364,6 +472,7 @@ bool layer_plan(const bsp_weights* w, const float* bias, int H, LayerPlan* out) 
   out->nstrips = rs[BSP_ROWS_NSTRIPS_W];
   out->nslabs = rs[BSP_ROWS_NSLABS_W];
   out->sc = rs[BSP_ROWS_SLAB_W] / 8;
+  out->wbytes = (int64_t)rs[BSP_ROWS_NCS_W] * H * 1024;
   return true;
 }
 
@@ -385,6 +494,9 @@ int bsp_launch_chain(const bsp_weights* w1, const bsp_weights* w2, const bsp_wei
                      const float* bias1, const float* bias2, const float* bias3, const void* residual, void* Y,
                      int B, int L, int J, int relu, hipStream_t st) {
   ChainArgs a{};
+#ifdef BSP_ROWS_TUNE
+  if (const char* e = std::getenv("BSP_PW_TRACE_PTR")) a.trace = (long long*)std::strtoull(e, nullptr, 16);
+#endif
   if (!layer_plan(w1, bias1, 1, &a.l1) || !layer_plan(w2, bias2, 3, &a.l2) || !layer_plan(w3, bias3, 1, &a.l3))
     return BSP_ERR_UNSUPPORTED;
   if (w1->O != w2->I || w2->O != w2->I || w3->I != w2->O) return BSP_ERR_SHAPE;
@@ -414,20 +526,35 @@ int bsp_launch_chain(const bsp_weights* w1, const bsp_weights* w2, const bsp_wei
   for (;;) {
     const int64_t t1 = (int64_t)(BR + 2) * a.Jp * a.pitchC;
     const int64_t t2 = (int64_t)BR * J * a.pitchC;
-    const int64_t region1 = std::max<int64_t>(t1, 64 * a.opitch);
-    int ct = 0;
-    for (int cand : {3, 2, 1}) {
-      const int64_t region0 = std::max<int64_t>(2ll * cand * 16 * a.pitchX, t2);
-      if (region0 + region1 <= kLdsLimit) {
-        ct = cand;
-        break;
+    // most data in flight first: four chunk buffers and two output images, then less
+    int ct = 0, nbuf = 0, odbl = 0;
+    for (int nb : {4, 2}) {
+      for (int od : {1, 0}) {
+        const int64_t region1 = std::max<int64_t>(t1, (od ? 2 : 1) * 64 * a.opitch);
+        for (int cand : {3, 2, 1}) {
+          const int64_t region0 = (std::max<int64_t>((int64_t)nb * cand * 16 * a.pitchX, t2) + 255) & ~255ll;
+          if (region0 + region1 <= kLdsLimit) {
+            ct = cand;
+            break;
+          }
+        }
+        if (ct) {
+          nbuf = nb;
+          odbl = od;
+          break;
+        }
       }
+      if (ct) break;
     }
     if (ct) {
       a.CT = ct;
+      a.nbuf = nbuf;
+      a.odbl = odbl;
       a.xbuf = ct * 16 * a.pitchX;
-      a.t1_off = (int32_t)((std::max<int64_t>(2ll * a.xbuf, t2) + 255) & ~255ll);
-      const int64_t ldsb = a.t1_off + region1;
+      a.t1_off = (int32_t)((std::max<int64_t>((int64_t)nbuf * a.xbuf, t2) + 255) & ~255ll);
+      a.adv_pix = 4096 / a.pitchX;  // a mover's requests of one chunk are 4 KiB apart
+      a.adv_rem = 4096 % a.pitchX;
+      const int64_t ldsb = a.t1_off + std::max<int64_t>(t1, (odbl ? 2 : 1) * 64 * a.opitch);
       if (ldsb <= kLdsLimit) {
         a.nbands = (L + BR - 1) / BR;
         a.d_J = make_fastdiv((uint32_t)J);
@@ -437,6 +564,13 @@ int bsp_launch_chain(const bsp_weights* w1, const bsp_weights* w2, const bsp_wei
         if ((int64_t)(BR + 2) * J * J >= (1ll << 32) || (int64_t)a.xbuf * a.pitchX >= (1ll << 32) ||
             (int64_t)a.l1.nstrips * a.CT * a.CT >= (1ll << 32) || (int64_t)B * a.nbands >= (1ll << 31))
           return BSP_ERR_UNSUPPORTED;
+        // Every band streams all three layers' weights: worth it only while that stays below
+        // what the intermediates would have cost in memory traffic (their round trips are about
+        // what X and Y cost).  Deep, small-image bottlenecks are faster layer by layer; a
+        // caller's kernel mask (BSP_KERNEL_CHAIN in any of the three) overrides the rule.
+        const bool forced = ((w1->kernels | w2->kernels | w3->kernels) & BSP_KERNEL_CHAIN) != 0;
+        const int64_t wtraffic = (a.l1.wbytes + a.l2.wbytes + a.l3.wbytes) * B * a.nbands;
+        if (!forced && wtraffic > (int64_t)B * L * J * (a.I + a.O) * 2) return BSP_ERR_UNSUPPORTED;
         dim3 grid((unsigned)(B * a.nbands));
         switch (BR) {
           case 7: return launch_chain<7>(a, grid, (size_t)ldsb, st);

@@ -51,7 +51,7 @@ def _run(cs, residual=None, relu=True):
     B, L, J, _ = X.shape
     Y = torch.full((B, L, J, cs[2].O), float("nan"), dtype=torch.bfloat16, device="cuda")
     R = None if residual is None else torch.from_numpy(residual).to(torch.bfloat16).cuda()
-    bsp.bottleneck(layers[0], layers[1], layers[2], X, residual=R, relu=relu, out=Y)
+    bsp.bottleneck(layers[0], layers[1], layers[2], X, residual=R, relu=relu, out=Y, force=True)
     torch.cuda.synchronize()
     return to_host(Y), layers, X, R
 
@@ -146,6 +146,23 @@ def test_chain_resnet50_bottlenecks_full_size(name, shape):
     R = _residual(cs)
     y, *_ = _run(cs, residual=R)
     assert_close(y, _oracle(cs, residual=R), "bf16", name)
+
+
+def test_chain_leaves_deep_small_image_bottlenecks_to_the_caller():
+    """Without the override the library declines a chain whose weights, streamed once per
+    band, outweigh the intermediates it would keep on chip."""
+    import torch
+    cs = _chain(32, 14, 14, 1024, 256, 1024, seed=9600, mask_kind="exact")
+    l = [make_layer(c) for c in cs]
+    X = torch.zeros((32, 14, 14, 1024), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(bsp.BspError) as e:
+        bsp.bottleneck(l[0], l[1], l[2], X)
+    assert e.value.code == -6
+    cs = _chain(4, 56, 56, 256, 64, 256, seed=9601)
+    l = [make_layer(c) for c in cs]
+    X = torch.zeros((4, 56, 56, 256), dtype=torch.bfloat16, device="cuda")
+    bsp.bottleneck(l[0], l[1], l[2], X)          # a layer1-shaped chain is taken
+    torch.cuda.synchronize()
 
 
 def test_chain_declines_other_forms():
