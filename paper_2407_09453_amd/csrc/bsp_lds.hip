@@ -620,8 +620,8 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
   int NT = 0;
   {
     static std::mutex mu;
-    static std::map<std::array<int32_t, 12>, std::pair<int, TileCfg>> memo;
-    const std::array<int32_t, 12> key = {p.M, p.N, p.I, p.O, p.H, p.K, p.sh, p.sw, p.ph, p.pw,
+    static std::map<std::array<int32_t, 13>, std::pair<int, TileCfg>> memo;
+    const std::array<int32_t, 13> key = {p.B, p.M, p.N, p.I, p.O, p.H, p.K, p.sh, p.sw, p.ph, p.pw,
                                          c.maxsteps, dtype};
     std::lock_guard<std::mutex> lock(mu);
     auto it = memo.find(key);
@@ -664,6 +664,11 @@ int launch_lds(const ConvParams& p_in, int dtype, const void* plan_host, int shi
   c.wg_per_group = (int32_t)(ntiles < slots ? ntiles : slots);
   const int64_t nwg = (int64_t)c.wg_per_group * c.groups;
   const int64_t npieces = (int64_t)t.TPH * t.TPW * (t.slab / BSP_CHUNK);
+  // the multiply-high divisions of a tile number (by tiles per image, then by tiles per row;
+  // of a workgroup number by the strip groups) are exact while dividend * divisor < 2^32
+  if (ntiles * std::max<int64_t>((int64_t)t.tiles_y * t.tiles_x, t.tiles_x) >= (1ll << 32) ||
+      nwg * c.groups >= (1ll << 32))
+    return BSP_ERR_UNSUPPORTED;
   if (nwg >= (1 << 24) || ntiles >= (1 << 24) ||
       npieces > max_pieces ||
       (npieces + kXBatchFlat * kLoaderThreads) * t.TPW >= (1ll << 32) || (int64_t)p.L * p.J * p.I >= (1ll << 31))

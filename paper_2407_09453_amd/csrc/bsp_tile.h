@@ -4,17 +4,8 @@
 #define BSP_TILE_H
 
 #include "bsp_device.h"
+#include "bsp_fastdiv.h"
 
-// x / d for small x by one multiply-high: mul = floor(2^32 / d) + 1 (exact while x * d < 2^32).
-struct FastDiv {
-  uint32_t d, mul;
-};
-inline FastDiv make_fastdiv(uint32_t d) {
-  FastDiv f;
-  f.d = d;
-  f.mul = d > 1 ? (uint32_t)((0x100000000ull / d) + 1) : 0u;
-  return f;
-}
 __device__ __forceinline__ uint32_t fdiv(uint32_t x, FastDiv f) {
   return f.d == 1 ? x : __umulhi(x, f.mul);
 }

@@ -112,3 +112,38 @@ def test_no_rows_section_where_it_cannot_serve():
         rp, ci, pl = bsp.bsp_pack(c.W, c.gamma, 8, 8, code)
         plan = bsp.bsp_plan_build(rp, ci, pl, O, 1, 1, I, 8, 8)
         assert plan[24] == 0
+
+
+@pytest.mark.parametrize("bo,bi", GRANS)
+def test_pointwise_layers_keep_one_slab_and_windows_of_64_channels(bo, bi):
+    """A 1x1 layer's section has all input channels in one slab (up to 256 units) and its
+    strips in window order: strip s produces channels of [64 * (s // 4), 64 * (s // 4) + 64)
+    only, so four consecutive strips cover whole 128-byte lines of the output."""
+    O, I = 200, 1024 if bi == 4 else 2048
+    c = draw_layer("t", B=1, L=2, J=2, I=I, O=O, H=1, K=1, bo=bo, bi=bi, dtype="bf16", seed=77,
+                   draw_x=False)
+    rp, ci, pl = bsp.bsp_pack(c.W, c.gamma, bo, bi, bsp.BSP_BF16)
+    plan = bsp.bsp_plan_build(rp, ci, pl, O, 1, 1, I, bo, bi)
+    rs, _ = _rows_section(plan)
+    nstrips, slab, nslabs = (int(v) for v in rs[0:3])
+    assert slab == I and nslabs == 1 and int(rs[14]) == 4
+    assert nstrips == -(-O // 16)
+    rstrip = rs[int(rs[5]):int(rs[5]) + nstrips * 4].reshape(nstrips, 4)
+    for s in range(nstrips):
+        ch = rstrip[s][rstrip[s] >= 0]
+        assert len(ch) and (ch // 64 == s // 4).all(), (s, rstrip[s])
+    Wd, _, _ = _decode_rows(plan, O, 1, 1, I, bo, bi)
+    Wm = oracle.bf16_bits_rne(oracle.apply_mask(c.W, c.gamma, bo, bi)).reshape(c.W.shape)
+    assert (Wd == Wm).all()
+    # wider layers than one descriptor can address get a second slab (served by other kernels)
+    c = draw_layer("t", B=1, L=2, J=2, I=2 * I, O=16, H=1, K=1, bo=bo, bi=bi, dtype="bf16", seed=78,
+                   draw_x=False)
+    rp, ci, pl = bsp.bsp_pack(c.W, c.gamma, bo, bi, bsp.BSP_BF16)
+    rs, _ = _rows_section(bsp.bsp_plan_build(rp, ci, pl, 16, 1, 1, 2 * I, bo, bi))
+    assert int(rs[1]) == I and int(rs[2]) == 2
+    # windows do not apply to layers with a window of taps
+    c = draw_layer("t", B=1, L=4, J=4, I=64, O=128, H=3, K=3, bo=bo, bi=bi, dtype="bf16", seed=79,
+                   draw_x=False)
+    rp, ci, pl = bsp.bsp_pack(c.W, c.gamma, bo, bi, bsp.BSP_BF16)
+    rs, _ = _rows_section(bsp.bsp_plan_build(rp, ci, pl, 128, 3, 3, 64, bo, bi))
+    assert int(rs[14]) == 0
