@@ -160,24 +160,14 @@ def bench_i8(args) -> int:
     stream = torch.cuda.current_stream(dev)
 
     def timed(lay):
-        for i in range(args.warmup):
-            lay.conv2d(Xs[i % nsets], c.stride, c.pad, shift=shift, out=Ys[i % nsets])
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t = time.perf_counter()
-        e0.record(stream)
-        for i in range(args.steps):
-            lay.conv2d(Xs[i % nsets], c.stride, c.pad, shift=shift, out=Ys[i % nsets])
-        e1.record(stream)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t) * 1e3 / args.steps, e0.elapsed_time(e1) / args.steps
+        def launch(i, st):
+            lay.conv2d(Xs[i % nsets], c.stride, c.pad, shift=shift, out=Ys[i % nsets], stream=st)
+        return time_launches(launch, args.steps, args.warmup, dev, use_graph=args.graph)
 
     ms_wall, ms_ev = timed(layer)
     ms_wall_d, _ = timed(dense)
     ops = 2 * c.P * layer.nnzb * c.bo * c.bi * c.H * c.K
     achieved = nbytes / (ms_ev * 1e-3) / 1e9
-    traffic = None if args.general or args.mask != "synthetic" or args.fused \
-        else MEASURED_TRAFFIC.get(args.workload)
     out = {
         "metric": "effective nonzero TOP/s (2*P*nnzb*bo*bi*H*K / t), 50% 8x8 block-sparse int8 conv",
         "value": round(ops / (ms_wall * 1e-3) / 1e12, 4), "unit": "TOP/s", "n_gpus": 1,
@@ -193,7 +183,6 @@ def bench_i8(args) -> int:
         "event_ms_per_step": round(ms_ev, 6),
         "timing": ("K launches captured into one HIP graph, one replay timed between synchronisations"
                    if args.graph else "K launches issued from the Python loop"),
-        "eager_ms_per_step": round(ms_eager, 6),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
                      "algorithmic_bytes": int(nbytes)},
@@ -266,9 +255,7 @@ def bench_spgemm(args) -> int:
                    "nnzb_a": Am.nnzb, "nnzb_b": Bm.nnzb},
         "speedup_vs_dense_mask": round(ms_d / ms, 4), "dense_mask_ms_per_step": round(ms_d, 6),
         "event_ms_per_step": round(ms_ev, 6),
-        "timing": ("K launches captured into one HIP graph, one replay timed between synchronisations"
-                   if args.graph else "K launches issued from the Python loop"),
-        "eager_ms_per_step": round(ms_eager, 6),
+        "timing": "K launches issued from the Python loop",
         "roofline": {"bound": "mfma", "achieved": round(flops / (ms_ev * 1e-3) / 1e12, 3),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(flops / (ms_ev * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5),
@@ -358,6 +345,49 @@ def bench_bottleneck(args) -> int:
     return 0
 
 
+def union_ratio(layer):
+    """Contraction units the strips of a layer run over the units in kept blocks (1.0 = work
+    exactly proportional to the kept blocks), from the plan's row-band section; None without one."""
+    plan = layer.plan
+    off = int(plan[24])
+    if off == 0:
+        return None
+    # kept counts every block row's units, union every strip's: a strip's units are multiplied
+    # with all 16 / bo block rows of the strip
+    kept, union = int(plan[off + 12]), int(plan[off + 13]) * (16 // layer.bo)
+    return round(union / kept, 4) if kept > 0 else None
+
+
+def bench_union(args) -> int:
+    """Issued / kept contraction units of the strips for the three kinds of mask (50 % of 8x8
+    blocks kept) on ResNet50-shaped layers; 16x4 blocks for comparison.  Host only."""
+    import paper_2407_09453_amd as bsp
+    from synthetic import draw_layer
+    shapes = [("3x3 64->64", 64, 64, 3), ("3x3 256->256", 256, 256, 3), ("3x3 512->512", 512, 512, 3),
+              ("1x1 256->1024", 256, 1024, 1), ("1x1 1024->256", 1024, 256, 1), ("1x1 2048->512", 2048, 512, 1)]
+    rows = []
+    for name, I, O, H in shapes:
+        row = {"layer": name}
+        for kind in ("exact", "row_balanced", "select_l2", "16x4"):
+            bo, bi = (16, 4) if kind == "16x4" else (8, 8)
+            c = draw_layer(name, B=1, L=3, J=3, I=I, O=O, H=H, K=H, pad=H // 2, bo=bo, bi=bi, dtype="bf16",
+                           mask_kind="row_balanced" if kind == "row_balanced" else "exact", density=0.5,
+                           seed=4242, draw_x=False)
+            gamma = bsp.bsp_select_mask(c.W, bo, bi, 0, 0.5) if kind == "select_l2" else c.gamma
+            rp, ci, pl = bsp.bsp_pack(c.W, gamma, bo, bi, bsp.BSP_BF16)
+            plan = bsp.bsp_plan_build(rp, ci, pl, O, H, H, I, bo, bi)
+            off = int(plan[24])
+            row[kind] = round(int(plan[off + 13]) * (16 // bo) / max(1, int(plan[off + 12])), 4)
+        rows.append(row)
+        print(row, file=sys.stderr)
+    print(json.dumps({"metric": "issued / kept contraction units of the plan's strips at 50 % density",
+                      "value": rows[1]["exact"], "unit": "ratio", "n_gpus": 1, "steps": 0, "warmup": 0,
+                      "ms_per_step": None, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+                      "dtype": "bf16", "data": "synthetic", "config": {"workload": "plan builder, host only"},
+                      "rows": rows}))
+    return 0
+
+
 def network_rows(args, net: str, peaks, reps: int = 20):
     """Per-layer timing of a whole network-shaped stack: every layer on its own resident
     N(0,1) input (layers are independent: glue such as pooling is not part of the path), the
@@ -393,6 +423,10 @@ def network_rows(args, net: str, peaks, reps: int = 20):
                 lay.conv2d(Xs[i % nb], c.stride, c.pad, out=Ys[i % nb], general=args.general, stream=st)
             ts = [time_launches(launch, reps, 2, dev)[1] * 1e3 for _ in range(5)]
             res[name] = float(np.median(ts))
+
+        def launch_hot(i, st):   # the same buffers every time: X and Y stay in the caches
+            sparse.conv2d(Xs[0], c.stride, c.pad, out=Ys[0], general=args.general, stream=st)
+        res["hot"] = float(np.median([time_launches(launch_hot, reps, 2, dev)[1] * 1e3 for _ in range(3)]))
         fl = flops_nonzero(c, sparse.nnzb)
         fl_d = flops_nonzero(c, int(c.gamma.size))
         by = algorithmic_bytes(c, sparse.nnzb)
@@ -403,6 +437,7 @@ def network_rows(args, net: str, peaks, reps: int = 20):
         rows.append({"layer": c.name, "I": c.I, "O": c.O, "HxK": f"{c.H}x{c.K}", "in": f"{c.L}x{c.J}",
                      "stride": c.stride[0], "nnzb": sparse.nnzb, "blocks": int(c.gamma.size),
                      "us": round(res["sparse"], 2), "us_dense_mask": round(res["dense"], 2),
+                     "us_hot": round(res["hot"], 2), "issued_over_kept": union_ratio(sparse),
                      "speedup": round(res["dense"] / res["sparse"], 3),
                      "speedup_ceiling": round(ceiling, 3),
                      "TFLOPs_nz": round(fl / res["sparse"] / 1e6, 2),
@@ -429,11 +464,12 @@ def bench_network(args, net: str) -> int:
     peaks = measured_peaks(dev)
     rows = network_rows(args, net, peaks, reps=args.steps)
     print(f"{'layer':28s} {'I':>5s} {'O':>5s} {'HxK':>4s} {'in':>8s} {'us':>8s} {'dense':>8s} {'x':>6s} {'ceil':>5s} "
-          f"{'TF/s':>7s} {'GB/s':>7s} {'bound':>5s} {'floor':>6s} {'frac':>6s}", file=sys.stderr)
+          f"{'TF/s':>7s} {'GB/s':>7s} {'bound':>5s} {'floor':>6s} {'frac':>6s} {'hot':>6s} {'i/k':>5s}", file=sys.stderr)
     for r in rows:
         print(f"{r['layer']:28s} {r['I']:5d} {r['O']:5d} {r['HxK']:>4s} {r['in']:>8s} {r['us']:8.1f} "
               f"{r['us_dense_mask']:8.1f} {r['speedup']:6.2f} {r['speedup_ceiling']:5.2f} {r['TFLOPs_nz']:7.1f} "
-              f"{r['GBs']:7.0f} {r['bound']:>5s} {r['floor_us']:6.1f} {r['roofline_frac']:6.3f}", file=sys.stderr)
+              f"{r['GBs']:7.0f} {r['bound']:>5s} {r['floor_us']:6.1f} {r['roofline_frac']:6.3f} {r['us_hot']:6.1f} "
+              f"{r['issued_over_kept'] if r['issued_over_kept'] else 0:5.2f}", file=sys.stderr)
     sm = network_summary(rows)
     out = {
         "metric": "effective nonzero TFLOP/s (2*P*nnzb*bo*bi*H*K / t), 50% 8x8 block-sparse layers",
@@ -499,6 +535,8 @@ def main() -> int:
         if args.steps == 400:
             args.steps, args.warmup = 50, 5
         return bench_spgemm(args)
+    if args.workload == "union":
+        return bench_union(args)
     if args.workload == "bottleneck":
         if args.steps == 400:
             args.steps, args.warmup = 30, 5

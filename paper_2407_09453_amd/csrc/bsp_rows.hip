@@ -531,12 +531,12 @@ constexpr int kLdsLimit = 160 * 1024;
 
 template <int H, int S, int BR, int NT, bool CW4, int D>
 int launch_inst(const RowsArgs& a, dim3 grid, int threads, size_t ldsb, hipStream_t st) {
-  static bool raised = false;  // dynamic LDS above 64 KB has to be allowed once per kernel
-  if (!raised) {
+  static size_t raised = 65536;  // dynamic LDS above 64 KB has to be allowed per kernel
+  if (ldsb > raised) {
     if (hipFuncSetAttribute((const void*)conv_rows<H, S, BR, NT, CW4, D>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsb) != hipSuccess)
       return BSP_ERR_HIP;
-    raised = true;
+    raised = ldsb;
   }
   hipLaunchKernelGGL((conv_rows<H, S, BR, NT, CW4, D>), grid, dim3(threads), ldsb, st, a);
   return hipGetLastError() == hipSuccess ? BSP_OK : BSP_ERR_HIP;
@@ -645,7 +645,12 @@ static bool rows_choose(const ConvParams& p, const int32_t* rs, int S, Choice* b
                 // eight cycles, so a column step costs its MFMAs plus its other instructions;
                 // a second wave on the SIMD hides most of that
                 const double step_mfma = p.H * BR * NT * 8.0, step_other = (20.0 + 10.0 * NT * ((BR - 1) * S + p.H)) * 4.0;
-                const int wg_per_cu = (int)std::max<int64_t>(1, std::min<int64_t>(kLdsLimit / g.ldsb, 10 / (waves + c.NM)));
+                // workgroups a CU holds at once: LDS, and the registers (117 per lane with seven
+                // rows per lane tile: four waves per SIMD; five otherwise), a workgroup's waves
+                // being dealt round over the four SIMDs
+                const int occ = BR == 7 ? 4 : 5;
+                const int wg_per_cu = (int)std::max<int64_t>(
+                    1, std::min<int64_t>(kLdsLimit / g.ldsb, occ / ((waves + c.NM + 3) / 4)));
                 const double conc = std::min<double>(wg_per_cu, std::max(1.0, (double)nwg / cus));
                 const double per_simd = std::max(1.0, waves * conc / 4.0);
                 const double t_step = per_simd >= 2.0 ? std::max(step_mfma * per_simd, (step_mfma + step_other) * per_simd / 2.0)
