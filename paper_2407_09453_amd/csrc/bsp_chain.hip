@@ -72,24 +72,6 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 
 constexpr int kComputeA = 12;  // compute waves of phase A; the other four move data
 
-// Four bf16 results (v) plus four residual values already in registers (r), the activation,
-// one more rounding: post_bf16x4's arithmetic without a trip through memory.
-__device__ __forceinline__ u32x2_t post_reg(u32x2_t v, u32x2_t r, bool has_r, int relu) {
-  float f[4] = {bf16_bits_to_f32((uint16_t)(v.x & 0xFFFF)), bf16_bits_to_f32((uint16_t)(v.x >> 16)),
-                bf16_bits_to_f32((uint16_t)(v.y & 0xFFFF)), bf16_bits_to_f32((uint16_t)(v.y >> 16))};
-  if (has_r) {
-    f[0] += bf16_bits_to_f32((uint16_t)(r.x & 0xFFFF));
-    f[1] += bf16_bits_to_f32((uint16_t)(r.x >> 16));
-    f[2] += bf16_bits_to_f32((uint16_t)(r.y & 0xFFFF));
-    f[3] += bf16_bits_to_f32((uint16_t)(r.y >> 16));
-  }
-  if (relu) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) f[k] = fmaxf(f[k], 0.f);
-  }
-  return u32x2_t{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3])};
-}
-
 template <int BR>
 __global__ __launch_bounds__(1024) void conv_chain(ChainArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
@@ -424,8 +406,8 @@ __global__ __launch_bounds__(1024) void conv_chain(ChainArgs a) {
           const u32x4_t v = *(const u32x4_t*)(oi + pixel * a.opitch + kk * 16);
           u32x2_t l2 = {v.x, v.y}, h2 = {v.z, v.w};
           if (a.residual || a.relu) {
-            l2 = post_reg(l2, u32x2_t{res[it].x, res[it].y}, a.residual != nullptr, a.relu);
-            h2 = post_reg(h2, u32x2_t{res[it].z, res[it].w}, a.residual != nullptr, a.relu);
+            l2 = post_bf16x4_reg(l2, u32x2_t{res[it].x, res[it].y}, a.residual != nullptr, a.relu);
+            h2 = post_bf16x4_reg(h2, u32x2_t{res[it].z, res[it].w}, a.residual != nullptr, a.relu);
           }
           *(u32x4_t*)(a.Y + ooff[it]) = u32x4_t{l2.x, l2.y, h2.x, h2.y};
         }

@@ -264,22 +264,52 @@ __global__ __launch_bounds__(MAXT) void conv_pw(PwArgs a) {
         if (chan >= 0) *(u32x2_t*)(ot + (lpix + t * 16) * a.opitch + (chan - range0) * 2) = v;
       }
     }
-    __syncthreads();
+    // what this thread copies out afterwards, and the residual that goes with it: asked for
+    // now, used after the barrier
     const int cpp = a.NS * 2;  // 16-byte pieces per pixel
     const int total = a.MT * cpp;
-    for (int i = tid; i < total; i += (int)blockDim.x) {
+    constexpr int NIT = PT >= 2 ? PT / 2 : 1;  // pieces per thread: 16 * PT * NS * 2 over 64 * NS * PG threads
+    uint32_t ooff[NIT], lsrc[NIT];
+    bool ovalid[NIT];
+    u32x4_t res[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int i = tid + it * (int)blockDim.x;
+      const int pixel = (int)fdiv((uint32_t)min(i, total - 1), a.d_cpp), k = min(i, total - 1) - pixel * cpp;
+      const int ch = range0 + k * 8, gp = pix0 + pixel;
+      ovalid[it] = i < total && gp < a.P && ch < a.O;
+      ooff[it] = ((uint32_t)gp * (uint32_t)a.O + (uint32_t)ch) * 2u;
+      lsrc[it] = (uint32_t)(pixel * a.opitch + k * 16);
+      res[it] = u32x4_t{0, 0, 0, 0};
+      if (ovalid[it] && a.residual) res[it] = *(const u32x4_t*)(a.residual + ooff[it]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      if (!ovalid[it]) continue;
+      const u32x4_t v = *(const u32x4_t*)(ot + lsrc[it]);
+      u32x2_t l2 = {v.x, v.y}, h2 = {v.z, v.w};
+      if (a.residual || a.relu) {
+        l2 = post_bf16x4_reg(l2, u32x2_t{res[it].x, res[it].y}, a.residual != nullptr, a.relu);
+        h2 = post_bf16x4_reg(h2, u32x2_t{res[it].z, res[it].w}, a.residual != nullptr, a.relu);
+      }
+      *(u32x4_t*)(a.Y + ooff[it]) = u32x4_t{l2.x, l2.y, h2.x, h2.y};
+    }
+    // (a workgroup with several pixel groups has more pieces per thread than NIT covers)
+    for (int i = tid + NIT * (int)blockDim.x; i < total; i += (int)blockDim.x) {
       const int pixel = (int)fdiv((uint32_t)i, a.d_cpp), k = i - pixel * cpp;
       const int ch = range0 + k * 8, gp = pix0 + pixel;
       if (gp >= a.P || ch >= a.O) continue;
-      u32x4_t v = *(const u32x4_t*)(ot + pixel * a.opitch + k * 16);
+      const u32x4_t v = *(const u32x4_t*)(ot + pixel * a.opitch + k * 16);
       const uint32_t off = ((uint32_t)gp * (uint32_t)a.O + (uint32_t)ch) * 2u;
+      u32x2_t l2 = {v.x, v.y}, h2 = {v.z, v.w};
       if (a.residual || a.relu) {
-        const uint16_t* rp = a.residual ? (const uint16_t*)(a.residual + off) : nullptr;
-        const u32x2_t l2 = post_bf16x4(u32x2_t{v.x, v.y}, rp, 4, true, a.relu);
-        const u32x2_t h2 = post_bf16x4(u32x2_t{v.z, v.w}, rp ? rp + 4 : nullptr, 4, true, a.relu);
-        v = u32x4_t{l2.x, l2.y, h2.x, h2.y};
+        u32x4_t r = {0, 0, 0, 0};
+        if (a.residual) r = *(const u32x4_t*)(a.residual + off);
+        l2 = post_bf16x4_reg(l2, u32x2_t{r.x, r.y}, a.residual != nullptr, a.relu);
+        h2 = post_bf16x4_reg(h2, u32x2_t{r.z, r.w}, a.residual != nullptr, a.relu);
       }
-      *(u32x4_t*)(a.Y + off) = v;
+      *(u32x4_t*)(a.Y + off) = u32x4_t{l2.x, l2.y, h2.x, h2.y};
     }
   } else if (PT >= 2 && a.pair) {
 #pragma unroll

@@ -40,6 +40,24 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
+// Four bf16 results (v) plus four residual values already in registers (r), the activation,
+// one more rounding: post_bf16x4's arithmetic without a trip through memory.
+__device__ __forceinline__ u32x2_t post_bf16x4_reg(u32x2_t v, u32x2_t r, bool has_r, int relu) {
+  float f[4] = {bf16_bits_to_f32((uint16_t)(v.x & 0xFFFF)), bf16_bits_to_f32((uint16_t)(v.x >> 16)),
+                bf16_bits_to_f32((uint16_t)(v.y & 0xFFFF)), bf16_bits_to_f32((uint16_t)(v.y >> 16))};
+  if (has_r) {
+    f[0] += bf16_bits_to_f32((uint16_t)(r.x & 0xFFFF));
+    f[1] += bf16_bits_to_f32((uint16_t)(r.x >> 16));
+    f[2] += bf16_bits_to_f32((uint16_t)(r.y & 0xFFFF));
+    f[3] += bf16_bits_to_f32((uint16_t)(r.y >> 16));
+  }
+  if (relu) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) f[k] = fmaxf(f[k], 0.f);
+  }
+  return u32x2_t{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3])};
+}
+
 // The activations one step needs: every pixel tile of the wave reads its 16
 // bytes at the offset the step's descriptor d (chunk, tap) selects.
 template <int NT>
