@@ -162,6 +162,8 @@ enum bsp_kernel_family {
   BSP_KERNEL_TILE = 4,  /* weights streamed through a register ring */
   BSP_KERNEL_FC = 8,    /* weight-streaming kernels for layers with at most 64 output pixels */
   BSP_KERNEL_PW = 16,   /* pointwise layers: all input channels of a pixel tile resident in LDS */
+  BSP_KERNEL_BAND = 64, /* 3x3 stride-1 layers with at most 128 input channels and rows of at most
+                           64 pixels: one workgroup per band of whole image rows */
   BSP_KERNEL_CHAIN = 32 /* bsp_bottleneck only: run the fused chain even where the library
                            expects the three layers one by one to be faster */
 };

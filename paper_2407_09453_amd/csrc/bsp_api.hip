@@ -83,6 +83,8 @@ int dispatch(const bsp_weights* w, const ConvParams& p, void* stream) {
     // than 100 000 pixels.  A caller's kernel mask overrides the rule.
     if ((allow & BSP_KERNEL_PW) && p.H == 1 && p.K == 1) rc = bsp_launch_pw(p, w->dtype, w->plan_host, st);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
+    if ((allow & BSP_KERNEL_BAND) && p.H == 3 && p.K == 3) rc = bsp_launch_band(p, w->dtype, w->plan_host, st);
+    if (rc != BSP_ERR_UNSUPPORTED) return rc;
     const bool rows_pick = p.H > 1 ? p.I >= 128
                                    : (p.I >= 128 && p.I <= 512 && p.O >= 128 && p.P < 100000);
     if ((allow & BSP_KERNEL_ROWS) && (rows_pick || w->kernels)) rc = bsp_launch_rows(p, w->dtype, w->plan_host, st);
@@ -143,6 +145,7 @@ int bsp_conv2d_only(const bsp_weights* w, const void* X, const float* bias, cons
   switch (family) {
     case BSP_KERNEL_ROWS: return bsp_launch_rows(p, w->dtype, w->plan_host, st);
     case BSP_KERNEL_PW: return bsp_launch_pw(p, w->dtype, w->plan_host, st);
+    case BSP_KERNEL_BAND: return bsp_launch_band(p, w->dtype, w->plan_host, st);
     case BSP_KERNEL_LDS: return bsp_launch_lds(p, w->dtype, w->plan_host, st);
     case BSP_KERNEL_TILE: return chunked ? bsp_launch_tile(p, w->dtype, st) : BSP_ERR_UNSUPPORTED;
     case BSP_KERNEL_FC: {

@@ -1,0 +1,323 @@
+// 3x3 layers (stride 1, padding 1, bf16) whose input channels fit one slab of the row-band plan
+// section (at most 128) and whose image rows are at most 64 pixels wide: one workgroup per band
+// of BR output rows, all columns, all output channels.
+//
+// The band's input rows (one halo row above and below) are whole image rows, so they are
+// copied global -> LDS with no gather at all: an LDS image of (BR + 2) rows of Jp pixels (Jp a
+// multiple of 16, which makes the bank permutation slot = piece ^ f(pixel) independent of the
+// row), column 0 and column J + 1 and rows outside the image cleared (they are never copied
+// into: no ordering between clearing and copying is needed).  Wave (strip s, column tile t)
+// owns 16 output columns x BR rows of strip s: per column step it reads the BR + 2 patch rows
+// of the step's (unit, dx) item once and issues 3 * BR MFMAs (output row r, window row dy
+// uses patch row r + dy), weights streamed from the plan through a register ring as in the
+// row-band kernel.  The results of all strips are gathered in LDS as whole output lines (the
+// band's output is one contiguous range of Y) and leave 16 bytes per lane with the optional
+// residual and ReLU.  With 56-pixel rows and 64 channels that is 16 waves per workgroup and,
+// at batch 32, exactly one workgroup per CU.
+#include "bsp_launch.h"
+#include "bsp_tile.h"
+
+#include <algorithm>
+#include <cstdlib>
+
+namespace {
+
+struct BandArgs {
+  const unsigned char* X;
+  unsigned char* Y;
+  const float* bias;
+  const unsigned char* residual;
+  const int32_t* rstrip;
+  const int32_t* rslab;
+  const unsigned char* rdesc;
+  const unsigned char* rfrag;
+  int32_t relu, nstrips;
+  int32_t B, L, J, I, O;
+  int32_t nbands, ctiles;
+  int32_t Jp, pitch, swz_shift, swz_mask;
+  int32_t ppr;      // pixels per KiB request
+  int32_t rpr;      // requests per image row
+  int32_t opitch;   // bytes per pixel of the output image
+  int32_t llpp;     // log2 of the 16-byte slots per staged pixel
+  FastDiv d_rpr, d_ctiles, d_cpp, d_nbands, d_nb;
+#ifdef BSP_ROWS_TUNE
+  long long* trace;
+#endif
+};
+
+#ifdef BSP_ROWS_TUNE
+#define BAND_MARK(k)                                                                                 \
+  do {                                                                                               \
+    if (a.trace && lane == 0) a.trace[((size_t)blockIdx.x * 16 + wave) * 8 + (k)] = wall_clock64(); \
+  } while (0)
+#else
+#define BAND_MARK(k)
+#endif
+
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+template <int BR, int D>
+__global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nwaves = (int)(blockDim.x >> 6);
+  const int n = (int)fdiv(blockIdx.x, a.d_nbands), band = (int)blockIdx.x - n * a.nbands;
+  const int y0 = band * BR;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
+  const int rowbytes = a.Jp * a.pitch;
+
+  BAND_MARK(0);
+  // ---- copies: request rq = (patch row fr, group of ppr pixels)
+  {
+    const int nreq = (BR + 2) * a.rpr;
+    const int lpp = a.pitch >> 4;                 // 16-byte slots per pixel
+    const int sp = lane / lpp, slot = lane - sp * lpp;
+    for (int rq = wave; rq < nreq; rq += nwaves) {
+      const int fr = (int)fdiv((uint32_t)rq, a.d_rpr), grp = rq - fr * a.rpr;
+      const int row = y0 - 1 + fr, col = grp * a.ppr + sp;
+      const uint32_t tp = (uint32_t)(fr * a.Jp + 1 + col);
+      const uint32_t piece = (uint32_t)slot ^ ((tp >> a.swz_shift) & (uint32_t)a.swz_mask);
+      if ((unsigned)row < (unsigned)a.L && col < a.J && piece * 8u < (uint32_t)a.I)
+        __builtin_amdgcn_global_load_lds(
+            (gptr_t)(a.X + (((uint32_t)((n * a.L + row) * a.J + col)) * (uint32_t)a.I + piece * 8u) * 2u),
+            (lptr_t)(uintptr_t)(lds0 + (uint32_t)(fr * a.Jp + 1 + grp * a.ppr) * (uint32_t)a.pitch), 16, 0, 0);
+    }
+  }
+  BAND_MARK(1);
+  // ---- what is never copied into must read as zero: column 0 and columns J + 1 .. Jp - 1 of
+  // every row, whole rows outside the image
+  {
+    const int lpp = a.pitch >> 4, nb = a.Jp - a.J;  // slots per pixel (a power of two), border pixels per row
+    for (int i = tid; i < (BR + 2) * nb * lpp; i += (int)blockDim.x) {
+      const int bp = i >> a.llpp, fr = (int)fdiv((uint32_t)bp, a.d_nb), b = bp - fr * nb;
+      const int col = b == 0 ? 0 : a.J + b;
+      ((u32x4_t*)lds)[((fr * a.Jp + col) << a.llpp) + (i & (lpp - 1))] = u32x4_t{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int fr = 0; fr < BR + 2; ++fr) {
+      if ((unsigned)(y0 - 1 + fr) < (unsigned)a.L) continue;
+      for (int i = tid; i < a.J * lpp; i += (int)blockDim.x)
+        ((u32x4_t*)lds)[((fr * a.Jp + 1) << a.llpp) + i] = u32x4_t{0, 0, 0, 0};
+    }
+  }
+
+  BAND_MARK(2);
+  // ---- this wave's strip and column tile; its step range and channels as scalar loads behind
+  // the copies
+  const int strip = (int)fdiv((uint32_t)wave, a.d_ctiles), ct = wave - strip * a.ctiles;
+  const bool active = strip < a.nstrips;
+  const int sq = active ? strip : 0;
+  u32x2_t lohi;
+  u32x4_t ch4;
+  {
+    const int32_t* ps = a.rslab + sq * 2;
+    const int32_t* pc = a.rstrip + sq * 4;
+    asm volatile("s_load_dwordx2 %0, %2, 0x0\n\ts_load_dwordx4 %1, %3, 0x0\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&s"(lohi), "=&s"(ch4)
+                 : "s"(ps), "s"(pc)
+                 : "memory");
+  }
+  const int lo = (int)lohi.x, hi = active ? (int)lohi.y : lo;
+  const int chan = !active ? -1 : g == 0 ? (int)ch4.x : g == 1 ? (int)ch4.y : g == 2 ? (int)ch4.z : (int)ch4.w;
+
+  const uint32_t frag_lane = (uint32_t)lane * 16u, desc_lane = (uint32_t)g * 4u;
+  u32x4_t wr[D][3];
+  int dr[D];
+  int fnext = lo;
+  auto fetch = [&](int d) {
+    const int cs = min(fnext, hi - 1);  // past the end: the last step again, never used
+    ++fnext;
+    dr[d] = *(const int*)(a.rdesc + ((uint32_t)cs * 16u + desc_lane));
+#pragma unroll
+    for (int dy = 0; dy < 3; ++dy)
+      wr[d][dy] = *(const u32x4_t*)(a.rfrag + (((uint32_t)cs * 3u + dy) * 1024u + frag_lane));
+  };
+  if (hi > lo) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) fetch(d);
+  }
+  f32x4_t bv = {0.f, 0.f, 0.f, 0.f};
+  if (a.bias && chan >= 0) bv = f32x4_t{a.bias[chan], a.bias[chan + 1], a.bias[chan + 2], a.bias[chan + 3]};
+
+  f32x4_t acc[BR];
+#pragma unroll
+  for (int r = 0; r < BR; ++r) acc[r] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  BAND_MARK(3);
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();  // the patch is in LDS
+  BAND_MARK(4);
+
+  const int x = min(ct * 16 + c, a.J - 1);  // lanes past the row's end repeat its last column (never stored)
+  auto step = [&](int d) {
+    uint32_t desc = (uint32_t)dr[d];
+    asm volatile("" : "+v"(desc));  // decoded at its use, so that the wait is for this slot only
+    const uint32_t unit = desc & 0xFFu, tp = (uint32_t)x + ((desc >> 8) & 0xFFu);  // image column x + dx
+    const uint32_t ad = tp * (uint32_t)a.pitch + ((unit ^ ((tp >> a.swz_shift) & (uint32_t)a.swz_mask)) << 4);
+    u32x4_t f[BR + 2];
+#pragma unroll
+    for (int fr = 0; fr < BR + 2; ++fr) f[fr] = *(const u32x4_t*)(lds + ad + fr * rowbytes);
+#pragma unroll
+    for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+      for (int r = 0; r < BR; ++r) acc[r] = mfma_bf16_16x16x32(wr[d][dy], f[r + dy], acc[r]);
+  };
+  if (active) {
+    int cs0 = lo;
+    for (; cs0 + D < hi; cs0 += D) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        step(d);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(d);  // refilled in place, after the MFMAs that read it
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+      if (cs0 + d < hi) step(d);
+  }
+  BAND_MARK(5);
+  __syncthreads();  // everybody is done with the patch: its LDS becomes the output image
+
+  // ---- results as whole output lines in LDS, then out
+  if (chan >= 0 && ct * 16 + c < a.J) {
+#pragma unroll
+    for (int r = 0; r < BR; ++r) {
+      const f32x4_t v = acc[r] + bv;
+      *(u32x2_t*)(lds + (r * a.J + ct * 16 + c) * a.opitch + chan * 2) =
+          u32x2_t{pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
+    }
+  }
+  const int rows_out = min(BR, a.L - y0);
+  const int cpp = a.O >> 3;  // 16-byte pieces per pixel
+  const int total = rows_out * a.J * cpp;
+  const uint32_t y_off0 = (uint32_t)((n * a.L + y0) * a.J) * (uint32_t)a.O * 2u;  // the band's output is contiguous
+  constexpr int NIT = 4;
+  uint32_t lsrc[NIT];
+  u32x4_t res[NIT];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int i = min(tid + it * (int)blockDim.x, max(total - 1, 0));
+    const int pixel = (int)fdiv((uint32_t)i, a.d_cpp), k = i - pixel * cpp;
+    lsrc[it] = (uint32_t)(pixel * a.opitch + k * 16);
+    res[it] = u32x4_t{0, 0, 0, 0};
+    if (tid + it * (int)blockDim.x < total && a.residual) res[it] = *(const u32x4_t*)(a.residual + y_off0 + (uint32_t)i * 16u);
+  }
+  __syncthreads();
+  BAND_MARK(6);
+  auto out_piece = [&](int i, uint32_t src, u32x4_t r) {
+    const u32x4_t v = *(const u32x4_t*)(lds + src);
+    u32x2_t l2 = {v.x, v.y}, h2 = {v.z, v.w};
+    if (a.residual || a.relu) {
+      l2 = post_bf16x4_reg(l2, u32x2_t{r.x, r.y}, a.residual != nullptr, a.relu);
+      h2 = post_bf16x4_reg(h2, u32x2_t{r.z, r.w}, a.residual != nullptr, a.relu);
+    }
+    *(u32x4_t*)(a.Y + y_off0 + (uint32_t)i * 16u) = u32x4_t{l2.x, l2.y, h2.x, h2.y};
+  };
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int i = tid + it * (int)blockDim.x;
+    if (i < total) out_piece(i, lsrc[it], res[it]);
+  }
+  for (int i = tid + NIT * (int)blockDim.x; i < total; i += (int)blockDim.x) {
+    const int pixel = (int)fdiv((uint32_t)i, a.d_cpp), k = i - pixel * cpp;
+    u32x4_t r = {0, 0, 0, 0};
+    if (a.residual) r = *(const u32x4_t*)(a.residual + y_off0 + (uint32_t)i * 16u);
+    out_piece(i, (uint32_t)(pixel * a.opitch + k * 16), r);
+  }
+#ifdef BSP_ROWS_TUNE
+  __builtin_amdgcn_s_waitcnt(0);
+#endif
+  BAND_MARK(7);
+}
+
+constexpr int kLdsLimit = 160 * 1024;
+
+template <int BR>
+int launch_band(const BandArgs& a, dim3 grid, int threads, size_t ldsb, hipStream_t st) {
+  static bool raised = false;  // dynamic LDS above 64 KB has to be allowed once per kernel
+  if (!raised) {
+    if (hipFuncSetAttribute((const void*)conv_band3<BR, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit) !=
+        hipSuccess)
+      return BSP_ERR_HIP;
+    raised = true;
+  }
+  hipLaunchKernelGGL((conv_band3<BR, 2>), grid, dim3(threads), ldsb, st, a);
+  return hipGetLastError() == hipSuccess ? BSP_OK : BSP_ERR_HIP;
+}
+
+}  // namespace
+
+int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st) {
+  if (dtype != BSP_BF16 || !plan_host) return BSP_ERR_UNSUPPORTED;
+  const int32_t* hdr = (const int32_t*)plan_host;
+  if (hdr[BSP_PLAN_MAGIC_W] != BSP_PLAN_MAGIC || hdr[BSP_PLAN_VERSION_W] != BSP_PLAN_VERSION ||
+      hdr[BSP_PLAN_O_W] != p.O || hdr[BSP_PLAN_I_W] != p.I || hdr[BSP_PLAN_H_W] != p.H ||
+      hdr[BSP_PLAN_K_W] != p.K || hdr[BSP_PLAN_DTYPE_W] != dtype || hdr[BSP_PLAN_OFF_ROWS_W] == 0)
+    return BSP_ERR_UNSUPPORTED;
+  const int32_t* rs = hdr + hdr[BSP_PLAN_OFF_ROWS_W];
+  if (p.H != 3 || p.K != 3 || p.sh != 1 || p.sw != 1 || p.ph != 1 || p.pw != 1) return BSP_ERR_UNSUPPORTED;
+  if (rs[BSP_ROWS_NSLABS_W] != 1 || rs[BSP_ROWS_CW_W] != 8 || p.J > 64 || p.I > 128) return BSP_ERR_UNSUPPORTED;
+  if ((int64_t)p.B * p.L * p.J * p.I * 2 >= (1ll << 31) || (int64_t)p.P * p.O * 2 >= (1ll << 31))
+    return BSP_ERR_UNSUPPORTED;
+  const int nstrips = rs[BSP_ROWS_NSTRIPS_W];
+  BandArgs a{};
+#ifdef BSP_ROWS_TUNE
+  if (const char* e = std::getenv("BSP_PW_TRACE_PTR")) a.trace = (long long*)std::strtoull(e, nullptr, 16);
+#endif
+  a.ctiles = (p.J + 15) / 16;
+  if (nstrips * a.ctiles > 16) return BSP_ERR_UNSUPPORTED;  // one wave per (strip, column tile)
+  const int raw = p.I * 2;
+  a.pitch = raw <= 128 ? 128 : 256;
+  if (a.pitch % 256 == 0) {
+    a.swz_shift = 0;
+    a.swz_mask = 15;
+  } else {
+    a.swz_shift = 1;
+    a.swz_mask = 7;
+  }
+  a.Jp = (p.J + 2 + 15) & ~15;
+  a.ppr = 1024 / a.pitch;
+  a.rpr = (p.J + a.ppr - 1) / a.ppr;
+  a.opitch = p.O * 2 + 16;
+  // rows per band: seven unless that leaves CUs without a workgroup
+  const int BR = (int64_t)p.B * ((p.L + 6) / 7) >= 200 ? 7 : 4;
+  a.nbands = (p.L + BR - 1) / BR;
+  const int64_t patch = (int64_t)(BR + 2) * a.Jp * a.pitch;
+  const int64_t outimg = (int64_t)BR * p.J * a.opitch;
+  const int64_t ldsb = std::max(patch, outimg);
+  if (ldsb > kLdsLimit) return BSP_ERR_UNSUPPORTED;
+  const int32_t* sec = p.plan + hdr[BSP_PLAN_OFF_ROWS_W];
+  a.X = (const unsigned char*)p.X;
+  a.Y = (unsigned char*)p.Y;
+  a.bias = p.bias;
+  a.residual = (const unsigned char*)p.residual;
+  a.relu = p.relu;
+  a.rstrip = sec + rs[BSP_ROWS_OFF_STRIP_W];
+  a.rslab = sec + rs[BSP_ROWS_OFF_SLAB_W];
+  a.rdesc = (const unsigned char*)(sec + rs[BSP_ROWS_OFF_DESC_W]);
+  a.rfrag = (const unsigned char*)(sec + rs[BSP_ROWS_OFF_FRAG_W]);
+  a.nstrips = nstrips;
+  a.B = p.B;
+  a.L = p.L;
+  a.J = p.J;
+  a.I = p.I;
+  a.O = p.O;
+  a.d_rpr = make_fastdiv((uint32_t)a.rpr);
+  a.d_ctiles = make_fastdiv((uint32_t)a.ctiles);
+  a.d_cpp = make_fastdiv((uint32_t)(p.O >> 3));
+  a.d_nbands = make_fastdiv((uint32_t)a.nbands);
+  a.d_nb = make_fastdiv((uint32_t)(a.Jp - p.J));
+  a.llpp = a.pitch == 128 ? 3 : 4;
+  // multiply-high divisions are exact while dividend * divisor < 2^32
+  const int64_t nwg = (int64_t)p.B * a.nbands;
+  if (nwg * a.nbands >= (1ll << 32) || nwg >= (1ll << 31) || (int64_t)(BR + 2) * a.rpr * a.rpr >= (1ll << 32) ||
+      (int64_t)(BR * p.J * (p.O >> 3) + 8192) * (p.O >> 3) >= (1ll << 32))
+    return BSP_ERR_UNSUPPORTED;
+  const int threads = 64 * nstrips * a.ctiles;
+  dim3 grid((unsigned)nwg);
+  return BR == 7 ? launch_band<7>(a, grid, threads, (size_t)ldsb, st) : launch_band<4>(a, grid, threads, (size_t)ldsb, st);
+}

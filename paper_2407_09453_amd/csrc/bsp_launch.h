@@ -30,6 +30,10 @@ int bsp_launch_lds_i8(const ConvParams& p, const void* plan_host, int shift, hip
 // section and its host copy).  BSP_ERR_UNSUPPORTED = not applicable, nothing launched.
 int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);
 
+// Band kernel (bf16, 3x3 stride 1 padding 1, at most 128 input channels, rows of at most 64
+// pixels, strips x column tiles <= 16).  BSP_ERR_UNSUPPORTED = not applicable, nothing launched.
+int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);
+
 // Pointwise kernel (bf16, 1x1 windows without padding, any stride, all input channels in one
 // slab of the row-band section).  BSP_ERR_UNSUPPORTED = not applicable, nothing launched.
 int bsp_launch_pw(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);
