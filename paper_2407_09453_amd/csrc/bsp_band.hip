@@ -63,7 +63,12 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nwaves = (int)(blockDim.x >> 6);
-  const int n = (int)fdiv(blockIdx.x, a.d_nbands), band = (int)blockIdx.x - n * a.nbands;
+  // consecutive workgroups go to different XCDs: all bands of an image are given to one XCD, so
+  // that the halo rows two neighbouring bands share are fetched from HBM once
+  const int xcd = blockIdx.x & 7, slot_wg = blockIdx.x >> 3;
+  const int grp8 = (int)fdiv((uint32_t)slot_wg, a.d_nbands), band = slot_wg - grp8 * a.nbands;
+  const int n = xcd + 8 * grp8;
+  if (n >= a.B) return;
   const int y0 = band * BR;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
   const int rowbytes = a.Jp * a.pitch;
@@ -313,7 +318,7 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
   a.d_nb = make_fastdiv((uint32_t)(a.Jp - p.J));
   a.llpp = a.pitch == 128 ? 3 : 4;
   // multiply-high divisions are exact while dividend * divisor < 2^32
-  const int64_t nwg = (int64_t)p.B * a.nbands;
+  const int64_t nwg = (int64_t)((p.B + 7) / 8) * a.nbands * 8;  // eight images at a time, one per XCD
   if (nwg * a.nbands >= (1ll << 32) || nwg >= (1ll << 31) || (int64_t)(BR + 2) * a.rpr * a.rpr >= (1ll << 32) ||
       (int64_t)(BR * p.J * (p.O >> 3) + 8192) * (p.O >> 3) >= (1ll << 32))
     return BSP_ERR_UNSUPPORTED;
