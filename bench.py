@@ -227,23 +227,18 @@ def bench_spgemm(args) -> int:
     stream = torch.cuda.current_stream()
 
     def timed(x, y):
-        for _ in range(args.warmup):
-            x.matmul_nt(y, out=C)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t = time.perf_counter()
-        e0.record(stream)
-        for _ in range(args.steps):
-            x.matmul_nt(y, out=C)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t) * 1e3 / args.steps, e0.elapsed_time(e1) / args.steps
+        def launch(i, st):
+            x.matmul_nt(y, out=C, stream=st)
+        return time_launches(launch, args.steps, args.warmup, torch.device("cuda:0"),
+                             use_graph=args.graph)
 
     ms, ms_ev = timed(Am, Bm)
     ms_d, _ = timed(Ad, Bd)
+    quarter = (rng.random((n, n)) < 0.25).astype(np.uint8), (rng.random((n, n)) < 0.25).astype(np.uint8)
+    ms_q, _ = timed(bsp.BspMatrix(A, quarter[0]), bsp.BspMatrix(B, quarter[1]))
     pairs = int((gamma.astype(np.int64) @ omega.astype(np.int64).T).sum())
     flops = 2 * 512 * pairs                                   # 8x8x8 multiply-adds per block pair
-    nbytes = (Am.nnzb + Bm.nnzb) * 128 + 2 * n * n * 4 + C.numel() * 4
+    nbytes = (Am.nnzb + Bm.nnzb) * (128 + 4) + Am.seg_ptr.nbytes + Bm.seg_ptr.nbytes + C.numel() * 4
     out = {
         "metric": "effective TFLOP/s of the block-sparse x block-sparse product (2*8^3 per matching block pair)",
         "value": round(flops / (ms * 1e-3) / 1e12, 4), "unit": "TFLOP/s", "n_gpus": 1,
@@ -254,8 +249,9 @@ def bench_spgemm(args) -> int:
                                "Bernoulli(0.5) masks, C fp32", "matching_block_pairs": pairs,
                    "nnzb_a": Am.nnzb, "nnzb_b": Bm.nnzb},
         "speedup_vs_dense_mask": round(ms_d / ms, 4), "dense_mask_ms_per_step": round(ms_d, 6),
+        "quarter_density_ms_per_step": round(ms_q, 6),
         "event_ms_per_step": round(ms_ev, 6),
-        "timing": "K launches issued from the Python loop",
+        "timing": "one HIP graph of K launches" if args.graph else "K launches from the Python loop",
         "roofline": {"bound": "mfma", "achieved": round(flops / (ms_ev * 1e-3) / 1e12, 3),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(flops / (ms_ev * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5),

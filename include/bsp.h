@@ -250,9 +250,13 @@ int bsp_bottleneck(const bsp_weights* w1, const bsp_weights* w2, const bsp_weigh
 /* ------------------------------------------- block-sparse x block-sparse product
  * Paper Section III-A: C = (Gamma A) (Omega B)^t with k x k blocks; a block product is done
  * if and only if both blocks are kept (the paper merges the two sorted lists of kept block
- * columns; here the same matches are found from a dense position table per operand).
+ * columns; here two block rows of each operand meet in one matrix-core tile, their column
+ * sets are united per side and intersected across the sides, 64 columns at a time, and only
+ * the surviving columns are multiplied).
  * An operand is what bsp_pack makes of a matrix [rows*8][1][1][cols*8] with 8x8 blocks:
- * row_ptr / col_idx / payload [nnzb][8][8], plus the position table from bsp_bcsr_index.
+ * row_ptr / col_idx / payload [nnzb][8][8], plus row pointers per sixteen block columns from
+ * bsp_bcsr_segments (a second level of row_ptr: it grows with rows * cols / 16, not with the
+ * dense matrix).
  */
 typedef struct {
   int32_t rows, cols;      /* block rows and block columns */
@@ -260,20 +264,23 @@ typedef struct {
   int32_t dtype;           /* BSP_BF16 */
   int64_t nnzb;
   const int32_t* row_ptr;  /* device, rows + 1 */
-  const int32_t* col_idx;  /* device, nnzb */
+  const int32_t* col_idx;  /* device, nnzb, ascending within a block row */
   const void* payload;     /* device, [nnzb][k][k], 16-byte aligned */
-  const int32_t* index;    /* device, [rows][cols]: position of block (r, c) in payload, or -1 */
+  const int32_t* seg_ptr;  /* device, [rows][ceil(cols/16) + 1]: seg_ptr[r][s] = position in
+                              col_idx / payload of row r's first kept block with column >= 16 s */
 } bsp_bcsr;
 
-/* Host: fill index[rows][cols] from row_ptr / col_idx (validated first).
+/* Host: fill seg_ptr[rows][ceil(cols/16) + 1] from row_ptr / col_idx (validated first:
+ * ascending, distinct, in range).  seg_ptr[r][0] = row_ptr[r], the last entry = row_ptr[r+1].
  * Errors: NULL, SHAPE, INDEX. */
-int bsp_bcsr_index(const int32_t* row_ptr, const int32_t* col_idx, int32_t rows, int32_t cols,
-                   int32_t* index);
+int bsp_bcsr_segments(const int32_t* row_ptr, const int32_t* col_idx, int32_t rows, int32_t cols,
+                      int32_t* seg_ptr);
 
 /* Device: C [A.rows*k][B.rows*k] float, row-major, = A . B^t, every element written (zero
  * where no block pair matches); fp32 accumulation of bf16 products.  A.cols must equal
- * B.cols.  Asynchronous on `stream`.  Errors: NULL, SHAPE, DTYPE, UNSUPPORTED (k != 8),
- * ALIGN, HIP. */
+ * B.cols.  seg_ptr and col_idx are trusted to describe the payload (as bsp_bcsr_segments and
+ * bsp_pack wrote them).  Asynchronous on `stream`.  Errors: NULL, SHAPE, DTYPE,
+ * UNSUPPORTED (k != 8), ALIGN, HIP. */
 int bsp_spgemm_nt(const bsp_bcsr* A, const bsp_bcsr* B, float* C, void* stream);
 
 /* ------------------------------------------------------- choosing the mask (host)

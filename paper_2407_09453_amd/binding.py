@@ -29,7 +29,7 @@ EXPORTS = ("bsp_strerror", "bsp_version", "bsp_pack_count", "bsp_pack", "bsp_unp
            "bsp_validate", "bsp_plan_size", "bsp_plan_build", "bsp_fc", "bsp_conv2d",
            "bsp_conv2d_general", "bsp_quantize", "bsp_conv2d_i8", "bsp_fc_i8",
            "bsp_block_importance", "bsp_select_mask", "bsp_mask_step", "bsp_conv2d_fused",
-           "bsp_fc_fused", "bsp_bcsr_index", "bsp_spgemm_nt",
+           "bsp_fc_fused", "bsp_bcsr_segments", "bsp_spgemm_nt",
            "bsp_conv2d_only", "bsp_bottleneck", "bsp_bench_copy", "bsp_bench_mfma_bf16", "bsp_bench_lds_read")
 
 
@@ -53,7 +53,7 @@ class bsp_bcsr(ctypes.Structure):
     _fields_ = [("rows", ctypes.c_int32), ("cols", ctypes.c_int32), ("k", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("nnzb", ctypes.c_int64), ("row_ptr", ctypes.c_void_p),
                 ("col_idx", ctypes.c_void_p), ("payload", ctypes.c_void_p),
-                ("index", ctypes.c_void_p)]
+                ("seg_ptr", ctypes.c_void_p)]
 
 
 def lib_path() -> str:
@@ -104,8 +104,8 @@ def load_library():
         fn.restype = ctypes.c_int
         fn.argtypes = [wp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]
     f64 = ctypes.c_double
-    lib.bsp_bcsr_index.restype = ctypes.c_int
-    lib.bsp_bcsr_index.argtypes = [vp, vp, i32, i32, vp]
+    lib.bsp_bcsr_segments.restype = ctypes.c_int
+    lib.bsp_bcsr_segments.argtypes = [vp, vp, i32, i32, vp]
     lib.bsp_spgemm_nt.restype = ctypes.c_int
     lib.bsp_spgemm_nt.argtypes = [ctypes.POINTER(bsp_bcsr), ctypes.POINTER(bsp_bcsr), vp, vp]
     lib.bsp_conv2d_fused.restype = ctypes.c_int
@@ -474,14 +474,15 @@ class BspLayer:
         return out
 
 
-def bsp_bcsr_index(row_ptr, col_idx, rows: int, cols: int) -> np.ndarray:
-    """[rows][cols] position of every block in the payload, -1 where the block is zeroed."""
+def bsp_bcsr_segments(row_ptr, col_idx, rows: int, cols: int) -> np.ndarray:
+    """[rows][ceil(cols/16) + 1]: where, in a block row's run of kept blocks, every sixteenth
+    block column starts."""
     rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
     ci = np.ascontiguousarray(col_idx, dtype=np.int32)
-    index = np.zeros((rows, cols), dtype=np.int32)
-    _check(load_library().bsp_bcsr_index(_np_ptr(rp), _np_ptr(ci), rows, cols, _np_ptr(index)),
-           "bsp_bcsr_index")
-    return index
+    seg = np.zeros((rows, (cols + 15) // 16 + 1), dtype=np.int32)
+    _check(load_library().bsp_bcsr_segments(_np_ptr(rp), _np_ptr(ci), rows, cols, _np_ptr(seg)),
+           "bsp_bcsr_segments")
+    return seg
 
 
 def bsp_spgemm_nt(A: bsp_bcsr, B: bsp_bcsr, C: int, stream: int = 0) -> None:
@@ -518,7 +519,7 @@ class BspMatrix:
         self.rows, self.cols = R, Cc
         self.row_ptr, self.col_idx, self.payload = bsp_pack(M.reshape(R * 8, 1, 1, Cc * 8), gamma,
                                                             8, 8, BSP_BF16)
-        self.index = bsp_bcsr_index(self.row_ptr, self.col_idx, R, Cc)
+        self.seg_ptr = bsp_bcsr_segments(self.row_ptr, self.col_idx, R, Cc)
         self.nnzb = int(self.col_idx.size)
         dev = torch.device(device)
         pl = self.payload.view(np.int16)
@@ -527,10 +528,10 @@ class BspMatrix:
             self.d_payload[:pl.size].copy_(torch.from_numpy(pl.reshape(-1)))
         self.d_row_ptr = torch.from_numpy(self.row_ptr).to(dev)
         self.d_col_idx = torch.from_numpy(self.col_idx if self.nnzb else np.zeros(1, np.int32)).to(dev)
-        self.d_index = torch.from_numpy(self.index).to(dev)
+        self.d_seg_ptr = torch.from_numpy(self.seg_ptr).to(dev)
         self.struct = bsp_bcsr(R, Cc, 8, BSP_BF16, self.nnzb, self.d_row_ptr.data_ptr(),
                                self.d_col_idx.data_ptr(), self.d_payload.data_ptr(),
-                               self.d_index.data_ptr())
+                               self.d_seg_ptr.data_ptr())
 
     def matmul_nt(self, other: "BspMatrix", out=None, stream=None):
         """C = self . other^t, float32 [self.rows*8][other.rows*8]."""

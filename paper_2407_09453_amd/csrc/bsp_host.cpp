@@ -324,14 +324,20 @@ int bsp_mask_step(const float* W, int32_t O, int32_t H, int32_t K, int32_t I, in
 
 extern "C" {
 
-int bsp_bcsr_index(const int32_t* row_ptr, const int32_t* col_idx, int32_t rows, int32_t cols,
-                   int32_t* index) {
-  if (!row_ptr || !index) return BSP_ERR_NULL;
+int bsp_bcsr_segments(const int32_t* row_ptr, const int32_t* col_idx, int32_t rows, int32_t cols,
+                      int32_t* seg_ptr) {
+  if (!row_ptr || !seg_ptr) return BSP_ERR_NULL;
   if (rows <= 0 || cols <= 0) return BSP_ERR_SHAPE;
   if (int rc = bsp_validate(row_ptr, col_idx, rows * 8, cols * 8, 8, 8)) return rc;
-  for (int64_t i = 0; i < (int64_t)rows * cols; ++i) index[i] = -1;
-  for (int64_t r = 0; r < rows; ++r)
-    for (int64_t n = row_ptr[r]; n < row_ptr[r + 1]; ++n) index[r * cols + col_idx[n]] = (int32_t)n;
+  const int64_t nsub = (cols + 15) / 16;
+  for (int64_t r = 0; r < rows; ++r) {
+    int32_t* sp = seg_ptr + r * (nsub + 1);
+    int64_t n = row_ptr[r];
+    for (int64_t s = 0; s <= nsub; ++s) {  // col_idx is ascending within the row
+      while (n < row_ptr[r + 1] && col_idx[n] < 16 * s) ++n;
+      sp[s] = (int32_t)n;
+    }
+  }
   return BSP_OK;
 }
 

@@ -1,4 +1,4 @@
-"""Block-sparse x block-sparse product: host index table (CPU) and the HIP kernel against
+"""Block-sparse x block-sparse product: host segment pointers (CPU) and the HIP kernel against
 the oracle (GPU)."""
 import numpy as np
 import pytest
@@ -16,24 +16,31 @@ def _draw(Ra, Rb, N, seed, da=0.5, db=0.5):
     return A, gamma, B, omega
 
 
-def test_index_table_host():
-    A, gamma, _, _ = _draw(5, 3, 7, 1)
-    rp, ci, pl = bsp.bsp_pack(A.reshape(40, 1, 1, 56), gamma, 8, 8, bsp.BSP_BF16)
-    idx = bsp.bsp_bcsr_index(rp, ci, 5, 7)
-    assert ((idx >= 0) == (gamma == 1)).all()
-    assert sorted(idx[idx >= 0].tolist()) == list(range(int(gamma.sum())))
+def test_segment_pointers_host():
+    """seg_ptr[r][s] is where row r's kept blocks with column >= 16 s start: checked against a
+    search of the mask itself, on a shape with a ragged last sixteen."""
+    A, gamma, _, _ = _draw(5, 3, 37, 1)
+    rp, ci, pl = bsp.bsp_pack(A.reshape(40, 1, 1, 37 * 8), gamma, 8, 8, bsp.BSP_BF16)
+    seg = bsp.bsp_bcsr_segments(rp, ci, 5, 37)
+    assert seg.shape == (5, 4)
     for r in range(5):
-        for c in range(7):
-            if gamma[r, c]:
-                blk = oracle.bf16_bits_to_f32(pl[idx[r, c]].reshape(8, 8))
+        for s in range(4):
+            assert seg[r, s] == rp[r] + int(gamma[r, :16 * s].sum())
+        assert seg[r, 0] == rp[r] and seg[r, 3] == rp[r + 1]
+        for s in range(3):
+            cols = ci[seg[r, s]:seg[r, s + 1]]
+            assert ((cols >= 16 * s) & (cols < 16 * s + 16)).all()
+            assert cols.tolist() == [c for c in range(16 * s, min(16 * s + 16, 37)) if gamma[r, c]]
+            for n, c in zip(range(seg[r, s], seg[r, s + 1]), cols):
+                blk = oracle.bf16_bits_to_f32(pl[n].reshape(8, 8))
                 assert (blk == A[r * 8:(r + 1) * 8, c * 8:(c + 1) * 8]).all()
     with pytest.raises(bsp.BspError) as e:
-        bsp.bsp_bcsr_index(np.array([0, 2, 1], np.int32), ci, 2, 7)
+        bsp.bsp_bcsr_segments(np.array([0, 2, 1], np.int32), ci, 2, 37)
     assert e.value.code == -4
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("Ra,Rb,N", [(2, 2, 4), (5, 3, 7), (16, 16, 16), (33, 17, 21), (64, 64, 128)])
+@pytest.mark.parametrize("Ra,Rb,N", [(2, 2, 4), (5, 3, 7), (16, 16, 16), (33, 17, 21), (64, 64, 128), (40, 150, 200)])
 def test_spgemm_vs_oracle(Ra, Rb, N):
     import torch
     for da, db in ((0.5, 0.5), (0.1, 0.9), (1.0, 1.0), (0.0, 0.5)):
