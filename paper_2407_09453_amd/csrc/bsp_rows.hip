@@ -195,11 +195,14 @@ __device__ __forceinline__ void rows_stage(const RowsArgs& a, const TilePos& t, 
   }
 }
 
-// The patch rows one column step needs, for one lane tile: f[fr] for the needed fr.
-template <int H, int S, int BR, bool CW4>
-__device__ __forceinline__ void rows_read(const RowsArgs& a, const unsigned char* buf, uint32_t desc, int pixb,
-                                          int rowbytes, uint32_t uoff, u32x4_t (&f)[(BR - 1) * S + H]) {
-  constexpr int NF = (BR - 1) * S + H;
+// Where a lane finds its 16 bytes of a column step's patch row 0 (the other rows lie rowbytes
+// apart); with 4-channel units the 16 bytes are two pieces of 8.
+struct RowsAd {
+  uint32_t a0, a1;
+};
+template <bool CW4>
+__device__ __forceinline__ RowsAd rows_addr(const RowsArgs& a, uint32_t desc, int pixb, uint32_t uoff) {
+  RowsAd r;
   if (CW4) {
     uint32_t ad[2];
 #pragma unroll
@@ -208,21 +211,35 @@ __device__ __forceinline__ void rows_read(const RowsArgs& a, const unsigned char
       const uint32_t unit = (it & 0xFFu) + 2u * uoff, pj = (uint32_t)pixb + (it >> 8);
       ad[h] = (((pj << a.lscp) + ((unit >> 1) ^ ((pj >> a.swz_shift) & a.swz_mask))) << 4) + ((unit & 1u) << 3);
     }
-#pragma unroll
-    for (int fr = 0; fr < NF; ++fr) {
-      if (!row_needed<H, S, BR>(fr)) continue;
-      const u32x2_t p0 = *(const u32x2_t*)(buf + ad[0] + fr * rowbytes);
-      const u32x2_t p1 = *(const u32x2_t*)(buf + ad[1] + fr * rowbytes);
-      f[fr] = u32x4_t{p0.x, p0.y, p1.x, p1.y};
-    }
+    r.a0 = ad[0];
+    r.a1 = ad[1];
   } else {
     const uint32_t unit = (desc & 0xFFu) + uoff, pj = (uint32_t)pixb + ((desc >> 8) & 0xFFu);
-    const uint32_t ad = ((pj << a.lscp) + (unit ^ ((pj >> a.swz_shift) & a.swz_mask))) << 4;
+    r.a0 = ((pj << a.lscp) + (unit ^ ((pj >> a.swz_shift) & a.swz_mask))) << 4;
+    r.a1 = 0;
+  }
+  return r;
+}
+template <bool CW4>
+__device__ __forceinline__ u32x4_t rows_frag(const unsigned char* buf, const RowsAd& ad, int rowoff) {
+  if (CW4) {
+    const u32x2_t p0 = *(const u32x2_t*)(buf + ad.a0 + rowoff);
+    const u32x2_t p1 = *(const u32x2_t*)(buf + ad.a1 + rowoff);
+    return u32x4_t{p0.x, p0.y, p1.x, p1.y};
+  }
+  return *(const u32x4_t*)(buf + ad.a0 + rowoff);
+}
+
+// The patch rows one column step needs, for one lane tile: f[fr] for the needed fr.
+template <int H, int S, int BR, bool CW4>
+__device__ __forceinline__ void rows_read(const RowsArgs& a, const unsigned char* buf, uint32_t desc, int pixb,
+                                          int rowbytes, uint32_t uoff, u32x4_t (&f)[(BR - 1) * S + H]) {
+  constexpr int NF = (BR - 1) * S + H;
+  const RowsAd ad = rows_addr<CW4>(a, desc, pixb, uoff);
 #pragma unroll
-    for (int fr = 0; fr < NF; ++fr) {
-      if (!row_needed<H, S, BR>(fr)) continue;
-      f[fr] = *(const u32x4_t*)(buf + ad + fr * rowbytes);
-    }
+  for (int fr = 0; fr < NF; ++fr) {
+    if (!row_needed<H, S, BR>(fr)) continue;
+    f[fr] = rows_frag<CW4>(buf, ad, fr * rowbytes);
   }
 }
 
@@ -249,7 +266,7 @@ __device__ __forceinline__ void rows_store_direct(const RowsArgs& a, const f32x4
 }
 
 template <int H, int S, int BR, int NT, bool CW4, int D>
-__global__ __launch_bounds__(640) void conv_rows(RowsArgs a) {
+__global__ __launch_bounds__(640) __attribute__((amdgpu_waves_per_eu(H == 3 && NT == 1 && (S == 1 || BR == 4) ? 4 : 3))) void conv_rows(RowsArgs a) {
   constexpr int NF = (BR - 1) * S + H;
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x;
@@ -357,6 +374,7 @@ __global__ __launch_bounds__(640) void conv_rows(RowsArgs a) {
     int pixb[NT];
 #pragma unroll
     for (int j = 0; j < NT; ++j) pixb[j] = colpix[(pt * NT + j) * 16 + c];
+    u32x4_t f[NT][NF];  // the patch rows of the step at hand
 
     for (int ss = 0; ss < a.nstaged; ++ss) {
       for (int k = 0; k < a.G && active; ++k) {
@@ -368,12 +386,20 @@ __global__ __launch_bounds__(640) void conv_rows(RowsArgs a) {
         const int hi = __builtin_amdgcn_readlane(vr, sl + 1);
         lo += (ks - lo) & ksm;  // this wave's first step of the slab
         const int stepd = a.KS * D;
+        // The fragments of a slab's first step are read ahead of its loop; inside, a step's
+        // MFMAs run patch row by patch row (row k feeds output rows k - dy), and as soon as the
+        // ones that read row k have been issued the next step's row k is asked for into the same
+        // registers: the matrix cores work through a step while the next one's fragments arrive.
+        constexpr bool ROLL = H > 1;  // (a one-row window's fragments feed one MFMA each: read per step)
+        if (ROLL && lo < hi) {
+#pragma unroll
+          for (int j = 0; j < NT; ++j) rows_read<H, S, BR, CW4>(a, buf, (uint32_t)dr[0], pixb[j], rowbytes, uoff, f[j]);
+        }
         for (int cs0 = lo; cs0 < hi; cs0 += stepd) {
 #pragma unroll
           for (int d = 0; d < D; ++d) {
             const bool use = cs0 + d * a.KS < hi;
-            if (use) {
-              u32x4_t f[NT][NF];
+            if (use && !ROLL) {
 #pragma unroll
               for (int j = 0; j < NT; ++j) rows_read<H, S, BR, CW4>(a, buf, (uint32_t)dr[d], pixb[j], rowbytes, uoff, f[j]);
 #pragma unroll
@@ -383,6 +409,29 @@ __global__ __launch_bounds__(640) void conv_rows(RowsArgs a) {
 #pragma unroll
                   for (int r = 0; r < BR; ++r)
                     acc[j][r] = mfma_bf16_16x16x32(wr[d][dy], f[j][r * S + dy], acc[j][r]);
+            }
+            if (use && ROLL) {
+              // (the slab's last step asks for its own fragments again: nobody reads them)
+              const bool pre = cs0 + (d + 1) * a.KS < hi;
+              const uint32_t dn = (uint32_t)(pre ? dr[(d + 1) % D] : dr[d]);
+              RowsAd nad[NT];
+#pragma unroll
+              for (int j = 0; j < NT; ++j) nad[j] = rows_addr<CW4>(a, dn, pixb[j], uoff);
+#pragma unroll
+              for (int k = 0; k < NF; ++k) {
+#pragma unroll
+                for (int dy = 0; dy < H; ++dy) {
+                  if (k - dy < 0 || (k - dy) % S != 0 || (k - dy) / S >= BR) continue;
+#pragma unroll
+                  for (int j = 0; j < NT; ++j)
+                    acc[j][(k - dy) / S] = mfma_bf16_16x16x32(wr[d][dy], f[j][k], acc[j][(k - dy) / S]);
+                }
+                if (row_needed<H, S, BR>(k)) {
+#pragma unroll
+                  for (int j = 0; j < NT; ++j) f[j][k] = rows_frag<CW4>(buf, nad[j], k * rowbytes);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+              }
             }
             // refill the slot only now, in place: requested earlier, the new fragments would
             // need registers of their own and be copied over once the MFMAs have read the old
@@ -544,7 +593,7 @@ int launch_inst(const RowsArgs& a, dim3 grid, int threads, size_t ldsb, hipStrea
 
 template <int H, int S, bool CW4>
 int launch_hs(const RowsArgs& a, int BR, int NT, dim3 grid, int threads, size_t ldsb, hipStream_t st) {
-  constexpr int D = H == 1 ? 8 : (H == 3 ? 4 : 2);
+  constexpr int D = H == 1 ? 8 : (H == 3 ? 3 : 2);
   if (BR == 7 && NT == 1) return launch_inst<H, S, 7, 1, CW4, D>(a, grid, threads, ldsb, st);
   if (BR == 4 && NT == 1) return launch_inst<H, S, 4, 1, CW4, D>(a, grid, threads, ldsb, st);
   if (BR == 4 && NT == 2) return launch_inst<H, S, 4, 2, CW4, D>(a, grid, threads, ldsb, st);
@@ -645,10 +694,10 @@ static bool rows_choose(const ConvParams& p, const int32_t* rs, int S, Choice* b
                 // eight cycles, so a column step costs its MFMAs plus its other instructions;
                 // a second wave on the SIMD hides most of that
                 const double step_mfma = p.H * BR * NT * 8.0, step_other = (20.0 + 10.0 * NT * ((BR - 1) * S + p.H)) * 4.0;
-                // workgroups a CU holds at once: LDS, and the registers (117 per lane with seven
-                // rows per lane tile: four waves per SIMD; five otherwise), a workgroup's waves
-                // being dealt round over the four SIMDs
-                const int occ = BR == 7 ? 4 : 5;
+                // workgroups a CU holds at once: LDS, and the registers (between 92 and 168 per
+                // lane: three to five waves per SIMD, as the kernel's instances are compiled), a
+                // workgroup's waves being dealt round over the four SIMDs
+                const int occ = p.H == 1 ? (NT == 1 ? 5 : 4) : (NT == 1 && (S == 1 || BR == 4) ? 4 : 3);
                 const int wg_per_cu = (int)std::max<int64_t>(
                     1, std::min<int64_t>(kLdsLimit / g.ldsb, occ / ((waves + c.NM + 3) / 4)));
                 const double conc = std::min<double>(wg_per_cu, std::max(1.0, (double)nwg / cus));
