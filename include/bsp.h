@@ -177,6 +177,14 @@ enum bsp_kernel_family {
  * Accumulation is fp32; bias is added in fp32; the result is rounded once
  * (nearest-even) to w->dtype.  Asynchronous: returns after the launch.
  * B = 0 is valid and does nothing (X and Y may then be null).
+ * Device memory the library owns: a bf16 layer with 8x8 blocks, 1x1 window and at most 64
+ * output pixels whose activations do not fit the 150 KB of LDS in one piece (I * 32 *
+ * ceil(pixels / 16) bytes; VGG16's fc6 at batch 16) is cut along its input channels into
+ * nseg <= ~32 ranges, and the ranges' partial sums pass through nseg * pixels * O floats of
+ * scratch memory that the library allocates (hipMalloc) the first time such a layer runs,
+ * keeps, and replaces by a larger one when a larger layer comes.  Such a call therefore
+ * cannot be the first of its size under stream capture, and two such calls that overlap in
+ * time on different streams race on that memory.  No other call allocates.
  * Errors: NULL, SHAPE, UNSUPPORTED, DTYPE, ALIGN, HIP. */
 int bsp_fc(const bsp_weights* w, const void* X, const float* bias, void* Y,
            int32_t B, void* stream);

@@ -65,6 +65,27 @@ int prepare(const bsp_weights* w, const void* X, const float* bias, void* Y, int
 
 namespace {
 
+// The library's own scratch memory for the partial sums of FC layers cut along their input
+// channels: allocated on first need, kept, grown when a larger layer comes (one device).
+float* g_fc_scratch = nullptr;
+int64_t g_fc_scratch_bytes = 0;
+
+int launch_fc_xlds(const ConvParams& p, const bsp_weights* w, hipStream_t st) {
+  int64_t need = 0;
+  int rc = bsp_launch_fc_xlds(p, w->dtype, w->bo, w->bi, g_fc_scratch, g_fc_scratch_bytes, &need, st);
+  if (rc != BSP_ERR_CAPACITY) return rc;
+  // (under stream capture this allocation fails: run the layer once before capturing it)
+  if (g_fc_scratch) (void)hipFree(g_fc_scratch);
+  g_fc_scratch = nullptr;
+  g_fc_scratch_bytes = 0;
+  if (hipMalloc((void**)&g_fc_scratch, (size_t)need) != hipSuccess) {
+    (void)hipGetLastError();
+    return BSP_ERR_HIP;
+  }
+  g_fc_scratch_bytes = need;
+  return bsp_launch_fc_xlds(p, w->dtype, w->bo, w->bi, g_fc_scratch, g_fc_scratch_bytes, &need, st);
+}
+
 int dispatch(const bsp_weights* w, const ConvParams& p, void* stream) {
   if (p.P == 0) return BSP_OK;
   const int allow = w->kernels ? w->kernels : ~0;
@@ -73,7 +94,7 @@ int dispatch(const bsp_weights* w, const ConvParams& p, void* stream) {
     const bool chunked = bsp_tile_supported(p, w->dtype);  // whole 8-channel chunks
     hipStream_t st = (hipStream_t)stream;
     int rc = BSP_ERR_UNSUPPORTED;
-    if (chunked && (allow & BSP_KERNEL_FC)) rc = bsp_launch_fc_rows(p, w->dtype, w->bo, w->bi, w->nnzb, st);
+    if (chunked && (allow & BSP_KERNEL_FC)) rc = launch_fc_xlds(p, w, st);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
     if (chunked && (allow & BSP_KERNEL_FC)) rc = bsp_launch_fc_stream(p, w->dtype, w->bo, w->bi, st);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
@@ -150,7 +171,7 @@ int bsp_conv2d_only(const bsp_weights* w, const void* X, const float* bias, cons
     case BSP_KERNEL_TILE: return chunked ? bsp_launch_tile(p, w->dtype, st) : BSP_ERR_UNSUPPORTED;
     case BSP_KERNEL_FC: {
       if (!chunked) return BSP_ERR_UNSUPPORTED;
-      const int rc = bsp_launch_fc_rows(p, w->dtype, w->bo, w->bi, w->nnzb, st);
+      const int rc = launch_fc_xlds(p, w, st);
       return rc != BSP_ERR_UNSUPPORTED ? rc : bsp_launch_fc_stream(p, w->dtype, w->bo, w->bi, st);
     }
     default: return BSP_ERR_UNSUPPORTED;

@@ -16,9 +16,12 @@ int bsp_launch_tile(const ConvParams& p, int dtype, hipStream_t st);
 
 // Weight-streaming kernel for 1x1 layers with at most 64 output pixels (FC layers).
 int bsp_launch_fc_stream(const ConvParams& p, int dtype, int bo, int bi, hipStream_t st);
-// The same layers with 8x8 blocks and at most 60 % of them kept: every compressed block row is
-// streamed linearly.
-int bsp_launch_fc_rows(const ConvParams& p, int dtype, int bo, int bi, int64_t nnzb, hipStream_t st);
+// The same layers with 8x8 blocks, the activations resident in LDS and the compressed block rows
+// streamed past them.  Layers whose activations do not fit LDS in one piece are cut along the
+// input channels and need `scratch` (device, 16-byte aligned) for the partial sums:
+// BSP_ERR_CAPACITY, with nothing launched and the bytes needed in *need, when it is too small.
+int bsp_launch_fc_xlds(const ConvParams& p, int dtype, int bo, int bi, float* scratch, int64_t scratch_bytes,
+                       int64_t* need, hipStream_t st);
 
 // LDS-resident kernel (weights and activations of a slab both in LDS); needs the host copy
 // of the plan to size LDS.  BSP_ERR_UNSUPPORTED = not applicable, nothing launched.
