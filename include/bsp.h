@@ -50,7 +50,7 @@ enum bsp_status {
   BSP_ERR_DTYPE = -5,       /* unknown element type, or a combination not offered */
   BSP_ERR_UNSUPPORTED = -6, /* block granularity outside {8x8, 4x16, 16x4}; bsp_conv2d_only: the
                                layer lies outside the requested kernel family */
-  BSP_ERR_CAPACITY = -7,    /* an output buffer is too small */
+  BSP_ERR_CAPACITY = -7,    /* an output buffer, or the fixed scratch memory of a *_static call, is too small */
   BSP_ERR_HIP = -8,         /* the HIP runtime reported an error at launch */
   BSP_ERR_ALIGN = -9        /* a device pointer is not 16-byte aligned */
 };
@@ -215,6 +215,19 @@ int bsp_conv2d_fused(const bsp_weights* w, const void* X, const float* bias,
                      void* stream);
 int bsp_fc_fused(const bsp_weights* w, const void* X, const float* bias, const void* residual,
                  int32_t relu, void* Y, int32_t B, void* stream);
+
+/* bsp_fc_fused for callers that cannot allocate device memory or let a library do it: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and bit-identical results; the partial sums of a layer cut along its
+ * input channels (see bsp_fc) go to a fixed array of 4 MiB that is part of the library's
+ * image on each GPU (held until the process ends) instead of allocated memory, and nothing
+ * is allocated or freed.  A layer that needs more (nseg * B * O * 4 bytes > 4 MiB) is refused
+ * with BSP_ERR_CAPACITY and nothing launched.  All calls on one GPU share that array and it
+ * keeps the last call's contents (every value a call reads it has written itself, nothing
+ * needs clearing): calls that overlap in time on one GPU race.
+ * Errors: as bsp_fc_fused, plus CAPACITY. */
+int bsp_fc_fused_static(const bsp_weights* w, const void* X, const float* bias,
+                        const void* residual, int32_t relu, void* Y, int32_t B, void* stream);
 
 /* Same layer, but always through the general-shape kernel (no shape-specialised
  * fast path).  For testing and for timing the dispatcher's choice. */

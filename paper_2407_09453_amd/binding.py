@@ -29,7 +29,7 @@ EXPORTS = ("bsp_strerror", "bsp_version", "bsp_pack_count", "bsp_pack", "bsp_unp
            "bsp_validate", "bsp_plan_size", "bsp_plan_build", "bsp_fc", "bsp_conv2d",
            "bsp_conv2d_general", "bsp_quantize", "bsp_conv2d_i8", "bsp_fc_i8",
            "bsp_block_importance", "bsp_select_mask", "bsp_mask_step", "bsp_conv2d_fused",
-           "bsp_fc_fused", "bsp_bcsr_segments", "bsp_spgemm_nt",
+           "bsp_fc_fused", "bsp_fc_fused_static", "bsp_bcsr_segments", "bsp_spgemm_nt",
            "bsp_conv2d_only", "bsp_bottleneck", "bsp_bench_copy", "bsp_bench_mfma_bf16", "bsp_bench_lds_read")
 
 
@@ -117,6 +117,8 @@ def load_library():
     lib.bsp_bottleneck.argtypes = [wp, wp, wp, vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, vp]
     lib.bsp_fc_fused.restype = ctypes.c_int
     lib.bsp_fc_fused.argtypes = [wp, vp, vp, vp, i32, vp, i32, vp]
+    lib.bsp_fc_fused_static.restype = ctypes.c_int
+    lib.bsp_fc_fused_static.argtypes = [wp, vp, vp, vp, i32, vp, i32, vp]
     lib.bsp_block_importance.restype = ctypes.c_int
     lib.bsp_block_importance.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp]
     lib.bsp_select_mask.restype = ctypes.c_int
@@ -314,6 +316,13 @@ def bsp_fc_fused(w: bsp_weights, X: int, bias: Optional[int], residual: Optional
                  relu: bool, Y: int, B: int, stream: int = 0) -> None:
     _check(load_library().bsp_fc_fused(ctypes.byref(w), X, bias, residual, int(relu), Y, B,
                                        stream), "bsp_fc_fused")
+
+
+def bsp_fc_fused_static(w: bsp_weights, X: int, bias: Optional[int], residual: Optional[int],
+                        relu: bool, Y: int, B: int, stream: int = 0) -> None:
+    """bsp_fc_fused without any allocation: partial sums go to the library's fixed array."""
+    _check(load_library().bsp_fc_fused_static(ctypes.byref(w), X, bias, residual, int(relu), Y,
+                                              B, stream), "bsp_fc_fused_static")
 
 
 def bsp_conv2d_only(w: bsp_weights, X: int, bias: Optional[int], residual: Optional[int],

@@ -86,7 +86,13 @@ int launch_fc_xlds(const ConvParams& p, const bsp_weights* w, hipStream_t st) {
   return bsp_launch_fc_xlds(p, w->dtype, w->bo, w->bi, g_fc_scratch, g_fc_scratch_bytes, &need, st);
 }
 
-int dispatch(const bsp_weights* w, const ConvParams& p, void* stream) {
+// Scratch memory handed in by the caller of dispatch instead of the library's own.
+struct FixedScratch {
+  float* ptr;
+  int64_t bytes;
+};
+
+int dispatch(const bsp_weights* w, const ConvParams& p, void* stream, const FixedScratch* fixed = nullptr) {
   if (p.P == 0) return BSP_OK;
   const int allow = w->kernels ? w->kernels : ~0;
   if (w->dtype == BSP_BF16) {
@@ -94,7 +100,11 @@ int dispatch(const bsp_weights* w, const ConvParams& p, void* stream) {
     const bool chunked = bsp_tile_supported(p, w->dtype);  // whole 8-channel chunks
     hipStream_t st = (hipStream_t)stream;
     int rc = BSP_ERR_UNSUPPORTED;
-    if (chunked && (allow & BSP_KERNEL_FC)) rc = launch_fc_xlds(p, w, st);
+    if (chunked && (allow & BSP_KERNEL_FC)) {
+      int64_t need = 0;
+      rc = fixed ? bsp_launch_fc_xlds(p, w->dtype, w->bo, w->bi, fixed->ptr, fixed->bytes, &need, st)
+                 : launch_fc_xlds(p, w, st);
+    }
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
     if (chunked && (allow & BSP_KERNEL_FC)) rc = bsp_launch_fc_stream(p, w->dtype, w->bo, w->bi, st);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
@@ -120,7 +130,49 @@ int dispatch(const bsp_weights* w, const ConvParams& p, void* stream) {
 
 }  // namespace
 
+// The scratch memory of bsp_fc_fused_static: part of the library's image on every GPU it runs
+// on, there until the process ends.  In host code this name only stands for the array (its
+// device address comes from hipGetSymbolAddress, once per device).
+constexpr int64_t kStaticScratchBytes = 4ll << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+// The array's address on the current device.
+int static_scratch(float** out) {
+  static float* ptr[64] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return BSP_ERR_HIP;
+  if (dev < 0 || dev >= 64) return BSP_ERR_UNSUPPORTED;
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return BSP_ERR_HIP;
+    }
+    ptr[dev] = (float*)p;
+  }
+  *out = ptr[dev];
+  return BSP_OK;
+}
+
+}  // namespace
+
 extern "C" {
+
+int bsp_fc_fused_static(const bsp_weights* w, const void* X, const float* bias, const void* residual,
+                        int32_t relu, void* Y, int32_t B, void* stream) {
+  if (!w || (B != 0 && (!X || !Y))) return BSP_ERR_NULL;
+  if (w->H != 1 || w->K != 1) return BSP_ERR_SHAPE;
+  ConvParams p;
+  if (int rc = prepare(w, X, bias, Y, B, 1, 1, 1, 1, 0, 0, &p)) return rc;
+  if (residual && !aligned16(residual)) return BSP_ERR_ALIGN;
+  p.residual = residual;
+  p.relu = relu != 0;
+  FixedScratch fixed{nullptr, kStaticScratchBytes};
+  if (int rc = static_scratch(&fixed.ptr)) return rc;
+  return dispatch(w, p, stream, &fixed);
+}
 
 int bsp_conv2d_general(const bsp_weights* w, const void* X, const float* bias, void* Y,
                        int32_t B, int32_t L, int32_t J, int32_t stride_h, int32_t stride_w,

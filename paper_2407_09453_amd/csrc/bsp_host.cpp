@@ -119,7 +119,7 @@ const char* bsp_strerror(int code) {
     case BSP_ERR_UNSUPPORTED:
       return "unsupported: block granularity not in {8x8, 4x16, 16x4}, or a layer outside the "
              "requested kernel family";
-    case BSP_ERR_CAPACITY: return "output buffer too small";
+    case BSP_ERR_CAPACITY: return "output buffer (or the fixed scratch memory of a *_static call) too small";
     case BSP_ERR_HIP: return "HIP runtime error at launch";
     case BSP_ERR_ALIGN: return "device pointer not 16-byte aligned";
     default: return "unknown status";
