@@ -274,8 +274,8 @@ def bench_spgemm(args) -> int:
 
 
 def bench_bottleneck(args) -> int:
-    """ResNet50-shaped bottlenecks (layer1: 256 -> 64 -> 256 on 56x56, layer3: 1024 -> 256 ->
-    1024 on 14x14; batch 32, 8x8 blocks, half kept): bsp_bottleneck, which keeps the two
+    """ResNet50-shaped bottlenecks (layer1: 256 -> 64 -> 256 on 56x56, layer2: 512 -> 128 -> 512 on
+    28x28, layer3: 1024 -> 256 -> 1024 on 14x14; batch 32, 8x8 blocks, half kept): bsp_bottleneck, which keeps the two
     intermediates in LDS, against the same three layers launched one by one."""
     import torch
     import paper_2407_09453_amd as bsp
@@ -286,6 +286,7 @@ def bench_bottleneck(args) -> int:
     gen.manual_seed(2407)
     out = []
     for name, (B, L, J, I, C, O) in (("layer1", (32, 56, 56, 256, 64, 256)),
+                                     ("layer2", (32, 28, 28, 512, 128, 512)),
                                      ("layer3", (32, 14, 14, 1024, 256, 1024))):
         specs = ((I, C, 1, 0), (C, C, 3, 1), (C, O, 1, 0))
         cs = [draw_layer(f"{name}.{k}", B=1, L=3, J=3, I=i, O=o, H=h, K=h, pad=p, dtype="bf16",

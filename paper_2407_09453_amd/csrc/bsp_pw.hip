@@ -397,13 +397,13 @@ inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 // Tile choice, from per-shape timings of ResNet50-, VGG16- and InceptionV3-shaped pointwise
 // layers (several configurations each): one pixel group; four lane tiles per wave unless the
 // tile's channels then exceed 128 KiB of LDS; few strips per workgroup while pixels are
-// plentiful (many small workgroups hide each other's latencies), many when they are not
+// plentiful or the tile is thin (many small workgroups hide each other's latencies), many when they are not
 // (every strip group re-reads the tile from L2, which is what bounds deep layers); whole-line
 // output for layers that widen (their output is the bulk of the traffic).
 PwChoice pw_choose(int P, int I, int O, int nstrips, int pitch, bool windowed) {
   PwChoice c{4, 1, 1, 0};
   while (c.PT > 1 && 16 * c.PT * pitch > 128 * 1024) c.PT /= 2;
-  int ns = P >= 50000 ? 4 : (I >= 512 ? 16 : 8);
+  int ns = (P >= 50000 || (I <= 128 && P >= 20000)) ? 4 : (I >= 512 ? 16 : 8);
   ns = std::min(ns, nstrips);
   if (ns >= 4) ns &= ~3;
   c.NS = std::max(ns, 1);
