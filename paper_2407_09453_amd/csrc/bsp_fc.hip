@@ -415,18 +415,50 @@ __global__ __launch_bounds__(1024) void fc_xlds_bf16(FcXArgs q) {
   }
 }
 
-// Y[pix][ch] = epilogue(sum over the channel ranges, in order, of part[range][pix][ch] + bias)
+// Y[pix][ch] = epilogue(sum over the channel ranges, in order, of part[range][pix][ch] + bias);
+// a thread takes four consecutive channels when O is a multiple of four, one otherwise.
+template <int V>
 __global__ __launch_bounds__(256) void fc_xlds_sum(FcXArgs q) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (pixel, channel)
-  if (i >= (int64_t)q.P * q.O) return;
+  const int64_t n = (int64_t)q.P * q.O;
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * V;  // (pixel, channel)
+  if (i >= n) return;
   const int ch = (int)(i % q.O);
-  float v = 0.f;
-  for (int s = 0; s < q.nseg; ++s) v += q.part[(int64_t)s * q.P * q.O + i];
-  if (q.bias) v += q.bias[ch];
-  float f = bf16_bits_to_f32(f32_to_bf16_rne(v));
-  if (q.residual) f += bf16_bits_to_f32(q.residual[i]);
-  if (q.relu) f = fmaxf(f, 0.f);
-  q.Y[i] = f32_to_bf16_rne(f);
+  float v[V];
+#pragma unroll
+  for (int k = 0; k < V; ++k) v[k] = 0.f;
+  for (int s0 = 0; s0 < q.nseg; s0 += 8) {  // eight ranges' loads in flight together
+    float t[8][V];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s = min(s0 + u, q.nseg - 1);
+      if (V == 4) {
+        const f32x4_t w = *(const f32x4_t*)(q.part + (int64_t)s * n + i);
+#pragma unroll
+        for (int k = 0; k < V; ++k) t[u][k] = w[k];
+      } else {
+        t[u][0] = q.part[(int64_t)s * n + i];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (s0 + u < q.nseg) {
+#pragma unroll
+        for (int k = 0; k < V; ++k) v[k] += t[u][k];
+      }
+  }
+  uint16_t o[V];
+#pragma unroll
+  for (int k = 0; k < V; ++k) {
+    float f = bf16_bits_to_f32(f32_to_bf16_rne(v[k] + (q.bias ? q.bias[ch + k] : 0.f)));
+    if (q.residual) f += bf16_bits_to_f32(q.residual[i + k]);
+    if (q.relu) f = fmaxf(f, 0.f);
+    o[k] = f32_to_bf16_rne(f);
+  }
+  if (V == 4) {
+    *(u32x2_t*)(q.Y + i) = u32x2_t{(uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16)};
+  } else {
+    q.Y[i] = o[0];
+  }
 }
 
 constexpr int kFcxLds = 150 * 1024;
@@ -514,7 +546,10 @@ int bsp_launch_fc_xlds(const ConvParams& p, int dtype, int bo, int bi, float* sc
   if (hipGetLastError() != hipSuccess) return BSP_ERR_HIP;
   if (q.nseg > 1) {
     const int64_t n = (int64_t)p.P * p.O;
-    hipLaunchKernelGGL(fc_xlds_sum, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, q);
+    if (p.O % 4 == 0)
+      hipLaunchKernelGGL(fc_xlds_sum<4>, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, st, q);
+    else
+      hipLaunchKernelGGL(fc_xlds_sum<1>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, q);
     if (hipGetLastError() != hipSuccess) return BSP_ERR_HIP;
   }
   return BSP_OK;
