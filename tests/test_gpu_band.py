@@ -74,6 +74,47 @@ def test_band_kernel_fused_epilogue():
         assert_close(y, ref, "bf16", f"fused res={res is not None} relu={relu}")
 
 
+# Enough images for bands of seven rows (the small shapes above get four-row bands):
+# (B, L, J, I, O)
+SEVEN_ROW_SHAPES = [
+    (34, 41, 50, 24, 40),      # last band six rows; four column tiles, the last one ragged; three strips
+    (29, 50, 28, 128, 128),    # 256-byte pixels; eight strips, one pair of column tiles; last band one row
+    (67, 17, 13, 72, 48),      # last band three rows; one column tile
+    (50, 25, 20, 64, 64),      # last band four rows
+    (40, 33, 64, 16, 16),      # the widest rows; last band five rows
+]
+
+
+@pytest.mark.parametrize("bo,bi", [(8, 8), (4, 16)])
+def test_band_kernel_seven_row_shapes(bo, bi):
+    for n, (B, L, J, I, O) in enumerate(SEVEN_ROW_SHAPES):
+        if bi == 16 and I % 16:
+            continue
+        c = draw_layer("bandp", B=B, L=L, J=J, I=I, O=O, H=3, K=3, stride=1, pad=1, bo=bo, bi=bi,
+                       dtype="bf16", mask_kind="bernoulli", density=0.5, seed=8970 + n, b_std=0.5)
+        print("seven-row band case", n, (B, L, J, I, O, bo, bi), flush=True)
+        assert_close(_run_band(c), oracle_conv(c), "bf16", f"seven-row band shape {n} {bo}x{bi}")
+
+
+@pytest.mark.parametrize("kind,density", [("zeros", 0.0), ("ones", 1.0), ("exact", 0.1)])
+def test_band_kernel_seven_row_mask_extremes_and_epilogue(kind, density):
+    import torch
+    c = draw_layer("bandp", B=50, L=25, J=20, I=64, O=64, H=3, K=3, stride=1, pad=1,
+                   dtype="bf16", mask_kind=kind, density=density, seed=8990, b_std=0.5)
+    y = _run_band(c)
+    if kind == "zeros":
+        want = oracle.round_to_storage(c.bias.astype(np.float64), "bf16").astype(np.float64)
+        assert (y == want).all(), "an all-zero mask gives cast(bias) exactly"
+    assert_close(y, oracle_conv(c), "bf16", kind)
+    rng = np.random.default_rng(2)
+    R = oracle.round_to_storage(rng.standard_normal((c.B, c.M, c.N, c.O)), "bf16")
+    Rd = torch.from_numpy(R).to(torch.bfloat16).cuda()
+    # the fused epilogue is the unfused result plus residual, ReLU, one more rounding: exactly
+    yf = _run_band(c, residual=Rd, relu=True)
+    want = oracle.round_to_storage(np.maximum(y.astype(np.float32) + R.astype(np.float32), np.float32(0)), "bf16")
+    assert (yf == want).all(), f"seven-row fused {kind}"
+
+
 def test_band_kernel_config1_full_size():
     from synthetic import config_cases
     c = next(config_cases(1))
