@@ -220,7 +220,8 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
       l2 = post_bf16x4_reg(l2, u32x2_t{r.x, r.y}, a.residual != nullptr, a.relu);
       h2 = post_bf16x4_reg(h2, u32x2_t{r.z, r.w}, a.residual != nullptr, a.relu);
     }
-    *(u32x4_t*)(a.Y + y_off0 + (uint32_t)i * 16u) = u32x4_t{l2.x, l2.y, h2.x, h2.y};
+    // (streaming store: no burst of dirty L2 lines is left for the end of the kernel)
+    __builtin_nontemporal_store(u32x4_t{l2.x, l2.y, h2.x, h2.y}, (u32x4_t*)(a.Y + y_off0 + (uint32_t)i * 16u));
   };
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {

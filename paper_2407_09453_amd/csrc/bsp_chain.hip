@@ -409,7 +409,7 @@ __global__ __launch_bounds__(1024) void conv_chain(ChainArgs a) {
             l2 = post_bf16x4_reg(l2, u32x2_t{res[it].x, res[it].y}, a.residual != nullptr, a.relu);
             h2 = post_bf16x4_reg(h2, u32x2_t{res[it].z, res[it].w}, a.residual != nullptr, a.relu);
           }
-          *(u32x4_t*)(a.Y + ooff[it]) = u32x4_t{l2.x, l2.y, h2.x, h2.y};
+          __builtin_nontemporal_store(u32x4_t{l2.x, l2.y, h2.x, h2.y}, (u32x4_t*)(a.Y + ooff[it]));
         }
         if (!a.odbl) __syncthreads();
       }

@@ -293,7 +293,9 @@ __global__ __launch_bounds__(MAXT) void conv_pw(PwArgs a) {
         l2 = post_bf16x4_reg(l2, u32x2_t{res[it].x, res[it].y}, a.residual != nullptr, a.relu);
         h2 = post_bf16x4_reg(h2, u32x2_t{res[it].z, res[it].w}, a.residual != nullptr, a.relu);
       }
-      *(u32x4_t*)(a.Y + ooff[it]) = u32x4_t{l2.x, l2.y, h2.x, h2.y};
+      // (whole output lines leave as streaming stores: no burst of dirty L2 lines is left for the
+      // end of the kernel; pieces scattered over a line, below, are better merged in L2)
+      __builtin_nontemporal_store(u32x4_t{l2.x, l2.y, h2.x, h2.y}, (u32x4_t*)(a.Y + ooff[it]));
     }
     // (a workgroup with several pixel groups has more pieces per thread than NIT covers)
     for (int i = tid + NIT * (int)blockDim.x; i < total; i += (int)blockDim.x) {
@@ -309,7 +311,7 @@ __global__ __launch_bounds__(MAXT) void conv_pw(PwArgs a) {
         l2 = post_bf16x4_reg(l2, u32x2_t{r.x, r.y}, a.residual != nullptr, a.relu);
         h2 = post_bf16x4_reg(h2, u32x2_t{r.z, r.w}, a.residual != nullptr, a.relu);
       }
-      *(u32x4_t*)(a.Y + off) = u32x4_t{l2.x, l2.y, h2.x, h2.y};
+      __builtin_nontemporal_store(u32x4_t{l2.x, l2.y, h2.x, h2.y}, (u32x4_t*)(a.Y + off));
     }
   } else if (PT >= 2 && a.pair) {
 #pragma unroll
