@@ -1,12 +1,13 @@
 // 3x3 layers (stride 1, padding 1, bf16) whose input channels fit one slab of the row-band plan
-// section (at most 128) and whose image rows are at most 64 pixels wide: one workgroup per band
-// of BR output rows, all columns, all output channels.
+// section (at most 128): one workgroup per band of BR output rows x chunk of CW columns (all
+// columns when the rows are at most 64 pixels wide), all output channels.
 //
-// The band's input rows (one halo row above and below) are whole image rows, so they are
-// copied global -> LDS with no gather at all: an LDS image of (BR + 2) rows of Jp pixels (Jp a
-// multiple of 16, which makes the bank permutation slot = piece ^ f(pixel) independent of the
-// row), column 0 and column J + 1 and rows outside the image cleared (they are never copied
-// into: no ordering between clearing and copying is needed).  Wave (strip s, column tile t)
+// The band's input rows (one halo row above and below, one halo column left and right of the
+// chunk) are runs of whole pixels of image rows, so they are copied global -> LDS with no
+// gather at all: an LDS image of (BR + 2) rows of Jp pixels (Jp a multiple of 16, which makes
+// the bank permutation slot = piece ^ f(pixel) independent of the row); the halo columns
+// that lie outside the image and the rows outside the image are cleared (they are never
+// copied into: no ordering between clearing and copying is needed).  Wave (strip s, column tile t)
 // owns 16 output columns x BR rows of strip s: per column step it reads the BR + 2 patch rows
 // of the step's (unit, dx) item once and issues 3 * BR MFMAs (output row r, window row dy
 // uses patch row r + dy), weights streamed from the plan through a register ring as in the
@@ -34,12 +35,13 @@ struct BandArgs {
   int32_t relu, nstrips;
   int32_t B, L, J, I, O;
   int32_t nbands, ctiles;
+  int32_t cw, nchunks;  // columns per chunk (a multiple of 16 when there are several chunks), chunks per row
   int32_t Jp, pitch, swz_shift, swz_mask;
   int32_t ppr;      // pixels per KiB request
   int32_t rpr;      // requests per image row
   int32_t opitch;   // bytes per pixel of the output image
   int32_t llpp;     // log2 of the 16-byte slots per staged pixel
-  FastDiv d_rpr, d_ctiles, d_cpp, d_nbands, d_nb;
+  FastDiv d_rpr, d_ctiles, d_cpp, d_nbands, d_nchunks, d_rowp;
 #ifdef BSP_ROWS_TUNE
   long long* trace;
 #endif
@@ -66,10 +68,12 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
   // consecutive workgroups go to different XCDs: all bands of an image are given to one XCD, so
   // that the halo rows two neighbouring bands share are fetched from HBM once
   const int xcd = blockIdx.x & 7, slot_wg = blockIdx.x >> 3;
-  const int grp8 = (int)fdiv((uint32_t)slot_wg, a.d_nbands), band = slot_wg - grp8 * a.nbands;
+  const int grp8 = (int)fdiv((uint32_t)slot_wg, a.d_nbands), bc = slot_wg - grp8 * a.nbands;  // nbands counts (band, chunk) pairs
   const int n = xcd + 8 * grp8;
   if (n >= a.B) return;
-  const int y0 = band * BR;
+  const int band = (int)fdiv((uint32_t)bc, a.d_nchunks), chunk = bc - band * a.nchunks;
+  const int y0 = band * BR, x0 = chunk * a.cw;
+  const int Jc = min(a.cw, a.J - x0);  // this chunk's columns: patch column pc holds image column x0 - 1 + pc
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
   const int rowbytes = a.Jp * a.pitch;
 
@@ -79,32 +83,35 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
     const int nreq = (BR + 2) * a.rpr;
     const int lpp = a.pitch >> 4;                 // 16-byte slots per pixel
     const int sp = lane / lpp, slot = lane - sp * lpp;
+    const int pc0 = x0 == 0 ? 1 : 0;  // (the first chunk's left halo column lies outside the image)
     for (int rq = wave; rq < nreq; rq += nwaves) {
       const int fr = (int)fdiv((uint32_t)rq, a.d_rpr), grp = rq - fr * a.rpr;
-      const int row = y0 - 1 + fr, col = grp * a.ppr + sp;
-      const uint32_t tp = (uint32_t)(fr * a.Jp + 1 + col);
+      const int row = y0 - 1 + fr, pc = pc0 + grp * a.ppr + sp, col = x0 - 1 + pc;
+      const uint32_t tp = (uint32_t)(fr * a.Jp + pc);
       const uint32_t piece = (uint32_t)slot ^ ((tp >> a.swz_shift) & (uint32_t)a.swz_mask);
-      if ((unsigned)row < (unsigned)a.L && col < a.J && piece * 8u < (uint32_t)a.I)
+      if ((unsigned)row < (unsigned)a.L && pc < Jc + 2 && (unsigned)col < (unsigned)a.J && piece * 8u < (uint32_t)a.I)
         __builtin_amdgcn_global_load_lds(
             (gptr_t)(a.X + (((uint32_t)((n * a.L + row) * a.J + col)) * (uint32_t)a.I + piece * 8u) * 2u),
-            (lptr_t)(uintptr_t)(lds0 + (uint32_t)(fr * a.Jp + 1 + grp * a.ppr) * (uint32_t)a.pitch), 16, 0, 0);
+            (lptr_t)(uintptr_t)(lds0 + (uint32_t)(fr * a.Jp + pc0 + grp * a.ppr) * (uint32_t)a.pitch), 16, 0, 0);
     }
   }
   BAND_MARK(1);
-  // ---- what is never copied into must read as zero: column 0 and columns J + 1 .. Jp - 1 of
-  // every row, whole rows outside the image
+  // ---- what is never copied into must read as zero: the halo columns where they lie outside
+  // the image (patch column 0 of the first chunk, Jc + 1 of the last), whole rows outside it
   {
-    const int lpp = a.pitch >> 4, nb = a.Jp - a.J;  // slots per pixel (a power of two), border pixels per row
-    for (int i = tid; i < (BR + 2) * nb * lpp; i += (int)blockDim.x) {
-      const int bp = i >> a.llpp, fr = (int)fdiv((uint32_t)bp, a.d_nb), b = bp - fr * nb;
-      const int col = b == 0 ? 0 : a.J + b;
-      ((u32x4_t*)lds)[((fr * a.Jp + col) << a.llpp) + (i & (lpp - 1))] = u32x4_t{0, 0, 0, 0};
+    const int lpp = a.pitch >> 4;  // slots per pixel (a power of two)
+    const bool left = x0 == 0, right = x0 + Jc == a.J;
+    for (int i = tid; i < (BR + 2) * 2 * lpp; i += (int)blockDim.x) {
+      const int bp = i >> a.llpp, fr = bp >> 1, side = bp & 1;
+      if (side == 0 ? !left : !right) continue;
+      const int pc = side == 0 ? 0 : Jc + 1;
+      ((u32x4_t*)lds)[((fr * a.Jp + pc) << a.llpp) + (i & (lpp - 1))] = u32x4_t{0, 0, 0, 0};
     }
 #pragma unroll
     for (int fr = 0; fr < BR + 2; ++fr) {
       if ((unsigned)(y0 - 1 + fr) < (unsigned)a.L) continue;
-      for (int i = tid; i < a.J * lpp; i += (int)blockDim.x)
-        ((u32x4_t*)lds)[((fr * a.Jp + 1) << a.llpp) + i] = u32x4_t{0, 0, 0, 0};
+      for (int i = tid; i < (Jc + 2) * lpp; i += (int)blockDim.x)
+        ((u32x4_t*)lds)[((fr * a.Jp) << a.llpp) + i] = u32x4_t{0, 0, 0, 0};
     }
   }
 
@@ -155,7 +162,7 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
   __syncthreads();  // the patch is in LDS
   BAND_MARK(4);
 
-  const int x = min(ct * 16 + c, a.J - 1);  // lanes past the row's end repeat its last column (never stored)
+  const int x = min(ct * 16 + c, Jc - 1);  // (column of the chunk) lanes past its end repeat its last column (never stored)
   auto step = [&](int d) {
     uint32_t desc = (uint32_t)dr[d];
     asm volatile("" : "+v"(desc));  // decoded at its use, so that the wait is for this slot only
@@ -188,32 +195,47 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
   __syncthreads();  // everybody is done with the patch: its LDS becomes the output image
 
   // ---- results as whole output lines in LDS, then out
-  if (chan >= 0 && ct * 16 + c < a.J) {
+  if (chan >= 0 && ct * 16 + c < Jc) {
 #pragma unroll
     for (int r = 0; r < BR; ++r) {
       const f32x4_t v = acc[r] + bv;
-      *(u32x2_t*)(lds + (r * a.J + ct * 16 + c) * a.opitch + chan * 2) =
+      *(u32x2_t*)(lds + (r * a.cw + ct * 16 + c) * a.opitch + chan * 2) =
           u32x2_t{pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
     }
   }
   const int rows_out = min(BR, a.L - y0);
   const int cpp = a.O >> 3;  // 16-byte pieces per pixel
-  const int total = rows_out * a.J * cpp;
-  const uint32_t y_off0 = (uint32_t)((n * a.L + y0) * a.J) * (uint32_t)a.O * 2u;  // the band's output is contiguous
+  const int rowp = a.cw * cpp;  // pieces per row of the output image
+  const int total = rows_out * rowp;
+  // piece i of the image: row r, column xl of the chunk, piece k of the pixel; a row of the chunk
+  // is one contiguous run of Y
+  const uint32_t y_off0 = (uint32_t)((n * a.L + y0) * a.J + x0) * (uint32_t)a.O * 2u;
+  const uint32_t y_row = (uint32_t)a.J * (uint32_t)a.O * 2u;
+  auto locate = [&](int i, uint32_t& src, uint32_t& dst) {
+    const int pixel = (int)fdiv((uint32_t)i, a.d_cpp), k = i - pixel * cpp;
+    src = (uint32_t)(pixel * a.opitch + k * 16);
+    if (a.nchunks == 1) {  // whole rows: the band's output is one contiguous range
+      dst = y_off0 + (uint32_t)i * 16u;
+      return i < total;
+    }
+    const int r = (int)fdiv((uint32_t)i, a.d_rowp), rem = i - r * rowp;
+    dst = y_off0 + (uint32_t)r * y_row + (uint32_t)rem * 16u;
+    return i < total && pixel - r * a.cw < Jc;
+  };
   constexpr int NIT = 4;
-  uint32_t lsrc[NIT];
+  uint32_t lsrc[NIT], ydst[NIT];
+  bool ok[NIT];
   u32x4_t res[NIT];
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
-    const int i = min(tid + it * (int)blockDim.x, max(total - 1, 0));
-    const int pixel = (int)fdiv((uint32_t)i, a.d_cpp), k = i - pixel * cpp;
-    lsrc[it] = (uint32_t)(pixel * a.opitch + k * 16);
+    ok[it] = locate(min(tid + it * (int)blockDim.x, max(total - 1, 0)), lsrc[it], ydst[it]) &&
+             tid + it * (int)blockDim.x < total;
     res[it] = u32x4_t{0, 0, 0, 0};
-    if (tid + it * (int)blockDim.x < total && a.residual) res[it] = *(const u32x4_t*)(a.residual + y_off0 + (uint32_t)i * 16u);
+    if (ok[it] && a.residual) res[it] = *(const u32x4_t*)(a.residual + ydst[it]);
   }
   __syncthreads();
   BAND_MARK(6);
-  auto out_piece = [&](int i, uint32_t src, u32x4_t r) {
+  auto out_piece = [&](uint32_t src, uint32_t dst, u32x4_t r) {
     const u32x4_t v = *(const u32x4_t*)(lds + src);
     u32x2_t l2 = {v.x, v.y}, h2 = {v.z, v.w};
     if (a.residual || a.relu) {
@@ -221,18 +243,17 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
       h2 = post_bf16x4_reg(h2, u32x2_t{r.z, r.w}, a.residual != nullptr, a.relu);
     }
     // (streaming store: no burst of dirty L2 lines is left for the end of the kernel)
-    __builtin_nontemporal_store(u32x4_t{l2.x, l2.y, h2.x, h2.y}, (u32x4_t*)(a.Y + y_off0 + (uint32_t)i * 16u));
+    __builtin_nontemporal_store(u32x4_t{l2.x, l2.y, h2.x, h2.y}, (u32x4_t*)(a.Y + dst));
   };
 #pragma unroll
-  for (int it = 0; it < NIT; ++it) {
-    const int i = tid + it * (int)blockDim.x;
-    if (i < total) out_piece(i, lsrc[it], res[it]);
-  }
+  for (int it = 0; it < NIT; ++it)
+    if (ok[it]) out_piece(lsrc[it], ydst[it], res[it]);
   for (int i = tid + NIT * (int)blockDim.x; i < total; i += (int)blockDim.x) {
-    const int pixel = (int)fdiv((uint32_t)i, a.d_cpp), k = i - pixel * cpp;
+    uint32_t src, dst;
+    if (!locate(i, src, dst)) continue;
     u32x4_t r = {0, 0, 0, 0};
-    if (a.residual) r = *(const u32x4_t*)(a.residual + y_off0 + (uint32_t)i * 16u);
-    out_piece(i, (uint32_t)(pixel * a.opitch + k * 16), r);
+    if (a.residual) r = *(const u32x4_t*)(a.residual + dst);
+    out_piece(src, dst, r);
   }
 #ifdef BSP_ROWS_TUNE
   __builtin_amdgcn_s_waitcnt(0);
@@ -266,7 +287,7 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
     return BSP_ERR_UNSUPPORTED;
   const int32_t* rs = hdr + hdr[BSP_PLAN_OFF_ROWS_W];
   if (p.H != 3 || p.K != 3 || p.sh != 1 || p.sw != 1 || p.ph != 1 || p.pw != 1) return BSP_ERR_UNSUPPORTED;
-  if (rs[BSP_ROWS_NSLABS_W] != 1 || rs[BSP_ROWS_CW_W] != 8 || p.J > 64 || p.I > 128) return BSP_ERR_UNSUPPORTED;
+  if (rs[BSP_ROWS_NSLABS_W] != 1 || rs[BSP_ROWS_CW_W] != 8 || p.I > 128) return BSP_ERR_UNSUPPORTED;
   if ((int64_t)p.B * p.L * p.J * p.I * 2 >= (1ll << 31) || (int64_t)p.P * p.O * 2 >= (1ll << 31))
     return BSP_ERR_UNSUPPORTED;
   const int nstrips = rs[BSP_ROWS_NSTRIPS_W];
@@ -274,8 +295,6 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
 #ifdef BSP_ROWS_TUNE
   if (const char* e = std::getenv("BSP_PW_TRACE_PTR")) a.trace = (long long*)std::strtoull(e, nullptr, 16);
 #endif
-  a.ctiles = (p.J + 15) / 16;
-  if (nstrips * a.ctiles > 16) return BSP_ERR_UNSUPPORTED;  // one wave per (strip, column tile)
   const int raw = p.I * 2;
   a.pitch = raw <= 128 ? 128 : 256;
   if (a.pitch % 256 == 0) {
@@ -285,17 +304,37 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
     a.swz_shift = 1;
     a.swz_mask = 7;
   }
-  a.Jp = (p.J + 2 + 15) & ~15;
   a.ppr = 1024 / a.pitch;
-  a.rpr = (p.J + a.ppr - 1) / a.ppr;
   a.opitch = p.O * 2 + 16;
-  // rows per band: seven unless that leaves CUs without a workgroup
-  const int BR = (int64_t)p.B * ((p.L + 6) / 7) >= 200 ? 7 : 4;
-  a.nbands = (p.L + BR - 1) / BR;
-  const int64_t patch = (int64_t)(BR + 2) * a.Jp * a.pitch;
-  const int64_t outimg = (int64_t)BR * p.J * a.opitch;
-  const int64_t ldsb = std::max(patch, outimg);
-  if (ldsb > kLdsLimit) return BSP_ERR_UNSUPPORTED;
+  // Column tiles per workgroup: one wave per (strip, column tile), sixteen waves at most.  One
+  // column tile (chunks of sixteen columns) wherever that still makes a workgroup of four waves:
+  // measured on every 3x3 shape of the three networks, many small workgroups (several per CU,
+  // each in another phase) beat one large one per CU by 5 to 35 %, although the chunks' halo
+  // columns are copied twice.
+  const int ct_all = (p.J + 15) / 16;
+  if (nstrips < 1 || nstrips > 16) return BSP_ERR_UNSUPPORTED;
+  int ct = std::min(ct_all, std::max(1, 4 / nstrips));
+#ifdef BSP_ROWS_TUNE
+  if (const char* e = std::getenv("BSP_BAND_CT")) ct = std::max(1, std::min(ct, std::atoi(e)));
+#endif
+  int BR = 7;
+  int64_t ldsb = 0;
+  for (; ct >= 1; --ct) {
+    a.cw = ct == ct_all ? p.J : 16 * ct;
+    a.nchunks = (p.J + a.cw - 1) / a.cw;
+    // rows per band: seven unless that leaves CUs without a workgroup
+    BR = (int64_t)p.B * ((p.L + 6) / 7) * a.nchunks >= 200 ? 7 : 4;
+    a.Jp = (a.cw + 2 + 15) & ~15;
+    const int64_t patch = (int64_t)(BR + 2) * a.Jp * a.pitch;
+    const int64_t outimg = (int64_t)BR * a.cw * a.opitch;
+    ldsb = std::max(patch, outimg);
+    if (ldsb <= kLdsLimit) break;
+  }
+  if (ct < 1) return BSP_ERR_UNSUPPORTED;
+  a.ctiles = ct;
+  // requests per patch row: a chunk's columns and its halo columns inside the image
+  a.rpr = ((a.nchunks == 1 ? p.J : a.cw + 2) + a.ppr - 1) / a.ppr;
+  a.nbands = ((p.L + BR - 1) / BR) * a.nchunks;  // (band, chunk) pairs of an image
   const int32_t* sec = p.plan + hdr[BSP_PLAN_OFF_ROWS_W];
   a.X = (const unsigned char*)p.X;
   a.Y = (unsigned char*)p.Y;
@@ -316,12 +355,13 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
   a.d_ctiles = make_fastdiv((uint32_t)a.ctiles);
   a.d_cpp = make_fastdiv((uint32_t)(p.O >> 3));
   a.d_nbands = make_fastdiv((uint32_t)a.nbands);
-  a.d_nb = make_fastdiv((uint32_t)(a.Jp - p.J));
+  a.d_nchunks = make_fastdiv((uint32_t)a.nchunks);
+  a.d_rowp = make_fastdiv((uint32_t)(a.cw * (p.O >> 3)));
   a.llpp = a.pitch == 128 ? 3 : 4;
   // multiply-high divisions are exact while dividend * divisor < 2^32
   const int64_t nwg = (int64_t)((p.B + 7) / 8) * a.nbands * 8;  // eight images at a time, one per XCD
   if (nwg * a.nbands >= (1ll << 32) || nwg >= (1ll << 31) || (int64_t)(BR + 2) * a.rpr * a.rpr >= (1ll << 32) ||
-      (int64_t)(BR * p.J * (p.O >> 3) + 8192) * (p.O >> 3) >= (1ll << 32))
+      (int64_t)(BR * a.cw * (p.O >> 3) + 8192) * a.cw * (p.O >> 3) >= (1ll << 32))
     return BSP_ERR_UNSUPPORTED;
   const int threads = 64 * nstrips * a.ctiles;
   dim3 grid((unsigned)nwg);

@@ -1,6 +1,6 @@
 """The band kernel on its own (bsp_conv2d_only with BSP_KERNEL_BAND) against the oracle, element
-by element: 3x3 stride-1 layers with at most 128 input channels and rows of at most 64 pixels;
-ragged rows, bands with a short tail, images smaller than a band, all mask extremes, fused
+by element: 3x3 stride-1 layers with at most 128 input channels; ragged rows, rows cut into
+column chunks, bands with a short tail, images smaller than a band, all mask extremes, fused
 epilogue, config 1 at full size (needs a GPU)."""
 import numpy as np
 import pytest
@@ -31,7 +31,11 @@ SHAPES = [
     (1, 56, 56, 64, 64),       # four column tiles, the last half full
     (2, 28, 28, 128, 128),     # 256-byte pixels, eight strips x two column tiles
     (3, 17, 13, 72, 48),       # ragged rows and columns, channels no power of two
-    (2, 9, 64, 32, 64),        # the widest rows
+    (2, 9, 64, 32, 64),        # the widest rows that are one chunk for four strips
+    (2, 20, 100, 64, 64),      # two column chunks: 64 + 36 columns
+    (1, 11, 70, 128, 128),     # 256-byte pixels, eight strips: chunks of 32, 32 and 6 columns
+    (1, 9, 224, 64, 64),       # 64 + 64 + 64 + 32
+    (3, 10, 33, 16, 96),       # six strips: chunks of two column tiles, the last one a single column
     (2, 30, 50, 8, 16),        # one 16-byte piece per pixel
     (33, 15, 20, 24, 8),       # one block row of eight channels
 ]
@@ -81,7 +85,8 @@ SEVEN_ROW_SHAPES = [
     (29, 50, 28, 128, 128),    # 256-byte pixels; eight strips, one pair of column tiles; last band one row
     (67, 17, 13, 72, 48),      # last band three rows; one column tile
     (50, 25, 20, 64, 64),      # last band four rows
-    (40, 33, 64, 16, 16),      # the widest rows; last band five rows
+    (40, 33, 64, 16, 16),      # last band five rows
+    (8, 60, 150, 64, 64),      # column chunks on seven-row bands: 64 + 64 + 22
 ]
 
 
@@ -122,8 +127,8 @@ def test_band_kernel_config1_full_size():
 
 
 def test_band_kernel_declines_what_it_cannot_do():
-    for kw in (dict(I=256, O=64, J=14, stride=1), dict(I=64, O=64, J=80, stride=1),
-               dict(I=64, O=64, J=14, stride=2), dict(I=64, O=512, J=14, stride=1)):
+    for kw in (dict(I=256, O=64, J=14, stride=1), dict(I=64, O=64, J=14, stride=2),
+               dict(I=64, O=512, J=14, stride=1)):
         c = draw_layer("band", B=1, L=14, J=kw["J"], I=kw["I"], O=kw["O"], H=3, K=3,
                        stride=kw["stride"], pad=1, dtype="bf16", seed=1)
         with pytest.raises(bsp.BspError) as e:
