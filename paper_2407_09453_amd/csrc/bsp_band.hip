@@ -1,4 +1,4 @@
-// 3x3 layers (stride 1, padding 1, bf16) whose input channels fit one slab of the row-band plan
+// 3x3 layers (stride 1, padding 1 or 0, bf16) whose input channels fit one slab of the row-band plan
 // section (at most 128): one workgroup per band of BR output rows x chunk of CW columns (all
 // columns when the rows are at most 64 pixels wide), all output channels.
 //
@@ -34,6 +34,7 @@ struct BandArgs {
   const unsigned char* rfrag;
   int32_t relu, nstrips;
   int32_t B, L, J, I, O;
+  int32_t M, N, pad;  // output rows and columns; padding 1 (M = L, N = J) or 0 (M = L - 2, N = J - 2)
   int32_t nbands, ctiles;
   int32_t cw, nchunks;  // columns per chunk (a multiple of 16 when there are several chunks), chunks per row
   int32_t Jp, pitch, swz_shift, swz_mask;
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
   if (n >= a.B) return;
   const int band = (int)fdiv((uint32_t)bc, a.d_nchunks), chunk = bc - band * a.nchunks;
   const int y0 = band * BR, x0 = chunk * a.cw;
-  const int Jc = min(a.cw, a.J - x0);  // this chunk's columns: patch column pc holds image column x0 - 1 + pc
+  const int Jc = min(a.cw, a.N - x0);  // this chunk's output columns: patch column pc holds image column x0 - pad + pc
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
   const int rowbytes = a.Jp * a.pitch;
 
@@ -83,10 +84,10 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
     const int nreq = (BR + 2) * a.rpr;
     const int lpp = a.pitch >> 4;                 // 16-byte slots per pixel
     const int sp = lane / lpp, slot = lane - sp * lpp;
-    const int pc0 = x0 == 0 ? 1 : 0;  // (the first chunk's left halo column lies outside the image)
+    const int pc0 = (a.pad && x0 == 0) ? 1 : 0;  // (with padding the first chunk's left halo column lies outside the image)
     for (int rq = wave; rq < nreq; rq += nwaves) {
       const int fr = (int)fdiv((uint32_t)rq, a.d_rpr), grp = rq - fr * a.rpr;
-      const int row = y0 - 1 + fr, pc = pc0 + grp * a.ppr + sp, col = x0 - 1 + pc;
+      const int row = y0 - a.pad + fr, pc = pc0 + grp * a.ppr + sp, col = x0 - a.pad + pc;
       const uint32_t tp = (uint32_t)(fr * a.Jp + pc);
       const uint32_t piece = (uint32_t)slot ^ ((tp >> a.swz_shift) & (uint32_t)a.swz_mask);
       if ((unsigned)row < (unsigned)a.L && pc < Jc + 2 && (unsigned)col < (unsigned)a.J && piece * 8u < (uint32_t)a.I)
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
   // the image (patch column 0 of the first chunk, Jc + 1 of the last), whole rows outside it
   {
     const int lpp = a.pitch >> 4;  // slots per pixel (a power of two)
-    const bool left = x0 == 0, right = x0 + Jc == a.J;
+    const bool left = a.pad && x0 == 0, right = a.pad && x0 + Jc == a.N;
     for (int i = tid; i < (BR + 2) * 2 * lpp; i += (int)blockDim.x) {
       const int bp = i >> a.llpp, fr = bp >> 1, side = bp & 1;
       if (side == 0 ? !left : !right) continue;
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
     }
 #pragma unroll
     for (int fr = 0; fr < BR + 2; ++fr) {
-      if ((unsigned)(y0 - 1 + fr) < (unsigned)a.L) continue;
+      if ((unsigned)(y0 - a.pad + fr) < (unsigned)a.L) continue;
       for (int i = tid; i < (Jc + 2) * lpp; i += (int)blockDim.x)
         ((u32x4_t*)lds)[((fr * a.Jp) << a.llpp) + i] = u32x4_t{0, 0, 0, 0};
     }
@@ -203,14 +204,14 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
           u32x2_t{pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
     }
   }
-  const int rows_out = min(BR, a.L - y0);
+  const int rows_out = min(BR, a.M - y0);
   const int cpp = a.O >> 3;  // 16-byte pieces per pixel
   const int rowp = a.cw * cpp;  // pieces per row of the output image
   const int total = rows_out * rowp;
   // piece i of the image: row r, column xl of the chunk, piece k of the pixel; a row of the chunk
   // is one contiguous run of Y
-  const uint32_t y_off0 = (uint32_t)((n * a.L + y0) * a.J + x0) * (uint32_t)a.O * 2u;
-  const uint32_t y_row = (uint32_t)a.J * (uint32_t)a.O * 2u;
+  const uint32_t y_off0 = (uint32_t)((n * a.M + y0) * a.N + x0) * (uint32_t)a.O * 2u;
+  const uint32_t y_row = (uint32_t)a.N * (uint32_t)a.O * 2u;
   auto locate = [&](int i, uint32_t& src, uint32_t& dst) {
     const int pixel = (int)fdiv((uint32_t)i, a.d_cpp), k = i - pixel * cpp;
     src = (uint32_t)(pixel * a.opitch + k * 16);
@@ -286,7 +287,7 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
       hdr[BSP_PLAN_K_W] != p.K || hdr[BSP_PLAN_DTYPE_W] != dtype || hdr[BSP_PLAN_OFF_ROWS_W] == 0)
     return BSP_ERR_UNSUPPORTED;
   const int32_t* rs = hdr + hdr[BSP_PLAN_OFF_ROWS_W];
-  if (p.H != 3 || p.K != 3 || p.sh != 1 || p.sw != 1 || p.ph != 1 || p.pw != 1) return BSP_ERR_UNSUPPORTED;
+  if (p.H != 3 || p.K != 3 || p.sh != 1 || p.sw != 1 || p.ph != p.pw || p.ph < 0 || p.ph > 1) return BSP_ERR_UNSUPPORTED;
   if (rs[BSP_ROWS_NSLABS_W] != 1 || rs[BSP_ROWS_CW_W] != 8 || p.I > 128) return BSP_ERR_UNSUPPORTED;
   if ((int64_t)p.B * p.L * p.J * p.I * 2 >= (1ll << 31) || (int64_t)p.P * p.O * 2 >= (1ll << 31))
     return BSP_ERR_UNSUPPORTED;
@@ -311,7 +312,7 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
   // measured on every 3x3 shape of the three networks, many small workgroups (several per CU,
   // each in another phase) beat one large one per CU by 5 to 35 %, although the chunks' halo
   // columns are copied twice.
-  const int ct_all = (p.J + 15) / 16;
+  const int ct_all = (p.N + 15) / 16;
   if (nstrips < 1 || nstrips > 16) return BSP_ERR_UNSUPPORTED;
   int ct = std::min(ct_all, std::max(1, 4 / nstrips));
 #ifdef BSP_ROWS_TUNE
@@ -320,10 +321,13 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
   int BR = 7;
   int64_t ldsb = 0;
   for (; ct >= 1; --ct) {
-    a.cw = ct == ct_all ? p.J : 16 * ct;
-    a.nchunks = (p.J + a.cw - 1) / a.cw;
+    a.cw = ct == ct_all ? p.N : 16 * ct;
+    a.nchunks = (p.N + a.cw - 1) / a.cw;
     // rows per band: seven unless that leaves CUs without a workgroup
-    BR = (int64_t)p.B * ((p.L + 6) / 7) * a.nchunks >= 200 ? 7 : 4;
+    BR = (int64_t)p.B * ((p.M + 6) / 7) * a.nchunks >= 200 ? 7 : 4;
+#ifdef BSP_ROWS_TUNE
+    if (const char* e = std::getenv("BSP_BAND_BR")) BR = std::atoi(e) == 4 ? 4 : 7;
+#endif
     a.Jp = (a.cw + 2 + 15) & ~15;
     const int64_t patch = (int64_t)(BR + 2) * a.Jp * a.pitch;
     const int64_t outimg = (int64_t)BR * a.cw * a.opitch;
@@ -331,10 +335,13 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
     if (ldsb <= kLdsLimit) break;
   }
   if (ct < 1) return BSP_ERR_UNSUPPORTED;
+  // (rows in several chunks with fewer than four strips or thin pixels: measured slower than the
+  // LDS-resident kernel, which takes them)
+  if (a.nchunks > 1 && (nstrips < 4 || p.I < 64)) return BSP_ERR_UNSUPPORTED;
   a.ctiles = ct;
   // requests per patch row: a chunk's columns and its halo columns inside the image
-  a.rpr = ((a.nchunks == 1 ? p.J : a.cw + 2) + a.ppr - 1) / a.ppr;
-  a.nbands = ((p.L + BR - 1) / BR) * a.nchunks;  // (band, chunk) pairs of an image
+  a.rpr = ((a.nchunks == 1 && p.ph == 1 ? p.J : a.cw + 2) + a.ppr - 1) / a.ppr;
+  a.nbands = ((p.M + BR - 1) / BR) * a.nchunks;  // (band, chunk) pairs of an image
   const int32_t* sec = p.plan + hdr[BSP_PLAN_OFF_ROWS_W];
   a.X = (const unsigned char*)p.X;
   a.Y = (unsigned char*)p.Y;
@@ -349,6 +356,9 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
   a.B = p.B;
   a.L = p.L;
   a.J = p.J;
+  a.M = p.M;
+  a.N = p.N;
+  a.pad = p.ph;
   a.I = p.I;
   a.O = p.O;
   a.d_rpr = make_fastdiv((uint32_t)a.rpr);

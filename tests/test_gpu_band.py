@@ -31,11 +31,11 @@ SHAPES = [
     (1, 56, 56, 64, 64),       # four column tiles, the last half full
     (2, 28, 28, 128, 128),     # 256-byte pixels, eight strips x two column tiles
     (3, 17, 13, 72, 48),       # ragged rows and columns, channels no power of two
-    (2, 9, 64, 32, 64),        # the widest rows that are one chunk for four strips
+    (2, 9, 64, 64, 64),        # four chunks of sixteen columns
     (2, 20, 100, 64, 64),      # two column chunks: 64 + 36 columns
     (1, 11, 70, 128, 128),     # 256-byte pixels, eight strips: chunks of 32, 32 and 6 columns
     (1, 9, 224, 64, 64),       # 64 + 64 + 64 + 32
-    (3, 10, 33, 16, 96),       # six strips: chunks of two column tiles, the last one a single column
+    (3, 10, 33, 64, 96),       # six strips: chunks of 16, 16 and one column
     (2, 30, 50, 8, 16),        # one 16-byte piece per pixel
     (33, 15, 20, 24, 8),       # one block row of eight channels
 ]
@@ -50,6 +50,16 @@ def test_band_kernel_shapes(bo, bi):
                        dtype="bf16", mask_kind="bernoulli", density=0.5, seed=8900 + n, b_std=0.5)
         print("band case", n, (B, L, J, I, O, bo, bi), flush=True)
         assert_close(_run_band(c), oracle_conv(c), "bf16", f"band shape {n} {bo}x{bi}")
+
+
+@pytest.mark.parametrize("B,L,J,I,O", [(2, 14, 14, 64, 64), (3, 20, 37, 80, 192), (40, 30, 21, 64, 64),
+                                       (1, 5, 3, 16, 16)])
+def test_band_kernel_without_padding(B, L, J, I, O):
+    """Windows that stay inside the image (padding 0): the output is two rows and columns smaller."""
+    c = draw_layer("band0", B=B, L=L, J=J, I=I, O=O, H=3, K=3, stride=1, pad=0, dtype="bf16",
+                   mask_kind="bernoulli", density=0.5, seed=9000 + L, b_std=0.5)
+    assert (c.M, c.N) == (L - 2, J - 2)
+    assert_close(_run_band(c), oracle_conv(c), "bf16", f"band pad 0 {(B, L, J, I, O)}")
 
 
 @pytest.mark.parametrize("kind,density", [("zeros", 0.0), ("ones", 1.0), ("exact", 0.1),
@@ -81,7 +91,7 @@ def test_band_kernel_fused_epilogue():
 # Enough images for bands of seven rows (the small shapes above get four-row bands):
 # (B, L, J, I, O)
 SEVEN_ROW_SHAPES = [
-    (34, 41, 50, 24, 40),      # last band six rows; four column tiles, the last one ragged; three strips
+    (34, 41, 50, 72, 64),      # last band six rows; four chunks, the last one two columns; four strips
     (29, 50, 28, 128, 128),    # 256-byte pixels; eight strips, one pair of column tiles; last band one row
     (67, 17, 13, 72, 48),      # last band three rows; one column tile
     (50, 25, 20, 64, 64),      # last band four rows
@@ -128,7 +138,9 @@ def test_band_kernel_config1_full_size():
 
 def test_band_kernel_declines_what_it_cannot_do():
     for kw in (dict(I=256, O=64, J=14, stride=1), dict(I=64, O=64, J=14, stride=2),
-               dict(I=64, O=512, J=14, stride=1)):
+               dict(I=64, O=512, J=14, stride=1),
+               dict(I=32, O=64, J=40, stride=1),     # several chunks of thin pixels
+               dict(I=64, O=32, J=70, stride=1)):    # several chunks, two strips
         c = draw_layer("band", B=1, L=14, J=kw["J"], I=kw["I"], O=kw["O"], H=3, K=3,
                        stride=kw["stride"], pad=1, dtype="bf16", seed=1)
         with pytest.raises(bsp.BspError) as e:
