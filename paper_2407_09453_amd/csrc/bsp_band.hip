@@ -4,10 +4,10 @@
 //
 // The band's input rows (one halo row above and below, one halo column left and right of the
 // chunk) are runs of whole pixels of image rows, so they are copied global -> LDS with no
-// gather at all: an LDS image of (BR + 2) rows of Jp pixels (Jp a multiple of 16, which makes
-// the bank permutation slot = piece ^ f(pixel) independent of the row); the halo columns
-// that lie outside the image and the rows outside the image are cleared (they are never
-// copied into: no ordering between clearing and copying is needed).  Wave (strip s, column tile t)
+// gather at all: an LDS image of (BR + 2) rows of Jp = CW + 2 pixels with the bank permutation
+// slot = piece ^ f(patch column), the same in every row; the halo columns that lie outside the
+// image and the rows outside the image are cleared (they are never copied into: no ordering
+// between clearing and copying is needed).  Wave (strip s, column tile t)
 // owns 16 output columns x BR rows of strip s: per column step it reads the BR + 2 patch rows
 // of the step's (unit, dx) item once and issues 3 * BR MFMAs (output row r, window row dy
 // uses patch row r + dy), weights streamed from the plan through a register ring as in the
@@ -88,8 +88,7 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
     for (int rq = wave; rq < nreq; rq += nwaves) {
       const int fr = (int)fdiv((uint32_t)rq, a.d_rpr), grp = rq - fr * a.rpr;
       const int row = y0 - a.pad + fr, pc = pc0 + grp * a.ppr + sp, col = x0 - a.pad + pc;
-      const uint32_t tp = (uint32_t)(fr * a.Jp + pc);
-      const uint32_t piece = (uint32_t)slot ^ ((tp >> a.swz_shift) & (uint32_t)a.swz_mask);
+      const uint32_t piece = (uint32_t)slot ^ (((uint32_t)pc >> a.swz_shift) & (uint32_t)a.swz_mask);
       if ((unsigned)row < (unsigned)a.L && pc < Jc + 2 && (unsigned)col < (unsigned)a.J && piece * 8u < (uint32_t)a.I)
         __builtin_amdgcn_global_load_lds(
             (gptr_t)(a.X + (((uint32_t)((n * a.L + row) * a.J + col)) * (uint32_t)a.I + piece * 8u) * 2u),
@@ -328,7 +327,7 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
 #ifdef BSP_ROWS_TUNE
     if (const char* e = std::getenv("BSP_BAND_BR")) BR = std::atoi(e) == 4 ? 4 : 7;
 #endif
-    a.Jp = (a.cw + 2 + 15) & ~15;
+    a.Jp = a.cw + 2;
     const int64_t patch = (int64_t)(BR + 2) * a.Jp * a.pitch;
     const int64_t outimg = (int64_t)BR * a.cw * a.opitch;
     ldsb = std::max(patch, outimg);
