@@ -65,7 +65,7 @@ struct RowsArgs {
   int32_t tbl_off;                 // LDS offset of the tables
   int32_t piece8;                  // results leave as 8-byte pieces (4x16 blocks)
   int32_t direct;                  // results leave straight from the accumulators, 8 bytes per lane
-  int32_t xlimit, ylimit;          // input / output pixels that exist
+  int32_t ylimit;                  // output pixels that exist
   int32_t lsg, lptw;               // log2 of SG and PTW
   FastDiv d_pcp, d_pr, d_np, d_br, d_nsg, d_tpi, d_tx, d_perimg, d_tw;
 #ifdef BSP_ROWS_TUNE
@@ -134,28 +134,15 @@ __device__ __forceinline__ void rows_tables(const RowsArgs& a, const TilePos& t,
   }
 }
 
-// Clear the staged pixels that lie outside the image, in every patch buffer.
-__device__ __forceinline__ void rows_clear_outside(const RowsArgs& a, const TilePos& t, unsigned char* lds) {
-  const int iy0 = t.y0 * a.stride - a.ph, ix0 = t.x0 * a.stride - a.pw;
-  const int npixels = a.NI * a.PR * a.PCp;
-  for (int pix = threadIdx.x; pix < npixels; pix += blockDim.x) {
-    const int row = (int)fdiv((uint32_t)pix, a.d_pcp), pc = pix - row * a.PCp;
-    const int img = (int)fdiv((uint32_t)row, a.d_pr), pr = row - img * a.PR;
-    const int gi = t.img0 + img, gy = iy0 + pr * a.gs, gx = ix0 + pc * a.gs;
-    const bool inside = gi < a.B && (unsigned)gy < (unsigned)a.L && (unsigned)gx < (unsigned)a.J &&
-                        (gi * a.L + gy) * a.J + gx < a.xlimit;
-    if (!inside && pc < a.PC) {
-      u32x4_t* p0 = (u32x4_t*)(lds + ((size_t)pix << (a.lscp + 4)));
-      for (int k = 0; k < (1 << a.lscp); ++k) {
-        p0[k] = u32x4_t{0, 0, 0, 0};
-        if (a.nstaged > 1) p0[k + (a.bufbytes >> 4)] = u32x4_t{0, 0, 0, 0};
-      }
-    }
-  }
-}
+// Sixteen zero bytes: what the copies read for the staged pixels that lie outside the image.
+__device__ __align__(16) const unsigned char rows_zero16[16] = {0};
 
-// Request staged slab sl (G plan slabs) of the tile's patch: wave w of nw takes every nw-th staged row.  Nothing
-// waits here; the copies complete in the background (vmcnt of the requesting wave).
+// Request staged slab sl (G plan slabs) of the tile's patch with the nw waves numbered w = 0 .. nw - 1:
+// side by side over the staged rows and, where there are fewer rows than waves, over the
+// requests of a row as well.  Nothing waits here; the copies complete in the background (vmcnt of
+// the requesting wave).  A staged pixel outside the image (padding) is copied from the zero
+// bytes above, so the patch needs no clearing: clearing by LDS stores cost the small layers,
+// whose patches are mostly padding, more than the copies themselves.
 __device__ __forceinline__ void rows_stage(const RowsArgs& a, const TilePos& t, unsigned char* lds, int sl,
                                            int w, int nw) {
   const int lane = threadIdx.x & 63;
@@ -167,30 +154,55 @@ __device__ __forceinline__ void rows_stage(const RowsArgs& a, const TilePos& t, 
   const int iy0 = t.y0 * a.stride - a.ph, ix0 = t.x0 * a.stride - a.pw;
   const int groups = a.PCp >> lppi;     // requests per staged row
   const int nrows = a.NI * a.PR;
-  // lane j: the j-th staged row of this wave, where it starts in X (or all ones: outside)
-  uint32_t rowsrc = 0xFFFFFFFFu;
-  const int myrow = w + lane * nw;
+  // wave w = (wr over the rows, wg over a row's requests)
+  const int nwr = min(nw, nrows);
+  int wr = w, wg = 0, nwg = 1;
+  while (wr >= nwr) {
+    wr -= nwr;
+    ++wg;
+  }
+  while ((nwg + 1) * nwr <= nw) ++nwg;
+  if (wg >= nwg) return;
+  // lane j: the j-th staged row of this wave, where it starts in X; kRowPad: a row above or
+  // below the image; kRowNone: an image past the end of the batch (nothing is stored from it)
+  constexpr uint32_t kRowNone = 0xFFFFFFFFu, kRowPad = 0xFFFFFFFEu;
+  uint32_t rowsrc = kRowNone;
+  const int myrow = wr + lane * nwr;
   if (myrow < nrows) {
     const int img = (int)fdiv((uint32_t)myrow, a.d_pr), pr = myrow - img * a.PR;
     const int gi = t.img0 + img, gy = iy0 + pr * a.gs;
-    if (gi < a.B && (unsigned)gy < (unsigned)a.L) rowsrc = (uint32_t)((gi * a.L + gy) * a.J) * (uint32_t)a.I * 2u;
+    if (gi < a.B) rowsrc = (unsigned)gy < (unsigned)a.L ? (uint32_t)((gi * a.L + gy) * a.J) * (uint32_t)a.I * 2u : kRowPad;
   }
-  const int nrw = (nrows - w + nw - 1) / nw;
-  for (int gq = 0; gq < groups; ++gq) {
+  const unsigned char* zero = rows_zero16;
+  const bool fill = sl == 0;  // the padding of both buffers is written with the first slab (all waves share that); later slabs leave it alone
+  for (int gq = wg; gq < groups; gq += nwg) {
     const int pc = (gq << lppi) + sub_pix;               // staged column of this lane
     const int cq = sidx ^ ((pc >> a.swz_shift) & a.swz_mask);
     const int gx = ix0 + pc * a.gs;
     const int ch = (sl * a.scs + cq) * 8;
-    const bool col_real = cq < a.scs && ch < a.I && pc < a.PC && (unsigned)gx < (unsigned)a.J;
+    const bool wanted = cq < a.scs && ch < a.I && pc < a.PC;  // a slot some column step reads
+    const bool col_real = wanted && (unsigned)gx < (unsigned)a.J;
     const uint32_t col_off = ((uint32_t)gx * (uint32_t)a.I + (uint32_t)ch) * 2u;
-    const uint32_t col_end = (uint32_t)(a.xlimit - gx) * (uint32_t)a.I * 2u;  // rows starting below this exist
-    for (int j = 0; j < nrw; ++j) {
+    const bool some_pad = __ballot(wanted && !col_real) != 0;
+    uint32_t dst = buf + ((uint32_t)(wr * a.PCp + (gq << lppi)) << (a.lscp + 4));
+    const uint32_t dst_step = (uint32_t)(nwr * a.PCp) << (a.lscp + 4);
+    for (int j = 0, row = wr; row < nrows; ++j, row += nwr, dst += dst_step) {
       const uint32_t src = __builtin_amdgcn_readlane(rowsrc, j);
-      if (src == 0xFFFFFFFFu) continue;
-      const uint32_t dst = buf + ((uint32_t)((w + j * nw) * a.PCp + (gq << lppi)) << (a.lscp + 4));
-      if (col_real && src < col_end)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.X + (src + col_off)),
+      if (src == kRowNone) continue;
+      const bool row_real = src != kRowPad;
+      // the real pixels from X (one scalar base per row, one offset per lane), the padding from the zero bytes
+      if (row_real && col_real)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.X + src + col_off),
                                          (__attribute__((address_space(3))) void*)(uintptr_t)dst, 16, 0, 0);
+      if (fill && (some_pad || !row_real)) {
+        if (wanted && !(row_real && col_real)) {
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)zero,
+                                           (__attribute__((address_space(3))) void*)(uintptr_t)dst, 16, 0, 0);
+          if (a.nstaged > 1)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)zero,
+                                             (__attribute__((address_space(3))) void*)(uintptr_t)(dst + a.bufbytes), 16, 0, 0);
+        }
+      }
     }
   }
 }
@@ -305,8 +317,53 @@ __global__ __launch_bounds__(640) __attribute__((amdgpu_waves_per_eu(H == 3 && N
     for (int r = 0; r < BR; ++r) acc[j][r] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const int rowbytes = a.PCp << (a.lscp + 4);
-  // (cleared pixels and requested pixels are disjoint: no barrier between the two)
-  rows_clear_outside(a, tp, lds);
+
+  // ---- compute waves: the strip's column steps come from the plan through a ring of registers,
+  // D steps ahead (weight fragments and item descriptors).  A strip's steps are numbered
+  // consecutively through all its slabs; with the contraction split KS ways (a power of two)
+  // this wave takes the steps whose number is ks modulo KS, so its sequence is one arithmetic
+  // progression from start to finish and the ring never has to be turned at a slab's end.
+  // The first D steps are asked for before the patch is: their latency passes while the
+  // requests for the patch are being issued.
+  // entry i: the first step of slab i.  The table is read with scalar loads (the plan is never
+  // written by a kernel): the address is made a scalar explicitly
+  typedef const __attribute__((address_space(4))) int32_t* cptr_t;
+  const uint64_t rsl_v = (uint64_t)(uintptr_t)(a.rslab + (active ? strip : 0) * (a.nslabs + 1));
+  // (the builtin returns a signed int: widened through uint32_t, or the low half's top bit would spill over the high half)
+  const uint32_t rsl_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)rsl_v);
+  const uint32_t rsl_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(rsl_v >> 32));
+  const cptr_t rsl = (cptr_t)(uintptr_t)((uint64_t)rsl_lo | ((uint64_t)rsl_hi << 32));
+  const int ksm = a.KS - 1;
+  int s_first = 0, s_end = 0, fnext = 0;
+  const uint32_t frag_lane = (uint32_t)lane * 16u, desc_lane = (uint32_t)g * 4u;
+  const unsigned char* fragb = (const unsigned char*)a.rfrag;
+  const unsigned char* descb = (const unsigned char*)a.rdesc;
+  u32x4_t wr[D][H];  // weight fragments of the next D steps of the sequence
+  int dr[D];         // their item descriptors
+  // Slot d takes the next step of the sequence; past the end it asks for the last step
+  // again (never used): every pass through the unrolled loop below issues the same loads,
+  // which lets the compiler wait for exactly the slot it needs.
+  auto fetch = [&](int d) {
+    const int cs = max(0, min(fnext, s_end - 1));
+    fnext += a.KS;
+    dr[d] = *(const int*)(descb + ((uint32_t)cs * 16u + desc_lane));
+    const uint32_t off = (uint32_t)cs * (uint32_t)(H * 1024) + frag_lane;
+#pragma unroll
+    for (int dy = 0; dy < H; ++dy) wr[d][dy] = *(const u32x4_t*)(fragb + off + dy * 1024);
+  };
+  if (!mover) {
+    // the strip's first and last step as scalar loads (the plan is never written by a kernel)
+    s_first = rsl[0];
+    s_end = rsl[a.nslabs];
+    fnext = s_first + ((ks - s_first) & ksm);
+    if (active) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        fetch(d);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
   ROWS_MARK(1);
   rows_stage(a, tp, lds, 0, wave_u, (int)(blockDim.x >> 6));  // the first slab: all waves together
   ROWS_MARK(2);
@@ -324,48 +381,6 @@ __global__ __launch_bounds__(640) __attribute__((amdgpu_waves_per_eu(H == 3 && N
     }
     __syncthreads();                  // the last slab is done
   } else {
-    // ---- compute waves.  The strip's column steps, slab after slab; their weight fragments
-    // and descriptors come from the plan through a ring of registers, D steps ahead.
-    const int* rsl = a.rslab + (active ? strip : 0) * (a.nslabs + 1);
-    const int vr = rsl[min(lane, a.nslabs)];  // lane i holds the first step of slab i
-    // A strip's steps are numbered consecutively through all its slabs.  With the
-    // contraction split KS ways (a power of two) this wave takes the steps whose number is
-    // ks modulo KS, so its sequence is one arithmetic progression from start to finish.
-    const int ksm = a.KS - 1;
-    // the strip's first and last step as scalar loads: they do not queue behind the patch's
-    // copies the way the table above does, and the first weights can be asked for at once
-    uint32_t s_first_u, s_end_u;
-    asm volatile("s_load_dword %0, %2, 0x0\n\ts_load_dword %1, %3, 0x0\n\ts_waitcnt lgkmcnt(0)"
-                 : "=&s"(s_first_u), "=&s"(s_end_u)
-                 : "s"(rsl), "s"(rsl + a.nslabs)
-                 : "memory");
-    const int s_first = (int)s_first_u, s_end = (int)s_end_u;
-    int fnext = s_first + ((ks - s_first) & ksm);
-    const uint32_t frag_lane = (uint32_t)lane * 16u, desc_lane = (uint32_t)g * 4u;
-    const unsigned char* fragb = (const unsigned char*)a.rfrag;
-    const unsigned char* descb = (const unsigned char*)a.rdesc;
-    u32x4_t wr[D][H];  // weight fragments of the next D steps of the sequence, oldest in slot 0
-    int dr[D];         // their item descriptors
-    int at[D];         // which step each slot holds
-    // Slot d takes the next step of the sequence (advance) or asks for the step it already
-    // holds again: every pass through the unrolled loop below then issues the same loads,
-    // whatever the step count, which lets the compiler wait for exactly the slot it needs.
-    auto fetch = [&](int d, bool advance) {
-      const int cs = advance ? max(0, min(fnext, s_end - 1)) : at[d];  // past the end: a valid step, never used
-      fnext += advance ? a.KS : 0;
-      at[d] = cs;
-      dr[d] = *(const int*)(descb + ((uint32_t)cs * 16u + desc_lane));
-      const uint32_t off = (uint32_t)cs * (uint32_t)(H * 1024) + frag_lane;
-#pragma unroll
-      for (int dy = 0; dy < H; ++dy) wr[d][dy] = *(const u32x4_t*)(fragb + off + dy * 1024);
-    };
-    if (active) {
-#pragma unroll
-      for (int d = 0; d < D; ++d) {
-        at[d] = 0;
-        fetch(d, true);
-      }
-    }
     ROWS_MARK(3);
     if (tid < a.SG * 4) chans[tid] = chan_v;  // (wave 0 is a compute wave)
     __builtin_amdgcn_s_waitcnt(0);  // this wave's share of the first patch has landed
@@ -376,93 +391,99 @@ __global__ __launch_bounds__(640) __attribute__((amdgpu_waves_per_eu(H == 3 && N
     for (int j = 0; j < NT; ++j) pixb[j] = colpix[(pt * NT + j) * 16 + c];
     u32x4_t f[NT][NF];  // the patch rows of the step at hand
 
-    for (int ss = 0; ss < a.nstaged; ++ss) {
-      for (int k = 0; k < a.G && active; ++k) {
-        const int sl = ss * a.G + k;
-        if (sl >= a.nslabs) break;
-        const unsigned char* buf = lds + (ss & 1) * a.bufbytes;
-        const uint32_t uoff = (uint32_t)(k * a.sc);  // where this plan slab's pieces start in a staged pixel
-        int lo = __builtin_amdgcn_readlane(vr, sl);
-        const int hi = __builtin_amdgcn_readlane(vr, sl + 1);
-        lo += (ks - lo) & ksm;  // this wave's first step of the slab
-        const int stepd = a.KS * D;
-        // The fragments of a slab's first step are read ahead of its loop; inside, a step's
-        // MFMAs run patch row by patch row (row k feeds output rows k - dy), and as soon as the
-        // ones that read row k have been issued the next step's row k is asked for into the same
-        // registers: the matrix cores work through a step while the next one's fragments arrive.
-        constexpr bool ROLL = H > 1;  // (a one-row window's fragments feed one MFMA each: read per step)
-        if (ROLL && lo < hi) {
+    // A step's MFMAs run patch row by patch row (row k feeds output rows k - dy), and as soon as
+    // the ones that read row k have been issued the next step's row k is asked for into the same
+    // registers: the matrix cores work through a step while the next one's fragments arrive.
+    // A step reads nothing but the next step's fragments, so where the next step lies in the
+    // next staged slab the wave passes that slab's barrier before the step, not after it.
+    constexpr bool ROLL = H > 1;  // (a one-row window's fragments feed one MFMA each: read per step)
+    int cs = s_first + ((ks - s_first) & ksm);  // this wave's next step
+    int sl = 0, ss = 0;                          // a plan slab; the staged slab the workgroup is at
+    int hi = rsl[1];                             // where plan slab sl ends
+    const unsigned char* buf = lds;
+    uint32_t uoff = 0;  // where plan slab sl's pieces start in a staged pixel
+    // (uniform) make sl the slab of step at < s_end; on the way into a later staged slab, the
+    // barriers that say the slabs before it are done everywhere and it has landed
+    auto enter = [&](int at) {
+      while (at >= hi) {
+        ++sl;
+        hi = rsl[sl + 1];
+      }
+      while ((ss + 1) * a.G <= sl) {
+        __syncthreads();
+        ++ss;
+      }
+      buf = lds + (ss & 1) * a.bufbytes;
+      uoff = (uint32_t)((sl - ss * a.G) * a.sc);
+    };
+    auto step = [&](int d) {
+      if (!ROLL) {
+        enter(cs);
 #pragma unroll
-          for (int j = 0; j < NT; ++j) rows_read<H, S, BR, CW4>(a, buf, (uint32_t)dr[0], pixb[j], rowbytes, uoff, f[j]);
-        }
-        for (int cs0 = lo; cs0 < hi; cs0 += stepd) {
+        for (int j = 0; j < NT; ++j) rows_read<H, S, BR, CW4>(a, buf, (uint32_t)dr[d], pixb[j], rowbytes, uoff, f[j]);
 #pragma unroll
-          for (int d = 0; d < D; ++d) {
-            const bool use = cs0 + d * a.KS < hi;
-            if (use && !ROLL) {
+        for (int dy = 0; dy < H; ++dy)
 #pragma unroll
-              for (int j = 0; j < NT; ++j) rows_read<H, S, BR, CW4>(a, buf, (uint32_t)dr[d], pixb[j], rowbytes, uoff, f[j]);
+          for (int j = 0; j < NT; ++j)
 #pragma unroll
-              for (int dy = 0; dy < H; ++dy)
+            for (int r = 0; r < BR; ++r)
+              acc[j][r] = mfma_bf16_16x16x32(wr[d][dy], f[j][r * S + dy], acc[j][r]);
+        cs += a.KS;
+      } else {
+        // (the last step of all asks for its own fragments again: nobody reads them)
+        const int nxt = cs + a.KS;
+        const bool pre = nxt < s_end;
+        if (pre) enter(nxt);
+        const uint32_t dn = (uint32_t)(pre ? dr[(d + 1) % D] : dr[d]);
+        RowsAd nad[NT];
 #pragma unroll
-                for (int j = 0; j < NT; ++j)
+        for (int j = 0; j < NT; ++j) nad[j] = rows_addr<CW4>(a, dn, pixb[j], uoff);
 #pragma unroll
-                  for (int r = 0; r < BR; ++r)
-                    acc[j][r] = mfma_bf16_16x16x32(wr[d][dy], f[j][r * S + dy], acc[j][r]);
-            }
-            if (use && ROLL) {
-              // (the slab's last step asks for its own fragments again: nobody reads them)
-              const bool pre = cs0 + (d + 1) * a.KS < hi;
-              const uint32_t dn = (uint32_t)(pre ? dr[(d + 1) % D] : dr[d]);
-              RowsAd nad[NT];
+        for (int k = 0; k < NF; ++k) {
 #pragma unroll
-              for (int j = 0; j < NT; ++j) nad[j] = rows_addr<CW4>(a, dn, pixb[j], uoff);
+          for (int dy = 0; dy < H; ++dy) {
+            if (k - dy < 0 || (k - dy) % S != 0 || (k - dy) / S >= BR) continue;
 #pragma unroll
-              for (int k = 0; k < NF; ++k) {
-#pragma unroll
-                for (int dy = 0; dy < H; ++dy) {
-                  if (k - dy < 0 || (k - dy) % S != 0 || (k - dy) / S >= BR) continue;
-#pragma unroll
-                  for (int j = 0; j < NT; ++j)
-                    acc[j][(k - dy) / S] = mfma_bf16_16x16x32(wr[d][dy], f[j][k], acc[j][(k - dy) / S]);
-                }
-                if (row_needed<H, S, BR>(k)) {
-#pragma unroll
-                  for (int j = 0; j < NT; ++j) f[j][k] = rows_frag<CW4>(buf, nad[j], k * rowbytes);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-              }
-            }
-            // refill the slot only now, in place: requested earlier, the new fragments would
-            // need registers of their own and be copied over once the MFMAs have read the old
-            // ones, and a copy has to wait for its load
-            __builtin_amdgcn_sched_barrier(0);
-            fetch(d, use);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int j = 0; j < NT; ++j)
+              acc[j][(k - dy) / S] = mfma_bf16_16x16x32(wr[d][dy], f[j][k], acc[j][(k - dy) / S]);
           }
-        }
-        // the slab's steps need not fill the ring a whole number of times: turn the ring so
-        // that the next step to use is in slot 0 again
-        const int turn = lo < hi ? ((hi - lo + ksm) / a.KS) % D : 0;
-        for (int k = 0; k < turn; ++k) {
-          u32x4_t t[H];
-          const int td = dr[0], ta = at[0];
+          if (row_needed<H, S, BR>(k)) {
 #pragma unroll
-          for (int dy = 0; dy < H; ++dy) t[dy] = wr[0][dy];
-#pragma unroll
-          for (int d = 0; d + 1 < D; ++d) {
-            dr[d] = dr[d + 1];
-            at[d] = at[d + 1];
-#pragma unroll
-            for (int dy = 0; dy < H; ++dy) wr[d][dy] = wr[d + 1][dy];
+            for (int j = 0; j < NT; ++j) f[j][k] = rows_frag<CW4>(buf, nad[j], k * rowbytes);
           }
-          dr[D - 1] = td;
-          at[D - 1] = ta;
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        cs = nxt;
+      }
+    };
+    if (ROLL && active && cs < s_end) {
+      enter(cs);
 #pragma unroll
-          for (int dy = 0; dy < H; ++dy) wr[D - 1][dy] = t[dy];
+      for (int j = 0; j < NT; ++j) rows_read<H, S, BR, CW4>(a, buf, (uint32_t)dr[0], pixb[j], rowbytes, uoff, f[j]);
+    }
+    if (active) {
+      // passes that refill the ring while more than D steps remain (a slot is refilled only
+      // after the MFMAs that read it, in place: requested earlier, the new fragments would
+      // need registers of their own), then the steps the ring already holds
+      while (cs + D * a.KS < s_end) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+          step(d);
+          __builtin_amdgcn_sched_barrier(0);
+          fetch(d);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
-      __syncthreads();  // this slab is done everywhere and the next one has landed
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        if (cs >= s_end) break;
+        step(d);
+      }
+    }
+    // the barriers of the staged slabs this wave had no step in: each slab's end is one
+    while (ss < a.nstaged) {
+      __syncthreads();
+      ++ss;
     }
   }
 
@@ -657,6 +678,8 @@ static bool rows_choose(const ConvParams& p, const int32_t* rs, int S, Choice* b
   for (int BR : {7, 4}) {
     for (int NT : {1, 2}) {
       if (BR == 7 && NT == 2) continue;
+      // (two column tiles of 4-channel units at stride 2 do not fit the register file)
+      if (NT == 2 && S == 2 && p.H > 1 && rs[BSP_ROWS_CW_W] == 4) continue;
       for (int SG : {1, 2, 4, 8}) {
         if (SG > nstrips && SG != 1) continue;
         for (int KS : {1, 2, 4}) {
@@ -782,7 +805,6 @@ static int rows_fill_common(const ConvParams& p, const ConvParams& v, const int3
   a.piece8 = hdr[BSP_PLAN_BO_W] == 4;
   a.direct = 1;
   a.tbl_off = (int32_t)geo.body;
-  a.xlimit = p.B * p.L * p.J;
   a.ylimit = p.P;
   const int64_t nstage = geo.bufbytes / 16;
   if (geo.ntiles >= (1 << 24) || nstage >= (1 << 24) || (int64_t)a.per_xcd * 8 >= (1ll << 31))
