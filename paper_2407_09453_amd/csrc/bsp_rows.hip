@@ -617,7 +617,9 @@ int launch_hs(const RowsArgs& a, int BR, int NT, dim3 grid, int threads, size_t 
   constexpr int D = H == 1 ? 8 : (H == 3 ? 3 : 2);
   if (BR == 7 && NT == 1) return launch_inst<H, S, 7, 1, CW4, D>(a, grid, threads, ldsb, st);
   if (BR == 4 && NT == 1) return launch_inst<H, S, 4, 1, CW4, D>(a, grid, threads, ldsb, st);
-  if (BR == 4 && NT == 2) return launch_inst<H, S, 4, 2, CW4, D>(a, grid, threads, ldsb, st);
+  if constexpr (H <= 3) {  // (two column tiles of a seven-row window do not fit the register file)
+    if (BR == 4 && NT == 2) return launch_inst<H, S, 4, 2, CW4, D>(a, grid, threads, ldsb, st);
+  }
   return BSP_ERR_UNSUPPORTED;
 }
 
@@ -680,6 +682,7 @@ static bool rows_choose(const ConvParams& p, const int32_t* rs, int S, Choice* b
       if (BR == 7 && NT == 2) continue;
       // (two column tiles of 4-channel units at stride 2 do not fit the register file)
       if (NT == 2 && S == 2 && p.H > 1 && rs[BSP_ROWS_CW_W] == 4) continue;
+      if (NT == 2 && p.H > 3) continue;
       for (int SG : {1, 2, 4, 8}) {
         if (SG > nstrips && SG != 1) continue;
         for (int KS : {1, 2, 4}) {
@@ -689,13 +692,16 @@ static bool rows_choose(const ConvParams& p, const int32_t* rs, int S, Choice* b
             const int slots = PTW * NT * 16;  // columns a workgroup can hold
             for (int G : {1, 2, 4}) {
               if (G > 1 && G / 2 >= nslabs) continue;
-              for (int mode = 0; mode < 3; ++mode) {
+              for (int mode = 0; mode < 4; ++mode) {
                 Choice c{BR, NT, 0, 1, 1, SG, PTW, KS, 0.0};
                 c.G = G;
                 if (mode == 0) {           // whole image rows, several bands
                   c.TW = p.N;
                   if (c.TW > slots) continue;
                   c.NB = std::min(slots / c.TW, (p.M + BR - 1) / BR);
+                } else if (mode == 3) {    // whole image rows, one band (a smaller patch per workgroup, more workgroups)
+                  c.TW = p.N;
+                  if (c.TW > slots || std::min(slots / c.TW, (p.M + BR - 1) / BR) < 2) continue;
                 } else if (mode == 1) {    // several images, every band of each
                   c.TW = p.N;
                   c.NB = (p.M + BR - 1) / BR;
@@ -717,10 +723,11 @@ static bool rows_choose(const ConvParams& p, const int32_t* rs, int S, Choice* b
                 // eight cycles, so a column step costs its MFMAs plus its other instructions;
                 // a second wave on the SIMD hides most of that
                 const double step_mfma = p.H * BR * NT * 8.0, step_other = (20.0 + 10.0 * NT * ((BR - 1) * S + p.H)) * 4.0;
-                // workgroups a CU holds at once: LDS, and the registers (between 92 and 168 per
-                // lane: three to five waves per SIMD, as the kernel's instances are compiled), a
-                // workgroup's waves being dealt round over the four SIMDs
-                const int occ = p.H == 1 ? (NT == 1 ? 5 : 4) : (NT == 1 && (S == 1 || BR == 4) ? 4 : 3);
+                // workgroups a CU holds at once: LDS, and the registers (between 77 and 168 per
+                // lane: three to six waves per SIMD, as the kernel's instances are compiled), a
+                // workgroup's waves being dealt round over the four SIMDs from the first one on
+                // (two workgroups of ten waves need six waves on a SIMD, not five)
+                const int occ = p.H == 1 ? (NT == 2 ? 4 : BR == 4 ? 6 : 5) : (p.H == 3 && NT == 1 && (S == 1 || BR == 4) ? 4 : 3);
                 const int wg_per_cu = (int)std::max<int64_t>(
                     1, std::min<int64_t>(kLdsLimit / g.ldsb, occ / ((waves + c.NM + 3) / 4)));
                 const double conc = std::min<double>(wg_per_cu, std::max(1.0, (double)nwg / cus));
@@ -734,6 +741,12 @@ static bool rows_choose(const ConvParams& p, const int32_t* rs, int S, Choice* b
                 const double t_wg = t_stage0 + std::max(t_compute, t_mover) + 250.0 * nstaged + t_epi;
                 const double rounds = std::ceil((double)nwg / ((double)cus * wg_per_cu));
                 c.cost = rounds * t_wg;
+#ifdef BSP_ROWS_TUNE
+                if (std::getenv("BSP_ROWS_COSTS"))
+                  fprintf(stderr, "cand %d,%d,%d,%d,%d,%d,%d,%d,%d,%d nwg=%lld wgcu=%d conc=%.2f stage0=%.0f comp=%.0f mover=%.0f epi=%.0f nst=%d rounds=%.0f cost=%.0f\n",
+                          c.BR, c.NT, c.TW, c.NB, c.NI, c.SG, c.PTW, c.KS, c.G, c.NM, (long long)nwg, wg_per_cu, conc, t_stage0,
+                          t_compute, t_mover, t_epi, nstaged, rounds, c.cost);
+#endif
                 if (c.cost < best->cost) *best = c;
               }
             }
@@ -837,7 +850,7 @@ int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipSt
     return BSP_ERR_UNSUPPORTED;
   const int32_t* rs = hdr + hdr[BSP_PLAN_OFF_ROWS_W];
   if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return BSP_ERR_UNSUPPORTED;
-  if (p.H != 1 && p.H != 3) return BSP_ERR_UNSUPPORTED;
+  if (p.H != 1 && p.H != 3 && !(p.H == 7 && p.sh == 1)) return BSP_ERR_UNSUPPORTED;  // (window heights the kernel is compiled for)
   if ((int64_t)p.B * p.L * p.J * p.I * 2 >= (1ll << 31) || (int64_t)p.P * p.O * 2 >= (1ll << 31))
     return BSP_ERR_UNSUPPORTED;
   if (p.H == 1 && p.K == 1) return BSP_ERR_UNSUPPORTED;  // pointwise layers: bsp_pw.hip
@@ -879,10 +892,12 @@ int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipSt
   const size_t ldsb = (size_t)geo.ldsb;
   if (cw == 4) {
     if (p.H == 1) return launch_hs<1, 1, true>(a, ch.BR, ch.NT, grid, threads, ldsb, st);
+    if (p.H == 7) return launch_hs<7, 1, true>(a, ch.BR, ch.NT, grid, threads, ldsb, st);
     return S == 1 ? launch_hs<3, 1, true>(a, ch.BR, ch.NT, grid, threads, ldsb, st)
                   : launch_hs<3, 2, true>(a, ch.BR, ch.NT, grid, threads, ldsb, st);
   }
   if (p.H == 1) return launch_hs<1, 1, false>(a, ch.BR, ch.NT, grid, threads, ldsb, st);
+  if (p.H == 7) return launch_hs<7, 1, false>(a, ch.BR, ch.NT, grid, threads, ldsb, st);
   return S == 1 ? launch_hs<3, 1, false>(a, ch.BR, ch.NT, grid, threads, ldsb, st)
                 : launch_hs<3, 2, false>(a, ch.BR, ch.NT, grid, threads, ldsb, st);
 }

@@ -1,5 +1,5 @@
 """The row-band kernel on its own (bsp_conv2d_only with BSP_KERNEL_ROWS) against the oracle,
-element by element: 3xK and 1xK windows (K > 1), strides 1 and 2, all granularities, ragged image
+element by element: 7xK, 3xK and 1xK windows (1xK with K > 1), strides 1 and 2, all granularities, ragged image
 sizes and tile tails, empty strips, fused epilogue (needs a GPU)."""
 import numpy as np
 import pytest
@@ -38,6 +38,9 @@ SHAPES = [
     (2, 12, 12, 32, 16, 1, 3, 1, (0, 1)),  # 1x3
     (2, 12, 12, 32, 16, 3, 1, 1, (1, 0)),  # 3x1
     (1, 17, 17, 128, 64, 1, 7, 1, (0, 3)),  # 1x7
+    (2, 17, 17, 160, 48, 7, 1, 1, (3, 0)),  # 7x1, two slabs
+    (1, 9, 20, 64, 32, 7, 3, 1, (3, 1)),    # 7x3, no full band
+    (2, 12, 12, 264, 40, 1, 3, 1, (0, 1)),  # 1x3 over three slabs, few steps in the last
 ]
 
 
