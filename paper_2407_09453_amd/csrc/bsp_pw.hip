@@ -418,6 +418,12 @@ PwChoice pw_choose(int P, int I, int O, int nstrips, int pitch, bool windowed) {
     else
       break;
   }
+  // few pixel tiles and few strips (a narrow layer on a small image): measured, tiles of 32
+  // pixels, two workgroups or so per CU, beat tiles of 64 by about half a microsecond
+  if (c.PT == 4 && cdiv(P, 64) < 96 && nstrips <= 16) {
+    c.PT = 2;
+    c.NS = nstrips <= 8 ? nstrips : 4;
+  }
   const int64_t xb = (int64_t)16 * c.PT * pitch, ob = (int64_t)16 * c.PT * (c.NS * 32 + 16);
   c.wout = windowed && (c.NS % 4 == 0 || c.NS >= nstrips) && O >= I && xb + ob <= kLdsLimit;
   return c;
