@@ -164,8 +164,10 @@ enum bsp_kernel_family {
   BSP_KERNEL_PW = 16,   /* pointwise layers: all input channels of a pixel tile resident in LDS */
   BSP_KERNEL_BAND = 64, /* 3x3 stride-1 layers with at most 128 input channels and rows of at most
                            64 pixels: one workgroup per band of whole image rows */
-  BSP_KERNEL_CHAIN = 32 /* bsp_bottleneck only: run the fused chain even where the library
-                           expects the three layers one by one to be faster */
+  BSP_KERNEL_CHAIN = 32, /* bsp_bottleneck only: run the fused chain even where the library
+                            expects the three layers one by one to be faster */
+  BSP_KERNEL_FIRST = 128 /* layers with at most four input channels (a network's first layer):
+                            the whole window is the contraction */
 };
 
 /* Fully-connected layer Y[B][O] = X[B][I] . (Gamma W-bar)^T + bias, work done

@@ -20,6 +20,7 @@ BSP_I32 = 3
 BSP_KERNEL_ROWS, BSP_KERNEL_LDS, BSP_KERNEL_TILE, BSP_KERNEL_FC, BSP_KERNEL_PW = 1, 2, 4, 8, 16
 BSP_KERNEL_CHAIN = 32
 BSP_KERNEL_BAND = 64
+BSP_KERNEL_FIRST = 128
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libbsp.so")

@@ -120,6 +120,8 @@ int dispatch(const bsp_weights* w, const ConvParams& p, void* stream, const Fixe
                                    : (p.I >= 128 && p.I <= 512 && p.O >= 128 && p.P < 100000);
     if ((allow & BSP_KERNEL_ROWS) && (rows_pick || w->kernels)) rc = bsp_launch_rows(p, w->dtype, w->plan_host, st);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
+    if ((allow & BSP_KERNEL_FIRST) && p.I <= 4) rc = bsp_launch_first(p, w->dtype, w->plan_host, st);
+    if (rc != BSP_ERR_UNSUPPORTED) return rc;
     if (allow & BSP_KERNEL_LDS) rc = bsp_launch_lds(p, w->dtype, w->plan_host, st);
     if (rc != BSP_ERR_UNSUPPORTED) return rc;
     if (chunked && (allow & BSP_KERNEL_TILE)) rc = bsp_launch_tile(p, w->dtype, st);
@@ -220,6 +222,7 @@ int bsp_conv2d_only(const bsp_weights* w, const void* X, const float* bias, cons
     case BSP_KERNEL_PW: return bsp_launch_pw(p, w->dtype, w->plan_host, st);
     case BSP_KERNEL_BAND: return bsp_launch_band(p, w->dtype, w->plan_host, st);
     case BSP_KERNEL_LDS: return bsp_launch_lds(p, w->dtype, w->plan_host, st);
+    case BSP_KERNEL_FIRST: return bsp_launch_first(p, w->dtype, w->plan_host, st);
     case BSP_KERNEL_TILE: return chunked ? bsp_launch_tile(p, w->dtype, st) : BSP_ERR_UNSUPPORTED;
     case BSP_KERNEL_FC: {
       if (!chunked) return BSP_ERR_UNSUPPORTED;

@@ -15,6 +15,10 @@ bool bsp_rows_wanted(int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo, int
 int bsp_rows_section(const int32_t* row_ptr, const int32_t* col_idx, const uint16_t* payload,
                      int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo, int32_t bi,
                      std::vector<int32_t>* sec);
+bool bsp_first_wanted(int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo, int32_t bi, int32_t dtype);
+int bsp_first_section(const int32_t* row_ptr, const int32_t* col_idx, const uint16_t* payload,
+                      int32_t O, int32_t H, int32_t K, int32_t I, int32_t bo, int32_t bi,
+                      std::vector<int32_t>* sec);
 
 namespace {
 
@@ -469,7 +473,13 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, const void*
     if (int rc = bsp_rows_section(row_ptr, col_idx, out ? (const uint16_t*)payload : nullptr, O, H,
                                   K, I, bo, bi, &rows))
       return rc;
-  const int64_t total = off_rows + (int64_t)rows.size();
+  const int64_t off_first = (off_rows + (int64_t)rows.size() + 3) & ~int64_t(3);
+  std::vector<int32_t> first;
+  if (bsp_first_wanted(O, H, K, I, bo, bi, dtype))
+    if (int rc = bsp_first_section(row_ptr, col_idx, out ? (const uint16_t*)payload : nullptr, O, H,
+                                   K, I, bo, bi, &first))
+      return rc;
+  const int64_t total = first.empty() ? off_rows + (int64_t)rows.size() : off_first + (int64_t)first.size();
   if (total > std::numeric_limits<int32_t>::max()) return BSP_ERR_SHAPE;
   if (words_needed) *words_needed = total;
   if (!out) return BSP_OK;
@@ -502,6 +512,8 @@ static int plan_walk(const int32_t* row_ptr, const int32_t* col_idx, const void*
   out[BSP_PLAN_MAXSLABSTEPS_W] = steps_wanted ? max_slab_steps : 0;
   out[BSP_PLAN_OFF_ROWS_W] = rows.empty() ? 0 : (int32_t)off_rows;
   if (!rows.empty()) std::memcpy(out + off_rows, rows.data(), sizeof(int32_t) * rows.size());
+  out[BSP_PLAN_OFF_FIRST_W] = first.empty() ? 0 : (int32_t)off_first;
+  if (!first.empty()) std::memcpy(out + off_first, first.data(), sizeof(int32_t) * first.size());
   std::memcpy(out + off_strip, strip_ptr.data(), sizeof(int32_t) * strip_ptr.size());
   if (nchunks) {
     std::memcpy(out + off_xc, xc_list.data(), sizeof(int32_t) * xc_list.size());

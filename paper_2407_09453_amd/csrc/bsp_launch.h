@@ -37,6 +37,11 @@ int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipSt
 // pixels, strips x column tiles <= 16).  BSP_ERR_UNSUPPORTED = not applicable, nothing launched.
 int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);
 
+// Thin-input kernel (bf16, at most four input channels, windows up to 7x7, 32 or 64 output
+// channels; needs the plan's thin-input section and its host copy).  BSP_ERR_UNSUPPORTED = not
+// applicable, nothing launched.
+int bsp_launch_first(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);
+
 // Pointwise kernel (bf16, 1x1 windows without padding, any stride, all input channels in one
 // slab of the row-band section).  BSP_ERR_UNSUPPORTED = not applicable, nothing launched.
 int bsp_launch_pw(const ConvParams& p, int dtype, const void* plan_host, hipStream_t st);

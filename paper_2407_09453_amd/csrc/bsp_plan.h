@@ -46,7 +46,7 @@ enum {
   BSP_MAXSUB = 4,
   BSP_PLAN_HEADER_WORDS = 32,
   BSP_PLAN_MAGIC = 0x42535032,
-  BSP_PLAN_VERSION = 5,
+  BSP_PLAN_VERSION = 6,
 };
 
 enum {
@@ -75,6 +75,7 @@ enum {
   BSP_PLAN_MAXSTEPS_W = 22,   // most steps in any one strip
   BSP_PLAN_MAXSLABSTEPS_W = 23,  // most steps in any one (strip, slab)
   BSP_PLAN_OFF_ROWS_W = 24,   // first word of the row-band section, 0 when there is none
+  BSP_PLAN_OFF_FIRST_W = 25,  // first word of the thin-input section, 0 when there is none
 };
 
 // Row-band section (bf16 layers with whole 8-channel groups; read by bsp_rows.hip).
@@ -117,6 +118,24 @@ enum {
   BSP_ROWS_WINDOW_W = 14,         // strips per window of output channels (see bsp_rows_window), 0: none
   BSP_ROWS_ZEROS_W = 16,          // four zero words, 16-byte aligned: the source of padding pieces
   BSP_ROWS_MAXH = 7,
+};
+
+// Thin-input section (bf16 layers with at most four input channels, a network's first layer;
+// read by bsp_first.hip).  Such a layer has one block column, so its mask only drops whole
+// block rows; the contraction index k = (dy * K + dx) * I + i runs over the whole window,
+// 32 per step, and the O / 16 strips interleave the output channels so that a lane ends up
+// with 4 * NS consecutive channels of its pixel: row 4q + r of strip s is channel
+// q * 4 * NS + 4 * s + r.
+//   [0..7]                      header, see enum
+//   frag[steps][NS][64][8]      bf16 weights, lane 16g + j of (step t, strip s):
+//                               W[channel(s, j)][k = 32 t + 8 g + 0..7] or 0 (k past the window,
+//                               block row dropped)
+enum {
+  BSP_FIRST_HEADER_WORDS = 8,
+  BSP_FIRST_NS_W = 0,
+  BSP_FIRST_STEPS_W = 1,
+  BSP_FIRST_KT_W = 2,        // H * K * I
+  BSP_FIRST_OFF_FRAG_W = 3,  // in words from the section start
 };
 
 // Channels of one slab of the row-band section: windows are staged 128 channels at a time;
