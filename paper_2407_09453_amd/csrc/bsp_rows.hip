@@ -70,6 +70,7 @@ struct RowsArgs {
   FastDiv d_pcp, d_pr, d_np, d_br, d_nsg, d_tpi, d_tx, d_perimg, d_tw;
 #ifdef BSP_ROWS_TUNE
   long long* trace;
+  int nodma;  // experiments: 1 = the data movers request nothing (timing only, results wrong)
 #endif
 };
 
@@ -186,6 +187,24 @@ __device__ __forceinline__ void rows_stage(const RowsArgs& a, const TilePos& t, 
     const bool some_pad = __ballot(wanted && !col_real) != 0;
     uint32_t dst = buf + ((uint32_t)(wr * a.PCp + (gq << lppi)) << (a.lscp + 4));
     const uint32_t dst_step = (uint32_t)(nwr * a.PCp) << (a.lscp + 4);
+    if (!fill) {
+      // Later slabs (the data movers' work, and what bounds the layers with several slabs): the
+      // real pixels only, four rows per pass with no branch taken inside a pass.  A lane past
+      // the wave's last row holds kRowNone, which is no real row either.
+      for (int j = 0, row = wr; row < nrows; j += 4, row += 4 * nwr, dst += 4 * dst_step) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const uint32_t src = __builtin_amdgcn_readlane(rowsrc, j + u);  // (rows per wave <= 64: j + u <= 63)
+#ifdef BSP_ROWS_TUNE
+          if (a.nodma & 1) continue;
+#endif
+          if (src < kRowPad && col_real)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.X + src + col_off),
+                                             (__attribute__((address_space(3))) void*)(uintptr_t)(dst + u * dst_step), 16, 0, 0);
+        }
+      }
+      continue;
+    }
     for (int j = 0, row = wr; row < nrows; ++j, row += nwr, dst += dst_step) {
       const uint32_t src = __builtin_amdgcn_readlane(rowsrc, j);
       if (src == kRowNone) continue;
@@ -447,6 +466,9 @@ __global__ __launch_bounds__(640) __attribute__((amdgpu_waves_per_eu(H == 3 && N
             for (int j = 0; j < NT; ++j)
               acc[j][(k - dy) / S] = mfma_bf16_16x16x32(wr[d][dy], f[j][k], acc[j][(k - dy) / S]);
           }
+#ifdef BSP_ROWS_TUNE
+          if (a.nodma & 2) continue;  // experiments: the fragments are not read again (timing only)
+#endif
           if (row_needed<H, S, BR>(k)) {
 #pragma unroll
             for (int j = 0; j < NT; ++j) f[j][k] = rows_frag<CW4>(buf, nad[j], k * rowbytes);
@@ -882,6 +904,7 @@ int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipSt
   a.direct = 0;
 #ifdef BSP_ROWS_TUNE
   if (const char* e = std::getenv("BSP_PW_TRACE_PTR")) a.trace = (long long*)std::strtoull(e, nullptr, 16);
+  if (const char* e = std::getenv("BSP_ROWS_NODMA")) a.nodma = std::atoi(e);
 #endif
 #ifdef BSP_ROWS_TUNE
   if (std::getenv("BSP_ROWS_DIRECT")) a.direct = 1;
