@@ -473,7 +473,6 @@ __global__ __launch_bounds__(640) __attribute__((amdgpu_waves_per_eu(H == 3 && N
 #pragma unroll
             for (int j = 0; j < NT; ++j) f[j][k] = rows_frag<CW4>(buf, nad[j], k * rowbytes);
           }
-          __builtin_amdgcn_sched_barrier(0);
         }
         cs = nxt;
       }
