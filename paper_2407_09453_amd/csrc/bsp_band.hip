@@ -79,20 +79,37 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
   const int rowbytes = a.Jp * a.pitch;
 
   BAND_MARK(0);
-  // ---- copies: request rq = (patch row fr, group of ppr pixels)
+  // ---- copies: a request is 1 KiB = a group of ppr pixels of one patch row.  A wave keeps to
+  // one group of columns (everything that depends on the column is computed once) and walks
+  // down the rows, which costs a few scalar instructions per request; where there are more
+  // waves than groups the waves of a group share its rows.
   {
-    const int nreq = (BR + 2) * a.rpr;
     const int lpp = a.pitch >> 4;                 // 16-byte slots per pixel
     const int sp = lane / lpp, slot = lane - sp * lpp;
     const int pc0 = (a.pad && x0 == 0) ? 1 : 0;  // (with padding the first chunk's left halo column lies outside the image)
-    for (int rq = wave; rq < nreq; rq += nwaves) {
-      const int fr = (int)fdiv((uint32_t)rq, a.d_rpr), grp = rq - fr * a.rpr;
-      const int row = y0 - a.pad + fr, pc = pc0 + grp * a.ppr + sp, col = x0 - a.pad + pc;
-      const uint32_t piece = (uint32_t)slot ^ (((uint32_t)pc >> a.swz_shift) & (uint32_t)a.swz_mask);
-      if ((unsigned)row < (unsigned)a.L && pc < Jc + 2 && (unsigned)col < (unsigned)a.J && piece * 8u < (uint32_t)a.I)
-        __builtin_amdgcn_global_load_lds(
-            (gptr_t)(a.X + (((uint32_t)((n * a.L + row) * a.J + col)) * (uint32_t)a.I + piece * 8u) * 2u),
-            (lptr_t)(uintptr_t)(lds0 + (uint32_t)(fr * a.Jp + pc0 + grp * a.ppr) * (uint32_t)a.pitch), 16, 0, 0);
+    const int nwg = min(nwaves, a.rpr);           // waves side by side over the groups
+    int nwr = 1;                                  // waves of a group over its rows
+    while ((nwr + 1) * nwg <= nwaves) ++nwr;
+    int wg = wave, wr = 0;
+    while (wg >= nwg) {
+      wg -= nwg;
+      ++wr;
+    }
+    if (wr < nwr) {
+      for (int grp = wg; grp < a.rpr; grp += nwg) {
+        const int pc = pc0 + grp * a.ppr + sp, col = x0 - a.pad + pc;
+        const uint32_t piece = (uint32_t)slot ^ (((uint32_t)pc >> a.swz_shift) & (uint32_t)a.swz_mask);
+        const bool lane_ok = pc < Jc + 2 && (unsigned)col < (unsigned)a.J && piece * 8u < (uint32_t)a.I;
+        const uint32_t goff = ((uint32_t)col * (uint32_t)a.I + piece * 8u) * 2u;
+        const uint32_t ldst = lds0 + (uint32_t)(pc0 + grp * a.ppr) * (uint32_t)a.pitch;
+        const uint32_t grow = (uint32_t)a.J * (uint32_t)a.I * 2u;  // bytes of an image row
+        for (int fr = wr; fr < BR + 2; fr += nwr) {
+          const int row = y0 - a.pad + fr;
+          if ((unsigned)row < (unsigned)a.L && lane_ok)
+            __builtin_amdgcn_global_load_lds((gptr_t)(a.X + (uint32_t)(n * a.L + row) * grow + goff),
+                                             (lptr_t)(uintptr_t)(ldst + (uint32_t)(fr * rowbytes)), 16, 0, 0);
+        }
+      }
     }
   }
   BAND_MARK(1);
