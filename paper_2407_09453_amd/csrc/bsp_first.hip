@@ -32,8 +32,8 @@ struct FirstArgs {
   int32_t lpitch;  // bytes per staged row (a multiple of four)
   int32_t Kt;      // H * K * C
   int32_t rowel;   // J * C: elements of an image row
-  int32_t units;   // copy units per image row: dwords when rowel is even, else 16-bit elements
-  int32_t dwords;
+  int32_t units;   // copy units per image row
+  int32_t ub;      // bytes per copy unit: 16, 4 or 2, the largest that divides a row's bytes
   int32_t halo;    // 16-bit elements of a staged row outside the image
   FastDiv d_nbands, d_tx, d_units, d_kc, d_halo;
 };
@@ -52,32 +52,55 @@ __global__ __launch_bounds__(256) void conv_first(FirstArgs a) {
   const int y0 = band * a.BR, iy0 = y0 * a.S - a.ph;
   const int data0 = a.lead + a.pw * a.C * 2;  // where image column 0 lies in a staged row
 
-  // ---- the band's input rows, as they lie in memory
+  // ---- the band's input rows, as they lie in memory: 16 bytes per lane and load where a row's
+  // bytes are a multiple of 16, else dwords (an even number of elements) or 16-bit elements.
+  // Eight loads are in flight per lane before the first is written to LDS, and every lane
+  // loads, from a row that exists (a load under a condition would be waited for on the spot,
+  // one memory latency per load).
   {
     const int total = a.PR * a.units;
     const uint32_t img = (uint32_t)(n * a.L) * (uint32_t)a.rowel * 2u;
-    for (int i0 = tid; i0 < total; i0 += 4 * 256) {
-      uint32_t v[4];
-      int dst[4];
+    constexpr int NB = 8;
+    if (a.ub == 16) {
+      for (int i0 = tid; i0 < total; i0 += NB * 256) {
+        u32x4_t v[NB];
+        int dst[NB];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int idx = i0 + u * 256;
-        const int r = (int)fdiv((uint32_t)min(idx, total - 1), a.d_units), d = min(idx, total - 1) - r * a.units;
-        const int gy = iy0 + r;
-        const bool ok = idx < total && (unsigned)gy < (unsigned)a.L;
-        dst[u] = ok ? r * a.lpitch + data0 + d * (a.dwords ? 4 : 2) : -1;
-        // (every lane loads, from a row that exists: a load under a condition would be waited
-        // for on the spot, one memory latency per load)
-        const unsigned char* src = a.X + img + (uint32_t)min(max(gy, 0), a.L - 1) * (uint32_t)a.rowel * 2u;
-        v[u] = a.dwords ? *(const uint32_t*)(src + d * 4) : (uint32_t) * (const uint16_t*)(src + d * 2);
+        for (int u = 0; u < NB; ++u) {
+          const int idx = i0 + u * 256, ic = min(idx, total - 1);
+          const int r = (int)fdiv((uint32_t)ic, a.d_units), d = ic - r * a.units;
+          const int gy = iy0 + r;
+          dst[u] = idx < total && (unsigned)gy < (unsigned)a.L ? r * a.lpitch + data0 + d * 16 : -1;
+          v[u] = *(const u32x4_t*)(a.X + img + (uint32_t)min(max(gy, 0), a.L - 1) * (uint32_t)a.rowel * 2u + d * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+          if (dst[u] < 0) continue;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) *(uint32_t*)(lds + dst[u] + 4 * k) = v[u][k];  // (image column 0 is dword aligned in LDS, no more)
+        }
       }
+    } else {
+      for (int i0 = tid; i0 < total; i0 += NB * 256) {
+        uint32_t v[NB];
+        int dst[NB];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (dst[u] < 0) continue;
-        if (a.dwords)
-          *(uint32_t*)(lds + dst[u]) = v[u];
-        else
-          *(uint16_t*)(lds + dst[u]) = (uint16_t)v[u];
+        for (int u = 0; u < NB; ++u) {
+          const int idx = i0 + u * 256, ic = min(idx, total - 1);
+          const int r = (int)fdiv((uint32_t)ic, a.d_units), d = ic - r * a.units;
+          const int gy = iy0 + r;
+          dst[u] = idx < total && (unsigned)gy < (unsigned)a.L ? r * a.lpitch + data0 + d * a.ub : -1;
+          const unsigned char* src = a.X + img + (uint32_t)min(max(gy, 0), a.L - 1) * (uint32_t)a.rowel * 2u;
+          v[u] = a.ub == 4 ? *(const uint32_t*)(src + d * 4) : (uint32_t) * (const uint16_t*)(src + d * 2);
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+          if (dst[u] < 0) continue;
+          if (a.ub == 4)
+            *(uint32_t*)(lds + dst[u]) = v[u];
+          else
+            *(uint16_t*)(lds + dst[u]) = (uint16_t)v[u];
+        }
       }
     }
   }
@@ -240,7 +263,7 @@ int bsp_launch_first(const ConvParams& p, int dtype, const void* plan_host, hipS
   // halo rows, smaller ones give the chip more workgroups; a five-step layer holds its weights
   // in 80 registers, three workgroups per CU, and does best with few, large workgroups; a
   // one-step layer at stride 2 reads twice the rows it writes and does best with small ones)
-  a.BR = steps == 5 ? 8 : (p.sh > 1 ? 2 : 4);
+  a.BR = steps == 5 ? 7 : (p.sh > 1 ? 2 : 4);
 #ifdef BSP_ROWS_TUNE
   if (const char* e = getenv("BSP_FIRST_BR")) a.BR = atoi(e);
 #endif
@@ -249,8 +272,8 @@ int bsp_launch_first(const ConvParams& p, int dtype, const void* plan_host, hipS
   a.tiles_x = (p.N + 15) / 16;
   a.Kt = fs[BSP_FIRST_KT_W];
   a.rowel = p.J * p.I;
-  a.dwords = a.rowel % 2 == 0;
-  a.units = a.dwords ? a.rowel / 2 : a.rowel;
+  a.ub = a.rowel % 8 == 0 ? 16 : (a.rowel % 2 == 0 ? 4 : 2);
+  a.units = a.rowel * 2 / a.ub;
   a.lead = (4 - (p.pw * p.I * 2) % 4) % 4;
   // a staged row reaches as far as the last window does
   const int reach = std::max(p.J + 2 * p.pw, (p.N - 1) * a.S + p.K);
@@ -265,7 +288,7 @@ int bsp_launch_first(const ConvParams& p, int dtype, const void* plan_host, hipS
   a.d_halo = make_fastdiv((uint32_t)std::max(a.halo, 1));
   // multiply-high divisions are exact while dividend * divisor < 2^32
   const int64_t nwg = (int64_t)((p.B + 7) / 8) * a.nbands * 8;  // eight images at a time, one per XCD
-  if (nwg * a.nbands >= (1ll << 32) || nwg >= (1ll << 31) || (int64_t)(a.PR * a.units + 1024) * a.units >= (1ll << 32) ||
+  if (nwg * a.nbands >= (1ll << 32) || nwg >= (1ll << 31) || (int64_t)(a.PR * a.units + 2048) * a.units >= (1ll << 32) ||
       (int64_t)a.PR * a.halo * std::max(a.halo, 1) >= (1ll << 32))
     return BSP_ERR_UNSUPPORTED;
   dim3 grid((unsigned)nwg);
