@@ -278,10 +278,6 @@ int bsp_launch_first(const ConvParams& p, int dtype, const void* plan_host, hipS
   // a staged row reaches as far as the last window does
   const int reach = std::max(p.J + 2 * p.pw, (p.N - 1) * a.S + p.K);
   a.lpitch = (a.lead + reach * p.I * 2 + 3) & ~3;
-  // A step's four lane groups gather from up to three patch rows at once: with rows 56 banks
-  // (of 64) apart their runs of banks overlap least (measured over the pitch modulo 64 banks on
-  // the three networks' first layers: ResNet50's conv1 25.9 us at the natural pitch, 22.0 here).
-  while ((a.lpitch / 4) % 64 != 56) a.lpitch += 4;
   a.halo = (a.lpitch - a.rowel * 2) / 2;
   const int64_t ldsb = (int64_t)a.PR * a.lpitch;
   if (ldsb > 64 * 1024 || (int64_t)(p.H - 1) * a.lpitch + p.K * p.I * 2 >= 65536) return BSP_ERR_UNSUPPORTED;
