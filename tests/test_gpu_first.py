@@ -37,6 +37,9 @@ SHAPES = [
     (1, 11, 16, 4, 64, 3, 3, 1, 1),         # four channels: two steps, an instance that is not compiled (declined)
     (1, 5, 5, 3, 64, 7, 7, 1, 3),           # an image smaller than the window's reach
     (3, 4, 70, 3, 32, 7, 7, 2, 3),          # one band, several lane tiles, O = 32 with five steps
+    (1, 14, 19, 1, 32, 5, 5, 1, 2),         # 5x5 over one channel: 25 indices, one step
+    (2, 20, 23, 3, 64, 3, 3, 3, 1),         # stride 3
+    (1, 6, 300, 3, 64, 3, 3, 1, 1),         # rows longer than any image of the three networks
 ]
 
 
