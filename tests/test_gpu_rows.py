@@ -74,6 +74,23 @@ def test_rows_kernel_empty_block_rows():
     assert_close(_run_rows(c), oracle_conv(c), "bf16", "empty block rows")
 
 
+@pytest.mark.parametrize("H,K,p", [(3, 3, 1), (1, 7, (0, 3)), (7, 1, (3, 0))])
+def test_rows_kernel_empty_slabs(H, K, p):
+    """Strips with no step in a whole slab of input channels (the middle one, the last one, all
+    but one), block rows with nothing at all: the flat step sequence has to find each step's
+    slab and pass every slab's barrier all the same."""
+    c = draw_layer("rows", B=3, L=9, J=17, I=392, O=80, H=H, K=K, stride=1, pad=p,
+                   dtype="bf16", mask_kind="bernoulli", density=0.6, seed=8350 + H, b_std=0.5)
+    nbc = c.gamma.shape[1]            # 49 block columns: slabs of 16, 16, 16 and 1
+    c.gamma[0:4, 16:32] = 0           # no step in the second slab
+    c.gamma[4:6, 32:] = 0             # none in the last two
+    c.gamma[6, :] = 0
+    c.gamma[6, nbc - 1] = 1           # only the last slab's single block
+    c.gamma[7, :] = 0                 # an empty block row
+    c.gamma[8:10, 0:48] = 0           # only the last block column
+    assert_close(_run_rows(c), oracle_conv(c), "bf16", f"empty slabs {H}x{K}")
+
+
 def test_rows_kernel_fused_epilogue():
     import torch
     for (H, K, p) in ((3, 3, 1), (1, 3, (0, 1))):
