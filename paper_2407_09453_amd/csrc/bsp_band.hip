@@ -339,8 +339,12 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
   for (; ct >= 1; --ct) {
     a.cw = ct == ct_all ? p.N : 16 * ct;
     a.nchunks = (p.N + a.cw - 1) / a.cw;
-    // rows per band: seven unless that leaves CUs without a workgroup
+    // rows per band: seven unless that leaves CUs without a workgroup, or unless a workgroup
+    // has nine to twelve waves: three per SIMD, of which the seven-row instance (94 registers,
+    // five waves per SIMD) lets a CU hold one workgroup and the four-row instance (70 registers,
+    // seven waves) two (InceptionV3's 80 -> 192 layer at 73x73: 33 -> 29 us)
     BR = (int64_t)p.B * ((p.M + 6) / 7) * a.nchunks >= 200 ? 7 : 4;
+    if ((nstrips * ct + 3) / 4 == 3) BR = 4;
 #ifdef BSP_ROWS_TUNE
     if (const char* e = std::getenv("BSP_BAND_BR")) BR = std::atoi(e) == 4 ? 4 : 7;
 #endif
