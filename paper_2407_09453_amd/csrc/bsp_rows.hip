@@ -900,7 +900,11 @@ int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipSt
 
   RowsArgs a{};
   if (int rc = rows_fill_common(p, v, hdr, rs, gs, ch, geo, &a)) return rc;
-  a.direct = 0;
+  // Small outputs of one-row windows (at most 2 MB: InceptionV3's 1x7 and 1x3 layers) leave
+  // straight from the accumulators, 8 bytes per lane: no staging tile, no barrier (measured
+  // 0.3-0.5 us faster on each of them; the other window heights and larger outputs are as
+  // fast or faster as 16-byte pieces).
+  a.direct = p.H == 1 && (int64_t)p.P * p.O * 2 <= (2ll << 20);
 #ifdef BSP_ROWS_TUNE
   if (const char* e = std::getenv("BSP_PW_TRACE_PTR")) a.trace = (long long*)std::strtoull(e, nullptr, 16);
   if (const char* e = std::getenv("BSP_ROWS_NODMA")) a.nodma = std::atoi(e);
