@@ -54,13 +54,13 @@ __global__ __launch_bounds__(256) void conv_first(FirstArgs a) {
 
   // ---- the band's input rows, as they lie in memory: 16 bytes per lane and load where a row's
   // bytes are a multiple of 16, else dwords (an even number of elements) or 16-bit elements.
-  // Eight loads are in flight per lane before the first is written to LDS, and every lane
+  // Four loads are in flight per lane before the first is written to LDS, and every lane
   // loads, from a row that exists (a load under a condition would be waited for on the spot,
   // one memory latency per load).
   {
     const int total = a.PR * a.units;
     const uint32_t img = (uint32_t)(n * a.L) * (uint32_t)a.rowel * 2u;
-    constexpr int NB = 8;
+    constexpr int NB = 4;  // (eight was measured 0.8 us slower on 299-pixel rows and no faster elsewhere)
     if (a.ub == 16) {
       for (int i0 = tid; i0 < total; i0 += NB * 256) {
         u32x4_t v[NB];
