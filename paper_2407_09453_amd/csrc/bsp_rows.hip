@@ -875,6 +875,7 @@ int bsp_launch_rows(const ConvParams& p, int dtype, const void* plan_host, hipSt
   if ((int64_t)p.B * p.L * p.J * p.I * 2 >= (1ll << 31) || (int64_t)p.P * p.O * 2 >= (1ll << 31))
     return BSP_ERR_UNSUPPORTED;
   if (p.H == 1 && p.K == 1) return BSP_ERR_UNSUPPORTED;  // pointwise layers: bsp_pw.hip
+  if (p.H == 1 && p.sh != 1) return BSP_ERR_UNSUPPORTED;  // (one-row windows are compiled for stride 1 only)
   const int cw = rs[BSP_ROWS_CW_W];
   const int slab = rs[BSP_ROWS_SLAB_W];
   const int S = p.sh;   // staged pixels per output pixel step

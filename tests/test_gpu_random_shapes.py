@@ -46,6 +46,26 @@ def test_random_shapes_float(dtype):
         assert_close(gpu_conv(c), oracle_conv(c), dtype, f"random shape {n}")
 
 
+# (B, L, J, I, O, H, K, stride, pad, bo, bi): shapes that a wider random search once caught the
+# dispatcher on (one-row windows at stride 2 with at least 128 input and output channels)
+REGRESSIONS = [
+    (2, 8, 19, 264, 256, 1, 3, (2, 2), (0, 1), 16, 4),
+    (1, 6, 17, 512, 136, 1, 3, (2, 2), (0, 0), 8, 8),
+    (2, 6, 18, 128, 256, 1, 3, (2, 2), (0, 2), 16, 4),
+    (3, 23, 1, 264, 136, 1, 3, (2, 2), (0, 1), 8, 8),
+    (2, 9, 21, 256, 128, 1, 7, (2, 1), (0, 3), 8, 8),
+    (2, 21, 9, 256, 128, 7, 1, (1, 2), (3, 0), 8, 8),
+]
+
+
+def test_regression_shapes():
+    for n, (B, L, J, I, O, H, K, s, p, bo, bi) in enumerate(REGRESSIONS):
+        c = draw_layer("r", B=B, L=L, J=J, I=I, O=O, H=H, K=K, stride=s, pad=p, bo=bo, bi=bi,
+                       dtype="bf16", mask_kind="bernoulli", density=0.5, seed=6500 + n, b_std=0.5)
+        print("regression case", n, (B, L, J, I, O, H, K, s, p, bo, bi), flush=True)
+        assert_close(gpu_conv(c), oracle_conv(c), "bf16", f"regression shape {n}")
+
+
 def test_random_shapes_int8():
     import torch
     rng = np.random.default_rng(5)

@@ -118,6 +118,12 @@ def test_rows_kernel_declines_what_it_cannot_do():
     with pytest.raises(bsp.BspError) as e:
         _run_rows(c)
     assert e.value.code == -6
+    # one-row windows at stride 2 are not compiled (they were once run through the stride-1
+    # instance: wrong rows of the patch)
+    c = draw_layer("rows", B=2, L=8, J=19, I=264, O=256, H=1, K=3, stride=2, pad=(0, 1), dtype="bf16", seed=1)
+    with pytest.raises(bsp.BspError) as e:
+        _run_rows(c)
+    assert e.value.code == -6
     # pointwise layers belong to the pointwise kernel
     c = draw_layer("rows", B=2, L=14, J=14, I=64, O=64, H=1, K=1, stride=1, pad=0, dtype="bf16", seed=1)
     with pytest.raises(bsp.BspError) as e:
