@@ -19,6 +19,7 @@
 #include "bsp_tile.h"
 
 #include <algorithm>
+#include <cstdio>
 #include <cstdlib>
 
 namespace {
@@ -43,6 +44,7 @@ struct BandArgs {
   int32_t opitch;   // bytes per pixel of the output image
   int32_t llpp;     // log2 of the 16-byte slots per staged pixel
   FastDiv d_rpr, d_ctiles, d_cpp, d_nbands, d_nchunks, d_rowp;
+  int32_t stg_shift, stg_mask, stg_unit;
 #ifdef BSP_ROWS_TUNE
   long long* trace;
 #endif
@@ -63,6 +65,7 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 template <int BR, int D>
 __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
+  kernarg_touch<BandArgs>();
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nwaves = (int)(blockDim.x >> 6);
@@ -79,13 +82,26 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
   const int rowbytes = a.Jp * a.pitch;
 
   BAND_MARK(0);
+  for (int i = ((slot_wg >> a.stg_shift) & a.stg_mask) * a.stg_unit; i > 0; --i) __builtin_amdgcn_s_sleep(4);
+  // this wave's strip and column tile; its step range and channels are asked for here (scalar
+  // loads) and waited for after the copies have been issued
+  const int strip = (int)fdiv((uint32_t)wave, a.d_ctiles), ct = wave - strip * a.ctiles;
+  const bool active = strip < a.nstrips;
+  const int sq = active ? strip : 0;
+  u32x2_t lohi;
+  u32x4_t ch4;
+  {
+    const int32_t* ps = a.rslab + sq * 2;
+    const int32_t* pc = a.rstrip + sq * 4;
+    asm volatile("s_load_dwordx2 %0, %2, 0x0\n\ts_load_dwordx4 %1, %3, 0x0" : "=&s"(lohi), "=&s"(ch4) : "s"(ps), "s"(pc) : "memory");
+  }
   // ---- copies: a request is 1 KiB = a group of ppr pixels of one patch row.  A wave keeps to
   // one group of columns (everything that depends on the column is computed once) and walks
   // down the rows, which costs a few scalar instructions per request; where there are more
   // waves than groups the waves of a group share its rows.
   {
-    const int lpp = a.pitch >> 4;                 // 16-byte slots per pixel
-    const int sp = lane / lpp, slot = lane - sp * lpp;
+    const int lpp = a.pitch >> 4;                 // 16-byte slots per pixel (a power of two)
+    const int sp = lane >> a.llpp, slot = lane & (lpp - 1);
     const int pc0 = (a.pad && x0 == 0) ? 1 : 0;  // (with padding the first chunk's left halo column lies outside the image)
     const int nwg = min(nwaves, a.rpr);           // waves side by side over the groups
     int nwr = 1;                                  // waves of a group over its rows
@@ -103,12 +119,15 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
         const uint32_t goff = ((uint32_t)col * (uint32_t)a.I + piece * 8u) * 2u;
         const uint32_t ldst = lds0 + (uint32_t)(pc0 + grp * a.ppr) * (uint32_t)a.pitch;
         const uint32_t grow = (uint32_t)a.J * (uint32_t)a.I * 2u;  // bytes of an image row
-        for (int fr = wr; fr < BR + 2; fr += nwr) {
-          const int row = y0 - a.pad + fr;
-          if ((unsigned)row < (unsigned)a.L && lane_ok)
-            __builtin_amdgcn_global_load_lds((gptr_t)(a.X + (uint32_t)(n * a.L + row) * grow + goff),
-                                             (lptr_t)(uintptr_t)(ldst + (uint32_t)(fr * rowbytes)), 16, 0, 0);
-        }
+        if (!lane_ok) continue;  // (the lanes are masked once per group; a row outside the image is a scalar branch)
+        // (the byte offset stays a 32-bit number that wraps: the row above the first image is at
+        // "minus one row", and only the sum with the later steps is a real offset)
+        uint32_t src = (uint32_t)(n * a.L + y0 - a.pad + wr) * grow + goff;
+        const uint32_t sstep = (uint32_t)nwr * grow, dstep = (uint32_t)(nwr * rowbytes);
+        uint32_t dst = ldst + (uint32_t)(wr * rowbytes);
+        for (int row = y0 - a.pad + wr; row < y0 - a.pad + BR + 2; row += nwr, src += sstep, dst += dstep)
+          if ((unsigned)row < (unsigned)a.L)
+            __builtin_amdgcn_global_load_lds((gptr_t)(a.X + src), (lptr_t)(uintptr_t)dst, 16, 0, 0);
       }
     }
   }
@@ -133,21 +152,9 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
   }
 
   BAND_MARK(2);
-  // ---- this wave's strip and column tile; its step range and channels as scalar loads behind
-  // the copies
-  const int strip = (int)fdiv((uint32_t)wave, a.d_ctiles), ct = wave - strip * a.ctiles;
-  const bool active = strip < a.nstrips;
-  const int sq = active ? strip : 0;
-  u32x2_t lohi;
-  u32x4_t ch4;
-  {
-    const int32_t* ps = a.rslab + sq * 2;
-    const int32_t* pc = a.rstrip + sq * 4;
-    asm volatile("s_load_dwordx2 %0, %2, 0x0\n\ts_load_dwordx4 %1, %3, 0x0\n\ts_waitcnt lgkmcnt(0)"
-                 : "=&s"(lohi), "=&s"(ch4)
-                 : "s"(ps), "s"(pc)
-                 : "memory");
-  }
+  // ---- the step range and channels asked for at the top have to be there now (the registers
+  // pass through the wait, so that no use of them is moved above it)
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(lohi), "+s"(ch4) : : "memory");
   const int lo = (int)lohi.x, hi = active ? (int)lohi.y : lo;
   const int chan = !active ? -1 : g == 0 ? (int)ch4.x : g == 1 ? (int)ch4.y : g == 2 ? (int)ch4.z : (int)ch4.w;
 
@@ -311,6 +318,7 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
   BandArgs a{};
 #ifdef BSP_ROWS_TUNE
   if (const char* e = std::getenv("BSP_PW_TRACE_PTR")) a.trace = (long long*)std::strtoull(e, nullptr, 16);
+  if (const char* e = std::getenv("BSP_BAND_STG")) std::sscanf(e, "%d,%d,%d", &a.stg_shift, &a.stg_mask, &a.stg_unit);
 #endif
   const int raw = p.I * 2;
   a.pitch = raw <= 128 ? 128 : 256;

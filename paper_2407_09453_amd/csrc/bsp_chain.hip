@@ -74,6 +74,7 @@ constexpr int kComputeA = 12;  // compute waves of phase A; the other four move 
 
 template <int BR>
 __global__ __launch_bounds__(1024) void conv_chain(ChainArgs a) {
+  kernarg_touch<ChainArgs>();
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

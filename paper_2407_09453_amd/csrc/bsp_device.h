@@ -33,6 +33,48 @@ struct ConvParams {
   int32_t relu;          // act = max(., 0) when nonzero, identity otherwise
 };
 
+// A kernel's argument block lies in a few 64-byte lines of memory, and the compiler reads each
+// argument where the code first needs it, basic block by basic block: a first use of a new line
+// is a miss of the scalar cache, and a kernel's opening takes several of them one after the
+// other.  This asks for one word of every line of an argument block of type Args at once and
+// waits for all of them (the words go nowhere), so that what follows hits.  The first statement
+// of a kernel; nothing past the end of Args is read.
+template <typename Args>
+__device__ __forceinline__ void kernarg_touch() {
+  constexpr int kLines = (int)((sizeof(Args) + 63) / 64);
+  const auto* p = __builtin_amdgcn_kernarg_segment_ptr();
+  uint32_t t0, t1, t2, t3, t4, t5;
+  if constexpr (kLines >= 6)
+    asm volatile(
+        "s_load_dword %0, %6, 0x0\n\ts_load_dword %1, %6, 0x40\n\ts_load_dword %2, %6, 0x80\n\t"
+        "s_load_dword %3, %6, 0xc0\n\ts_load_dword %4, %6, 0x100\n\ts_load_dword %5, %6, 0x140\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4), "=&s"(t5)
+        : "s"(p)
+        : "memory");
+  else if constexpr (kLines == 5)
+    asm volatile(
+        "s_load_dword %0, %5, 0x0\n\ts_load_dword %1, %5, 0x40\n\ts_load_dword %2, %5, 0x80\n\t"
+        "s_load_dword %3, %5, 0xc0\n\ts_load_dword %4, %5, 0x100\n\ts_waitcnt lgkmcnt(0)"
+        : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4)
+        : "s"(p)
+        : "memory");
+  else if constexpr (kLines == 4)
+    asm volatile(
+        "s_load_dword %0, %4, 0x0\n\ts_load_dword %1, %4, 0x40\n\ts_load_dword %2, %4, 0x80\n\t"
+        "s_load_dword %3, %4, 0xc0\n\ts_waitcnt lgkmcnt(0)"
+        : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3)
+        : "s"(p)
+        : "memory");
+  else if constexpr (kLines == 3)
+    asm volatile(
+        "s_load_dword %0, %3, 0x0\n\ts_load_dword %1, %3, 0x40\n\ts_load_dword %2, %3, 0x80\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&s"(t0), "=&s"(t1), "=&s"(t2)
+        : "s"(p)
+        : "memory");
+}
+
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __float_as_uint(f);
   if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (uint16_t)((u >> 16) | 0x0040u);

@@ -30,6 +30,7 @@ struct FcTab {
 
 template <int BO, int BI, int NT, int kFcWaves>
 __global__ __launch_bounds__(kFcWaves * 64) void fc_stream_bf16(ConvParams p) {
+  kernarg_touch<ConvParams>();
   constexpr int U = NT <= 2 ? 4 : 2;  // MFMA steps whose loads are issued together
   __shared__ f32x4_t red[kFcWaves][NT][64];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -249,6 +250,7 @@ __device__ __forceinline__ int fcx_lower_bound(const int32_t* col, int a, int b,
 
 template <int NT>
 __global__ __launch_bounds__(1024) void fc_xlds_bf16(FcXArgs q) {
+  kernarg_touch<FcXArgs>();
   constexpr int R = 8;  // MFMA steps of weights in flight per wave
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63, jn = lane & 15, g = lane >> 4;

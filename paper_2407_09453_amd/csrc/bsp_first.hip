@@ -40,6 +40,7 @@ struct FirstArgs {
 
 template <int NS, int STEPS>
 __global__ __launch_bounds__(256) void conv_first(FirstArgs a) {
+  kernarg_touch<FirstArgs>();
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

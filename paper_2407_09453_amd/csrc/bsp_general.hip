@@ -24,6 +24,7 @@ struct Gran {
 
 template <int BO, int BI, int MT>
 __global__ __launch_bounds__(256) void conv_general_bf16(ConvParams p) {
+  kernarg_touch<ConvParams>();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int jn = lane & 15, g = lane >> 4;
   const int strip = blockIdx.y;
@@ -157,6 +158,7 @@ __global__ __launch_bounds__(256) void conv_general_bf16(ConvParams p) {
 
 template <int BO, int BI, int MT>
 __global__ __launch_bounds__(256) void conv_general_f32(ConvParams p) {
+  kernarg_touch<ConvParams>();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int jn = lane & 15, g = lane >> 4;
   const int strip = blockIdx.y;

@@ -31,6 +31,7 @@ struct I8Params {
 
 template <int BO, int BI, int MT>
 __global__ __launch_bounds__(256) void conv_general_i8(I8Params q) {
+  kernarg_touch<I8Params>();
   const ConvParams& p = q.p;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int jn = lane & 15, g = lane >> 4;

@@ -109,6 +109,12 @@ enum { kBf16 = 0, kBf16Narrow = 1, kInt8 = 2 };
 
 template <int NT, int KIND, bool RELOAD, bool FLAT>
 __global__ __launch_bounds__(kThreads, 1) void conv_lds(ConvParams p, TileCfg t, LdsCfg c) {
+  struct AllArgs {  // the argument block as the three arguments lie in it
+    ConvParams p;
+    TileCfg t;
+    LdsCfg c;
+  };
+  kernarg_touch<AllArgs>();
   constexpr bool NARROW = KIND == kBf16Narrow;
   // int8 codes: a chunk is sixteen channels, the MFMA is i32 16x16x64, sums are exact 32-bit
   // integers, the results are int8 after a rounding shift (c.shift).  The data movers see

@@ -63,6 +63,7 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 
 template <int PT, bool CW4, int D, int MAXT>
 __global__ __launch_bounds__(MAXT) void conv_pw(PwArgs a) {
+  kernarg_touch<PwArgs>();
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

@@ -298,6 +298,9 @@ __device__ __forceinline__ void rows_store_direct(const RowsArgs& a, const f32x4
 
 template <int H, int S, int BR, int NT, bool CW4, int D>
 __global__ __launch_bounds__(640) __attribute__((amdgpu_waves_per_eu(H == 3 && NT == 1 && (S == 1 || BR == 4) ? 4 : 3))) void conv_rows(RowsArgs a) {
+  // (not in the one-row-window instances: there it costs scalar registers the kernel does not
+  // have, and the spills cost more than the misses)
+  if constexpr (H != 1) kernarg_touch<RowsArgs>();
   constexpr int NF = (BR - 1) * S + H;
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x;

@@ -81,6 +81,7 @@ __global__ __launch_bounds__(256) void spgemm_zero(float* C, int64_t n) {
 
 template <int U>
 __global__ __launch_bounds__(512) void spgemm_nt_bf16(SpParams q) {
+  kernarg_touch<SpParams>();
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63, jn = lane & 15, g = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

@@ -89,6 +89,11 @@ __device__ __forceinline__ void run_steps(f32x4_t (&acc)[NT], Ring& r,
 
 template <int NT>
 __global__ __launch_bounds__(256, BSP_TILE_OCC) void conv_tile_bf16(ConvParams p, TileCfg t) {
+  struct AllArgs {  // the argument block as the two arguments lie in it
+    ConvParams p;
+    TileCfg t;
+  };
+  kernarg_touch<AllArgs>();
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
