@@ -1,6 +1,7 @@
 // 3x3 layers (stride 1, padding 1 or 0, bf16) whose input channels fit one slab of the row-band plan
-// section (at most 128): one workgroup per band of BR output rows x chunk of CW columns (all
-// columns when the rows are at most 64 pixels wide), all output channels.
+// section (at most 128): one workgroup per band of BR output rows x chunk of CW columns (as
+// many sixteen-column tiles as make a workgroup of four waves with the layer's strips, or the
+// whole row where that is narrower), all output channels.
 //
 // The band's input rows (one halo row above and below, one halo column left and right of the
 // chunk) are runs of whole pixels of image rows, so they are copied global -> LDS with no
@@ -13,13 +14,12 @@
 // uses patch row r + dy), weights streamed from the plan through a register ring as in the
 // row-band kernel.  The results of all strips are gathered in LDS as whole output lines (the
 // band's output is one contiguous range of Y) and leave 16 bytes per lane with the optional
-// residual and ReLU.  With 56-pixel rows and 64 channels that is 16 waves per workgroup and,
-// at batch 32, exactly one workgroup per CU.
+// residual and ReLU.  With 56-pixel rows and 64 channels the launcher makes chunks of sixteen
+// columns: four waves per workgroup and, at batch 32, four workgroups per CU.
 #include "bsp_launch.h"
 #include "bsp_tile.h"
 
 #include <algorithm>
-#include <cstdio>
 #include <cstdlib>
 
 namespace {
@@ -44,7 +44,6 @@ struct BandArgs {
   int32_t opitch;   // bytes per pixel of the output image
   int32_t llpp;     // log2 of the 16-byte slots per staged pixel
   FastDiv d_rpr, d_ctiles, d_cpp, d_nbands, d_nchunks, d_rowp;
-  int32_t stg_shift, stg_mask, stg_unit;
 #ifdef BSP_ROWS_TUNE
   long long* trace;
 #endif
@@ -82,7 +81,6 @@ __global__ __launch_bounds__(1024) void conv_band3(BandArgs a) {
   const int rowbytes = a.Jp * a.pitch;
 
   BAND_MARK(0);
-  for (int i = ((slot_wg >> a.stg_shift) & a.stg_mask) * a.stg_unit; i > 0; --i) __builtin_amdgcn_s_sleep(4);
   // this wave's strip and column tile; its step range and channels are asked for here (scalar
   // loads) and waited for after the copies have been issued
   const int strip = (int)fdiv((uint32_t)wave, a.d_ctiles), ct = wave - strip * a.ctiles;
@@ -318,7 +316,6 @@ int bsp_launch_band(const ConvParams& p, int dtype, const void* plan_host, hipSt
   BandArgs a{};
 #ifdef BSP_ROWS_TUNE
   if (const char* e = std::getenv("BSP_PW_TRACE_PTR")) a.trace = (long long*)std::strtoull(e, nullptr, 16);
-  if (const char* e = std::getenv("BSP_BAND_STG")) std::sscanf(e, "%d,%d,%d", &a.stg_shift, &a.stg_mask, &a.stg_unit);
 #endif
   const int raw = p.I * 2;
   a.pitch = raw <= 128 ? 128 : 256;
