@@ -78,6 +78,24 @@ __global__ __launch_bounds__(MAXT) void conv_pw(PwArgs a) {
   const int pix0 = mt * a.MT;
   PW_MARK(0);
 
+  // ---- this wave's strip and pixel group.  Its step range and output channels are wave-uniform:
+  // scalar loads, asked for here and waited for once the tile's copies are on their way (a
+  // vector load would have to queue behind those copies, and a wait here would delay them)
+  const int sidx = wave >> a.lpg, pg = wave & ((1 << a.lpg) - 1);
+  const int strip = ns * a.NS + sidx;
+  const bool active = sidx < a.NS && strip < a.nstrips;
+  const int sq = active ? strip : 0;
+  u32x2_t lohi;
+  u32x4_t ch4;
+  {
+    const int32_t* ps = a.rslab + sq * 2;
+    const int32_t* pc = a.rstrip + sq * 4;
+    asm volatile("s_load_dwordx2 %0, %2, 0x0\n\ts_load_dwordx4 %1, %3, 0x0"
+                 : "=&s"(lohi), "=&s"(ch4)
+                 : "s"(ps), "s"(pc)
+                 : "memory");
+  }
+
   // ---- stage the tile: request rq fills LDS bytes [rq * 1024, rq * 1024 + 1024)
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
   {
@@ -107,23 +125,9 @@ __global__ __launch_bounds__(MAXT) void conv_pw(PwArgs a) {
     }
   }
   PW_MARK(1);
-  // ---- this wave's strip and pixel group.  Its step range and output channels are wave-uniform:
-  // scalar loads, issued once the tile's copies are on their way (a vector load here would
-  // have to queue behind those copies, and a scalar load before them would delay them)
-  const int sidx = wave >> a.lpg, pg = wave & ((1 << a.lpg) - 1);
-  const int strip = ns * a.NS + sidx;
-  const bool active = sidx < a.NS && strip < a.nstrips;
-  const int sq = active ? strip : 0;
-  u32x2_t lohi;
-  u32x4_t ch4;
-  {
-    const int32_t* ps = a.rslab + sq * 2;
-    const int32_t* pc = a.rstrip + sq * 4;
-    asm volatile("s_load_dwordx2 %0, %2, 0x0\n\ts_load_dwordx4 %1, %3, 0x0\n\ts_waitcnt lgkmcnt(0)"
-                 : "=&s"(lohi), "=&s"(ch4)
-                 : "s"(ps), "s"(pc)
-                 : "memory");
-  }
+  // ---- the step range and channels asked for above have to be there now (the registers pass
+  // through the wait, so that no use of them is moved above it)
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(lohi), "+s"(ch4) : : "memory");
   PW_MARK(2);
   const int lo = (int)lohi.x, hi = active ? (int)lohi.y : lo;
   const int nsteps = hi - lo;
