@@ -66,9 +66,10 @@ def time_launches(launch, steps, warmup, dev, use_graph=True):
     """Average time of one step, ms: `steps` back-to-back calls of launch(i, stream) timed
     between synchronisations (wall clock) and with HIP events on the launch stream.  With
     use_graph the calls are captured once into a HIP graph on a side stream and the graph
-    is replayed: what remains between kernels is the GPU's own dispatch, not the Python loop."""
+    is replayed: what remains between kernels is the GPU's own dispatch, not the Python loop;
+    the `warmup` untimed steps are then whole replays (rounded up to a multiple of `steps`)."""
     import torch
-    for i in range(warmup):
+    for i in range(min(warmup, 20) if use_graph else warmup):
         launch(i, None)
     torch.cuda.synchronize()
     if use_graph:
@@ -79,7 +80,11 @@ def time_launches(launch, steps, warmup, dev, use_graph=True):
                 for i in range(steps):
                     launch(i, side.cuda_stream)
         torch.cuda.synchronize()
-        graph.replay()                      # one untimed replay
+        # the warm-up steps are replays of the same graph, right before the timed one: capturing
+        # takes the host milliseconds in which the GPU idles, and warm-up done before it is lost
+        # (the GPU reaches its sustained state only after tens of milliseconds under load)
+        for _ in range(max(1, -(-warmup // max(steps, 1)))):
+            graph.replay()
         torch.cuda.synchronize()
         run = graph.replay
     else:
@@ -495,7 +500,10 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=3000,
+                    help="untimed steps before the timed ones (default 3000, about 30 ms: the GPU "
+                         "reaches its sustained state only after tens of milliseconds under load; "
+                         "with 50 the same kernel reads 10-15 %% slower)")
     ap.add_argument("--workload", default="c1",
                     help="c1 (default), c0, c2:<bo>x<bi>.d<density>, c1_i8, spgemm, bottleneck, resnet50, vgg16, inception_v3, "
                          "or one layer of a stack as <net>:<layer name>")
