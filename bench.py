@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
 # rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE), each scaled by the same
 # counter's reading for a device copy of known size; the summary names the commit it was
 # taken at (profiles/conv_band3_bf16_c1.md)
-MEASURED_TRAFFIC = {"c1": {"bytes": 26_250_392, "commit": "51d7356"}}
+MEASURED_TRAFFIC = {"c1": {"bytes": 26_250_297, "commit": "4633f0f"}}
 
 
 def measured_peaks(dev):
