@@ -69,7 +69,9 @@ def time_launches(launch, steps, warmup, dev, use_graph=True):
     is replayed: what remains between kernels is the GPU's own dispatch, not the Python loop;
     the `warmup` untimed steps are then whole replays (rounded up to a multiple of `steps`)."""
     import torch
-    for i in range(min(warmup, 20) if use_graph else warmup):
+    # (at least one launch outside the capture: a kernel's first launch sets attributes that a
+    # capture does not record)
+    for i in range(max(1, min(warmup, 20)) if use_graph else warmup):
         launch(i, None)
     torch.cuda.synchronize()
     if use_graph:
